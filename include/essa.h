@@ -1,0 +1,218 @@
+/*
+ * essa.h -- C ABI of the MI355X (gfx950) hot path of ESSA (arXiv 2507.04453):
+ * the population-batched forward of SVD-parameterised LoRA attention projections on a shared
+ * quantised base weight, the seed-to-candidate sampler and the rank-weighted CMA-ES update.
+ *
+ * Conventions
+ *   - "DEVICE" pointers are HIP device memory on the context's GPU; "HOST" pointers are ordinary
+ *     host memory.  Nothing here takes framework types.
+ *   - All matrices are row-major and dense.  K = population size, r = LoRA rank, n = search
+ *     dimension, R = rows (candidate-tokens) of one forward call, P = number of adapted matrices.
+ *   - Ownership: the caller owns every buffer it passes, inputs and outputs alike; the library
+ *     owns only what a *_create call returns (its own repacked copies and scratch).
+ *   - Every hot-path call is asynchronous on the context's stream and allocates scratch only when
+ *     a larger problem than any before is seen.  Argument errors are found on the host before any
+ *     launch; no call aborts or throws.  On failure the return code is non-zero and
+ *     essa_last_error() describes it.
+ *   - One context per host thread.  Calls on one context are ordered by its stream.
+ */
+#ifndef ESSA_H
+#define ESSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct essa_ctx essa_ctx;    /* device, stream, scratch                                      */
+typedef struct essa_proj essa_proj;  /* one adapted projection: repacked W, V_A, V_B^T U_A, U_B, spectra */
+typedef struct essa_cma essa_cma;    /* search distribution (n, t, sigma, m, p_sigma, p_c, C, B, D)   */
+
+typedef enum {
+    ESSA_OK = 0,
+    ESSA_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad enum, floor(alpha r) = 0 ...        */
+    ESSA_ERR_SHAPE = 2,       /* sizes that do not fit each other or the format (d_in % 128 for int4) */
+    ESSA_ERR_UNSUPPORTED = 3, /* a valid request this build has no kernel for                         */
+    ESSA_ERR_OOM = 4,
+    ESSA_ERR_HIP = 5,         /* a HIP runtime call failed; the message carries hipGetErrorString     */
+    ESSA_ERR_STATE = 6        /* object used in the wrong state (blob of another n, ...)              */
+} essa_status;
+
+typedef enum { ESSA_F32 = 0, ESSA_BF16 = 1 } essa_dtype;
+
+typedef enum {
+    ESSA_QUANT_INT8_PERCH = 0, /* int8 symmetric, one fp32 scale per output channel                   */
+    ESSA_QUANT_INT4_G128 = 1   /* 4-bit asymmetric, groups of 128 input columns, fp16 scale and zero  */
+} essa_quant;
+
+/* flags of the forward calls */
+#define ESSA_COMPUTE_W8A8 0x1u /* int8 x int8 -> int32 MFMA on per-row quantised activations (int8 weights only) */
+#define ESSA_LORA_ONLY 0x2u    /* test hook: Y = B_k A_k x only                                       */
+#define ESSA_BASE_ONLY 0x4u    /* test hook: Y = W_deq x only                                         */
+
+/* ---------------------------------------------------------------------------------------------
+ * Context
+ * ------------------------------------------------------------------------------------------- */
+
+/* Creates a context on GPU `device`.  `hip_stream` is a hipStream_t the caller owns (borrowed for
+ * the context's lifetime); NULL means the default stream. */
+essa_status essa_create(essa_ctx** out, int device, void* hip_stream);
+void essa_destroy(essa_ctx* ctx);
+/* Message of the last failing call on this host thread; valid until the next failing call. */
+const char* essa_last_error(void);
+const char* essa_version(void);
+/* Blocks until everything queued on the context's stream has finished. */
+essa_status essa_synchronize(essa_ctx* ctx);
+
+/* ---------------------------------------------------------------------------------------------
+ * One adapted projection  (paper: Method, "LoRA + SVD parameterization"; Algorithm 1, SVD-init step)
+ *
+ * W0 (d_out x d_in) is the frozen quantised base weight and dW = B A its LoRA update with
+ * B (d_out x r), A (r x d_in).  Creation is the one-time set-up step: on the host, in fp64, it takes
+ * the thin SVDs A = U_A S_A V_A^T and B = U_B S_B V_B^T (singular values descending), forms the
+ * r x r core V_B^T U_A, repacks the weight for the kernels and uploads everything.  All pointers in
+ * the descriptor are HOST pointers and may be freed when the call returns.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct essa_proj_desc {
+    int32_t d_in, d_out, r;   /* 1 <= r <= 32, r <= min(d_in, d_out)                                  */
+    int32_t quant;            /* essa_quant                                                           */
+    const void* Wq;           /* INT8: int8 [d_out, d_in].  INT4: uint8 [d_out, d_in/2], column 2j in
+                                 the low nibble and 2j+1 in the high nibble of byte j, values 0..15   */
+    const void* scales;       /* INT8: float [d_out].  INT4: IEEE fp16 [d_out, d_in/128]              */
+    const void* zeros;        /* INT8: NULL.  INT4: IEEE fp16 [d_out, d_in/128], in quantised units:
+                                 W[o,j] = scale[o,g] * (q[o,j] - zero[o,g]), g = j / 128              */
+    const float* lora_A;      /* float [r, d_in]                                                      */
+    const float* lora_B;      /* float [d_out, r]                                                     */
+} essa_proj_desc;
+
+essa_status essa_proj_create(essa_ctx* ctx, const essa_proj_desc* desc, essa_proj** out);
+void essa_proj_destroy(essa_proj* proj);
+/* Copies the factors' own singular values S_A[r], S_B[r] (descending) to HOST arrays. */
+essa_status essa_proj_spectrum(const essa_proj* proj, float* sA_host, float* sB_host);
+
+/* ---------------------------------------------------------------------------------------------
+ * Search distribution  (paper: Method, "Evolutionary optimization": N(m, sigma^2 C))
+ *
+ * C = B D^2 B^T with orthonormal columns in B and axis lengths D.  A new object has C = B = I,
+ * D = 1, both evolution paths 0, t = 0.  The eigendecomposition that refreshes (B, D) from C is not
+ * part of this library: the caller supplies it through essa_cma_set_basis.
+ * ------------------------------------------------------------------------------------------- */
+essa_status essa_cma_create(essa_ctx* ctx, int n, float sigma0, const float* m0_host /* [n] or NULL = 0 */,
+                            essa_cma** out);
+void essa_cma_destroy(essa_cma* cma);
+/* B: DEVICE float [n, n] (column j = j-th axis), D: DEVICE float [n].  Copied. */
+essa_status essa_cma_set_basis(essa_cma* cma, const float* B_dev, const float* D_dev);
+/* Flat HOST blob holding the whole state: header {u32 magic, u32 version, i32 n, i32 t, f32 sigma,
+ * u32 reserved} then float m[n], p_sigma[n], p_c[n], D[n], C[n*n], B[n*n].  Export with blob = NULL
+ * only reports the size.  Both calls synchronise the stream.  Import needs a blob of the same n. */
+essa_status essa_cma_export(const essa_cma* cma, void* blob_host, size_t* bytes);
+essa_status essa_cma_import(essa_cma* cma, const void* blob_host, size_t bytes);
+
+/* ---------------------------------------------------------------------------------------------
+ * Hot path 1: seeds -> candidates  (paper: Method, "Evolutionary optimization"; Algorithm 1, the
+ * "sample candidate offsets from shared seeds" step; a seed is the 32-bit word workers exchange)
+ *
+ * For each of the K seeds: z = N(0,1)^n from Philox4x32-10 with key (seed, 0) and counter
+ * (c, 0, 0, 0), block c giving z[4c..4c+3] by Box-Muller on 24-bit uniforms
+ * (u = ((w >> 8) + 0.5) 2^-24; words (0,1) and (2,3) each give rho cos, rho sin); then
+ * theta = m + sigma * B (D * z).
+ *   seeds      DEVICE uint32 [K]
+ *   theta_out  DEVICE float [K, n]
+ *   z_out      DEVICE float [K, n] or NULL
+ * The same seed gives the same bits on every call.  K >= 1.
+ * ------------------------------------------------------------------------------------------- */
+essa_status essa_sample_candidates(essa_ctx* ctx, const essa_cma* cma, const uint32_t* seeds, int K,
+                                   float* theta_out, float* z_out);
+
+/* Test hook: the raw Philox blocks 0..n_blocks-1 of every seed.  words_out DEVICE uint32 [K, n_blocks, 4]. */
+essa_status essa_philox_words(essa_ctx* ctx, const uint32_t* seeds, int K, int n_blocks, uint32_t* words_out);
+
+/* ---------------------------------------------------------------------------------------------
+ * Hot path 2: theta -> singular values  (paper: Algorithm 1, reconstruction step, diag(sigma + delta);
+ * Figure 1: one contiguous slice of theta per LoRA matrix)
+ *
+ * theta[k] holds, for projection p = 0..P-1 in order, n_top offsets for factor A then n_top offsets
+ * for factor B (n = P * 2 * n_top, n_top = floor(alpha r) >= 1):
+ *   sigmaA[k,p,j] = sft_A[p,j] + theta[k, p*2*n_top + j]          for j < n_top, sft_A[p,j] beyond
+ *   sigmaB[k,p,j] = sft_B[p,j] + theta[k, p*2*n_top + n_top + j]  likewise
+ * All pointers DEVICE float: sft_A, sft_B [P, r]; theta [K, n]; sigmaA, sigmaB [K, P, r].
+ * ------------------------------------------------------------------------------------------- */
+essa_status essa_theta_to_sigma(essa_ctx* ctx, int P, int r, int n_top, const float* sft_A, const float* sft_B,
+                                const float* theta, int K, float* sigmaA, float* sigmaB);
+
+/* ---------------------------------------------------------------------------------------------
+ * Hot path 3: population-batched forward  (paper: Algorithm 1, reconstruction step
+ * W' = W + B' A' with A' = U_A diag(sigma_A) V_A^T, B' = U_B diag(sigma_B) V_B^T, and the inference
+ * pass that follows it)
+ *
+ * For every row i:  Y[i,:] = W_deq x_i + U_B ( sB_c * ( (V_B^T U_A) ( sA_c * (V_A^T x_i) ) ) ),
+ * c = row2cand[i] -- the candidate's dense W' is never formed.
+ *   X          DEVICE [R, d_in], x_dtype (bf16 = upper half of an fp32)
+ *   row2cand   DEVICE int32 [R], values in [0, K) (not checked on the device)
+ *   sigmaA/B   DEVICE float, candidate k's r values at sigmaX + k * sigma_stride (absolute singular
+ *              values, not offsets)
+ *   Y          DEVICE [R, d_out], y_dtype, written in full
+ * Arithmetic: bf16 X -> bf16 MFMA with fp32 accumulation, weights exact; fp32 X -> fp32 throughout.
+ * With ESSA_COMPUTE_W8A8 the base term uses x quantised per row (amax/127, round to nearest even)
+ * in an int8 MFMA with exact int32 accumulation; the LoRA term still sees the unquantised x.
+ * R = 0 is a no-op.
+ * ------------------------------------------------------------------------------------------- */
+essa_status essa_svdlora_forward(essa_ctx* ctx, const essa_proj* proj, const void* X, int x_dtype, int R,
+                                 const int32_t* row2cand, const float* sigmaA, const float* sigmaB,
+                                 int64_t sigma_stride, int K, void* Y, int y_dtype, uint32_t flags);
+
+/* The same for several projections in one launch sequence (q, k, v of a layer share X; o has its own). */
+typedef struct essa_fwd_item {
+    const essa_proj* proj;
+    const void* X;
+    const int32_t* row2cand;
+    const float* sigmaA;
+    const float* sigmaB;
+    void* Y;
+    int64_t sigma_stride;
+    int32_t R;
+    int32_t K;
+} essa_fwd_item;
+#define ESSA_MAX_GROUP 8
+essa_status essa_svdlora_forward_group(essa_ctx* ctx, const essa_fwd_item* items /* HOST */, int n_items,
+                                       int x_dtype, int y_dtype, uint32_t flags);
+
+/* Test hook of the W8A8 mode: per-row quantised activations and the raw int32 accumulators.
+ * xq_out DEVICE int8 [R, d_in], xscale_out DEVICE float [R], acc_out DEVICE int32 [R, d_out]. */
+essa_status essa_w8a8_accumulators(essa_ctx* ctx, const essa_proj* proj, const void* X, int x_dtype, int R,
+                                   int8_t* xq_out, float* xscale_out, int32_t* acc_out);
+
+/* ---------------------------------------------------------------------------------------------
+ * Hot path 4: synthetic reward  (stands in for Algorithm 1's "compute reward F" step, which needs a
+ * model and data):  F[k] += < mean of the rows of Y owned by candidate k , v >.
+ * A candidate without rows gets NaN.  Y DEVICE [R, d_out] y_dtype; v DEVICE float [d_out];
+ * F DEVICE float [K], accumulated into (zero it before the first call of a generation).
+ * ------------------------------------------------------------------------------------------- */
+essa_status essa_reward_accumulate(essa_ctx* ctx, const void* Y, int y_dtype, int R, int d_out, const float* v,
+                                   const int32_t* row2cand, int K, float* F);
+
+/* ---------------------------------------------------------------------------------------------
+ * Hot path 5: rank-weighted update  (paper: Algorithm 1, "each worker reconstructs the same
+ * population and performs one CMA-ES update of (m, sigma, C)"; a reward is the 32-bit scalar workers
+ * exchange)
+ *
+ * (mu/mu_w, lambda)-CMA-ES with lambda = K, mu = K/2, positive log weights and the default constants
+ * of Hansen's tutorial.  Candidates are ordered by reward, larger first; equal rewards keep ascending
+ * index; NaN counts as -infinity.  z_k is regenerated from seeds[k]; y_k = B (D * z_k).  Updates
+ * m, p_sigma, p_c, C, sigma and t in place on the device; (B, D) are left alone.  The result is
+ * bit-identical from run to run (fixed reduction order, no atomics).
+ *   seeds    DEVICE uint32 [K]     rewards  DEVICE float [K]     order_out  DEVICE int32 [K] or NULL
+ * K >= 2.
+ * ------------------------------------------------------------------------------------------- */
+essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uint32_t* seeds, const float* rewards, int K,
+                              int32_t* order_out);
+
+/* The ranking alone.  rewards DEVICE float [K] -> order DEVICE int32 [K]; 1 <= K <= 1024. */
+essa_status essa_rank_rewards(essa_ctx* ctx, const float* rewards, int K, int32_t* order);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESSA_H */

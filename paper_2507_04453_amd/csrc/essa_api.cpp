@@ -1,0 +1,523 @@
+// Host glue of libessa: argument checks, set-up (SVD, repacking, upload), scratch planning and
+// the launch sequences behind every extern "C" entry point declared in essa.h.
+#include <cmath>
+#include <cstring>
+#include <memory>
+
+#include "essa_internal.h"
+
+static thread_local std::string g_err;
+
+essa_status essa_fail(essa_status code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+extern "C" const char* essa_last_error(void) { return g_err.c_str(); }
+extern "C" const char* essa_version(void) { return "essa-mi355x 0.1 (gfx950)"; }
+
+// ---------------------------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------------------------
+extern "C" essa_status essa_create(essa_ctx** out, int device, void* hip_stream) {
+    if (!out) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_create: out is NULL");
+    *out = nullptr;
+    int count = 0;
+    ESSA_HIP(hipGetDeviceCount(&count));
+    if (device < 0 || device >= count)
+        return essa_fail(ESSA_ERR_INVALID_ARG, "essa_create: device %d out of range (%d visible)", device, count);
+    ESSA_HIP(hipSetDevice(device));
+    hipDeviceProp_t prop;
+    ESSA_HIP(hipGetDeviceProperties(&prop, device));
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return essa_fail(ESSA_ERR_UNSUPPORTED, "essa_create: kernels are built for gfx950, device is %s",
+                         prop.gcnArchName);
+    auto* c = new essa_ctx();
+    c->device = device;
+    c->stream = (hipStream_t)hip_stream;
+    *out = c;
+    return ESSA_OK;
+}
+
+extern "C" void essa_destroy(essa_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    delete ctx;
+}
+
+extern "C" essa_status essa_synchronize(essa_ctx* ctx) {
+    if (!ctx) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_synchronize: ctx is NULL");
+    ESSA_HIP(hipStreamSynchronize(ctx->stream));
+    return ESSA_OK;
+}
+
+essa_status essa_ws_reserve(essa_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->ws_bytes) return ESSA_OK;
+    ESSA_HIP(hipStreamSynchronize(ctx->stream));
+    if (ctx->ws) ESSA_HIP(hipFree(ctx->ws));
+    ctx->ws = nullptr;
+    ctx->ws_bytes = 0;
+    size_t want = bytes + bytes / 4 + (1u << 20);
+    hipError_t e = hipMalloc(&ctx->ws, want);
+    if (e != hipSuccess) return essa_fail(ESSA_ERR_OOM, "scratch of %zu bytes: %s", want, hipGetErrorString(e));
+    ctx->ws_bytes = want;
+    return ESSA_OK;
+}
+
+template <class T>
+static essa_status upload(T** dst, const T* src, size_t count) {
+    *dst = nullptr;
+    hipError_t e = hipMalloc((void**)dst, count * sizeof(T) + 256);   // slack: kernels may over-read a vector
+    if (e != hipSuccess) return essa_fail(ESSA_ERR_OOM, "hipMalloc of %zu bytes: %s", count * sizeof(T), hipGetErrorString(e));
+    ESSA_HIP(hipMemset(*dst, 0, count * sizeof(T) + 256));
+    ESSA_HIP(hipMemcpy(*dst, src, count * sizeof(T), hipMemcpyHostToDevice));
+    return ESSA_OK;
+}
+
+static uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+static float f16_to_f32(uint16_t h) {
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16, exp = (h >> 10) & 0x1f, man = h & 0x3ffu, u;
+    if (exp == 0) {
+        if (man == 0) u = sign;
+        else {
+            int e = -1;
+            do { man <<= 1; ++e; } while (!(man & 0x400u));
+            u = sign | ((uint32_t)(127 - 15 - e) << 23) | ((man & 0x3ffu) << 13);
+        }
+    } else if (exp == 31) u = sign | 0x7f800000u | (man << 13);
+    else u = sign | ((exp + 112) << 23) | (man << 13);
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// projection set-up
+// ---------------------------------------------------------------------------------------------
+extern "C" void essa_proj_destroy(essa_proj* p) {
+    if (!p) return;
+    (void)hipSetDevice(p->device);
+    (void)hipDeviceSynchronize();
+    void* ptrs[] = {p->Wq, p->scale, p->zero, p->VA32, p->VA16, p->UB32, p->UB16, p->M};
+    for (void* q : ptrs)
+        if (q) (void)hipFree(q);
+    delete p;
+}
+
+extern "C" essa_status essa_proj_create(essa_ctx* ctx, const essa_proj_desc* d, essa_proj** out) {
+    if (!ctx || !d || !out) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_proj_create: NULL argument");
+    *out = nullptr;
+    if (!d->Wq || !d->scales || !d->lora_A || !d->lora_B)
+        return essa_fail(ESSA_ERR_INVALID_ARG, "essa_proj_create: NULL tensor in descriptor");
+    if (d->d_in <= 0 || d->d_out <= 0) return essa_fail(ESSA_ERR_SHAPE, "essa_proj_create: d_in=%d d_out=%d", d->d_in, d->d_out);
+    if (d->r < 1 || d->r > 32 || d->r > d->d_in || d->r > d->d_out)
+        return essa_fail(ESSA_ERR_SHAPE, "essa_proj_create: rank %d not in [1, min(32, d_in, d_out)]", d->r);
+    if (d->quant != ESSA_QUANT_INT8_PERCH && d->quant != ESSA_QUANT_INT4_G128)
+        return essa_fail(ESSA_ERR_INVALID_ARG, "essa_proj_create: unknown quant %d", d->quant);
+    if (d->quant == ESSA_QUANT_INT4_G128) {
+        if (d->d_in % 128 != 0) return essa_fail(ESSA_ERR_SHAPE, "essa_proj_create: int4 needs d_in %% 128 == 0, got %d", d->d_in);
+        if (!d->zeros) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_proj_create: int4 needs zeros");
+    }
+    ESSA_HIP(hipSetDevice(ctx->device));
+    std::unique_ptr<essa_proj, void (*)(essa_proj*)> p(new essa_proj(), essa_proj_destroy);
+    p->ctx = ctx;
+    p->device = ctx->device;
+    p->stream = ctx->stream;
+    p->d_in = d->d_in;
+    p->d_out = d->d_out;
+    p->r = d->r;
+    p->rp = d->r <= 16 ? 16 : 32;
+    p->quant = d->quant;
+    const int r = d->r, rp = p->rp, din = d->d_in, dout = d->d_out;
+
+    // thin SVDs in fp64.  A is r x d_in: decompose A^T (d_in x r) = V_A S U_A^T.
+    std::vector<double> At((size_t)din * r), VA((size_t)din * r), sA(r), UA((size_t)r * r);
+    for (int j = 0; j < r; ++j)
+        for (int i = 0; i < din; ++i) At[(size_t)i * r + j] = d->lora_A[(size_t)j * din + i];
+    essa_host_thin_svd(At.data(), din, r, VA.data(), sA.data(), UA.data());
+    std::vector<double> Bd((size_t)dout * r), UB((size_t)dout * r), sB(r), VB((size_t)r * r);
+    for (size_t i = 0; i < Bd.size(); ++i) Bd[i] = d->lora_B[i];
+    essa_host_thin_svd(Bd.data(), dout, r, UB.data(), sB.data(), VB.data());
+    p->sA.assign(sA.begin(), sA.end());
+    p->sB.assign(sB.begin(), sB.end());
+
+    std::vector<float> M((size_t)rp * rp, 0.f), VA32((size_t)din * rp, 0.f), UB32((size_t)dout * rp, 0.f);
+    std::vector<uint16_t> VA16((size_t)rp * din, 0), UB16((size_t)dout * 2 * rp, 0);
+    for (int b = 0; b < r; ++b)
+        for (int a = 0; a < r; ++a) {
+            double acc = 0;
+            for (int t = 0; t < r; ++t) acc += VB[(size_t)t * r + b] * UA[(size_t)t * r + a];
+            M[(size_t)b * rp + a] = (float)acc;
+        }
+    for (int i = 0; i < din; ++i)
+        for (int j = 0; j < r; ++j) {
+            float v = (float)VA[(size_t)i * r + j];
+            VA32[(size_t)i * rp + j] = v;
+            VA16[(size_t)j * din + i] = f32_to_bf16_rne(v);
+        }
+    for (int o = 0; o < dout; ++o)
+        for (int j = 0; j < r; ++j) {
+            float v = (float)UB[(size_t)o * r + j];
+            UB32[(size_t)o * rp + j] = v;
+            const uint16_t hi = f32_to_bf16_rne(v);   // bf16 head and tail, v = hi + lo
+            uint32_t hb = (uint32_t)hi << 16;
+            float hf;
+            std::memcpy(&hf, &hb, 4);
+            UB16[(size_t)o * 2 * rp + j] = hi;
+            UB16[(size_t)o * 2 * rp + rp + j] = f32_to_bf16_rne(v - hf);
+        }
+    ESSA_TRY(upload(&p->M, M.data(), M.size()));
+    ESSA_TRY(upload(&p->VA32, VA32.data(), VA32.size()));
+    ESSA_TRY(upload(&p->VA16, VA16.data(), VA16.size()));
+    ESSA_TRY(upload(&p->UB32, UB32.data(), UB32.size()));
+    ESSA_TRY(upload(&p->UB16, UB16.data(), UB16.size()));
+
+    if (d->quant == ESSA_QUANT_INT8_PERCH) {
+        int8_t* w = nullptr;
+        ESSA_TRY(upload(&w, (const int8_t*)d->Wq, (size_t)dout * din));
+        p->Wq = w;
+        ESSA_TRY(upload(&p->scale, (const float*)d->scales, (size_t)dout));
+    } else {
+        p->groups = din / 128;
+        uint8_t* w = nullptr;
+        ESSA_TRY(upload(&w, (const uint8_t*)d->Wq, (size_t)dout * din / 2));
+        p->Wq = w;
+        size_t ng = (size_t)dout * p->groups;
+        std::vector<float> s(ng), z(ng);
+        const uint16_t* sh = (const uint16_t*)d->scales;
+        const uint16_t* zh = (const uint16_t*)d->zeros;
+        for (size_t i = 0; i < ng; ++i) { s[i] = f16_to_f32(sh[i]); z[i] = f16_to_f32(zh[i]); }
+        ESSA_TRY(upload(&p->scale, s.data(), ng));
+        ESSA_TRY(upload(&p->zero, z.data(), ng));
+    }
+    *out = p.release();
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_proj_spectrum(const essa_proj* p, float* sA_host, float* sB_host) {
+    if (!p || !sA_host || !sB_host) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_proj_spectrum: NULL argument");
+    std::memcpy(sA_host, p->sA.data(), p->r * sizeof(float));
+    std::memcpy(sB_host, p->sB.data(), p->r * sizeof(float));
+    return ESSA_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// search distribution
+// ---------------------------------------------------------------------------------------------
+struct cma_blob_header {
+    uint32_t magic, version;
+    int32_t n, t;
+    float sigma;
+    uint32_t reserved;
+};
+static const uint32_t kCmaMagic = 0x41535345u;  // "ESSA"
+
+extern "C" void essa_cma_destroy(essa_cma* c) {
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    (void)hipDeviceSynchronize();
+    void* ptrs[] = {c->m, c->p_sigma, c->p_c, c->D, c->C, c->B, c->sc, c->weights};
+    for (void* q : ptrs)
+        if (q) (void)hipFree(q);
+    delete c;
+}
+
+extern "C" essa_status essa_cma_create(essa_ctx* ctx, int n, float sigma0, const float* m0_host, essa_cma** out) {
+    if (!ctx || !out) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_create: NULL argument");
+    *out = nullptr;
+    if (n < 1 || n > 16384) return essa_fail(ESSA_ERR_SHAPE, "essa_cma_create: n=%d not in [1, 16384]", n);
+    if (!(sigma0 > 0.f) || !std::isfinite(sigma0)) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_create: sigma0 must be positive and finite");
+    ESSA_HIP(hipSetDevice(ctx->device));
+    std::unique_ptr<essa_cma, void (*)(essa_cma*)> c(new essa_cma(), essa_cma_destroy);
+    c->ctx = ctx;
+    c->device = ctx->device;
+    c->stream = ctx->stream;
+    c->n = n;
+    std::vector<float> zeros((size_t)n, 0.f), ones((size_t)n, 1.f), eye((size_t)n * n, 0.f);
+    for (int i = 0; i < n; ++i) eye[(size_t)i * n + i] = 1.f;
+    ESSA_TRY(upload(&c->m, m0_host ? m0_host : zeros.data(), (size_t)n));
+    ESSA_TRY(upload(&c->p_sigma, zeros.data(), (size_t)n));
+    ESSA_TRY(upload(&c->p_c, zeros.data(), (size_t)n));
+    ESSA_TRY(upload(&c->D, ones.data(), (size_t)n));
+    ESSA_TRY(upload(&c->C, eye.data(), eye.size()));
+    ESSA_TRY(upload(&c->B, eye.data(), eye.size()));
+    essa_cma_scalars sc{sigma0, 0, 1.f, 0.f};
+    ESSA_TRY(upload(&c->sc, &sc, 1));
+    *out = c.release();
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_cma_set_basis(essa_cma* c, const float* B_dev, const float* D_dev) {
+    if (!c || !B_dev || !D_dev) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_set_basis: NULL argument");
+    ESSA_HIP(hipSetDevice(c->device));
+    ESSA_HIP(hipMemcpyAsync(c->B, B_dev, (size_t)c->n * c->n * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+    ESSA_HIP(hipMemcpyAsync(c->D, D_dev, (size_t)c->n * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_cma_export(const essa_cma* c, void* blob, size_t* bytes) {
+    if (!c || !bytes) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_export: NULL argument");
+    const size_t n = c->n, need = sizeof(cma_blob_header) + (4 * n + 2 * n * n) * sizeof(float);
+    if (!blob) { *bytes = need; return ESSA_OK; }
+    if (*bytes < need) { *bytes = need; return essa_fail(ESSA_ERR_SHAPE, "essa_cma_export: blob too small, need %zu bytes", need); }
+    ESSA_HIP(hipSetDevice(c->device));
+    ESSA_HIP(hipStreamSynchronize(c->stream));
+    essa_cma_scalars sc;
+    ESSA_HIP(hipMemcpy(&sc, c->sc, sizeof sc, hipMemcpyDeviceToHost));
+    cma_blob_header h{kCmaMagic, 1u, (int32_t)n, sc.t, sc.sigma, 0u};
+    char* dst = (char*)blob;
+    std::memcpy(dst, &h, sizeof h);
+    dst += sizeof h;
+    const float* vecs[] = {c->m, c->p_sigma, c->p_c, c->D};
+    for (const float* v : vecs) { ESSA_HIP(hipMemcpy(dst, v, n * sizeof(float), hipMemcpyDeviceToHost)); dst += n * sizeof(float); }
+    ESSA_HIP(hipMemcpy(dst, c->C, n * n * sizeof(float), hipMemcpyDeviceToHost));
+    dst += n * n * sizeof(float);
+    ESSA_HIP(hipMemcpy(dst, c->B, n * n * sizeof(float), hipMemcpyDeviceToHost));
+    *bytes = need;
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_cma_import(essa_cma* c, const void* blob, size_t bytes) {
+    if (!c || !blob) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_import: NULL argument");
+    const size_t n = c->n, need = sizeof(cma_blob_header) + (4 * n + 2 * n * n) * sizeof(float);
+    if (bytes < sizeof(cma_blob_header)) return essa_fail(ESSA_ERR_SHAPE, "essa_cma_import: blob shorter than its header");
+    cma_blob_header h;
+    std::memcpy(&h, blob, sizeof h);
+    if (h.magic != kCmaMagic || h.version != 1u) return essa_fail(ESSA_ERR_STATE, "essa_cma_import: not a state blob of this library");
+    if ((size_t)h.n != n || bytes != need) return essa_fail(ESSA_ERR_STATE, "essa_cma_import: blob holds n=%d (%zu bytes), object has n=%zu (%zu bytes)", h.n, bytes, n, need);
+    if (!(h.sigma > 0.f) || h.t < 0) return essa_fail(ESSA_ERR_STATE, "essa_cma_import: sigma=%g t=%d", h.sigma, h.t);
+    ESSA_HIP(hipSetDevice(c->device));
+    ESSA_HIP(hipStreamSynchronize(c->stream));
+    essa_cma_scalars sc{h.sigma, h.t, 1.f, 0.f};
+    ESSA_HIP(hipMemcpy(c->sc, &sc, sizeof sc, hipMemcpyHostToDevice));
+    const char* src = (const char*)blob + sizeof h;
+    float* vecs[] = {c->m, c->p_sigma, c->p_c, c->D};
+    for (float* v : vecs) { ESSA_HIP(hipMemcpy(v, src, n * sizeof(float), hipMemcpyHostToDevice)); src += n * sizeof(float); }
+    ESSA_HIP(hipMemcpy(c->C, src, n * n * sizeof(float), hipMemcpyHostToDevice));
+    src += n * n * sizeof(float);
+    ESSA_HIP(hipMemcpy(c->B, src, n * n * sizeof(float), hipMemcpyHostToDevice));
+    return ESSA_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// hot path: sampling and theta -> sigma
+// ---------------------------------------------------------------------------------------------
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+extern "C" essa_status essa_philox_words(essa_ctx* ctx, const uint32_t* seeds, int K, int n_blocks, uint32_t* words_out) {
+    if (!ctx || !seeds || !words_out) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_philox_words: NULL argument");
+    if (K < 1 || n_blocks < 1) return essa_fail(ESSA_ERR_SHAPE, "essa_philox_words: K=%d n_blocks=%d", K, n_blocks);
+    ESSA_HIP(hipSetDevice(ctx->device));
+    ESSA_HIP(essa_k::philox_words(ctx->stream, seeds, K, n_blocks, words_out));
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_sample_candidates(essa_ctx* ctx, const essa_cma* cma, const uint32_t* seeds, int K,
+                                              float* theta_out, float* z_out) {
+    if (!ctx || !cma || !seeds || !theta_out) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_sample_candidates: NULL argument");
+    if (K < 1 || K > 65536) return essa_fail(ESSA_ERR_SHAPE, "essa_sample_candidates: K=%d not in [1, 65536]", K);
+    if (cma->ctx != ctx) return essa_fail(ESSA_ERR_STATE, "essa_sample_candidates: state belongs to another context");
+    ESSA_HIP(hipSetDevice(ctx->device));
+    const int n = cma->n;
+    ESSA_TRY(essa_ws_reserve(ctx, align256((size_t)K * n * sizeof(float))));
+    float* S = (float*)ctx->ws;
+    ESSA_HIP(essa_k::normals_scaled(ctx->stream, seeds, nullptr, K, n, cma->D, S, z_out));
+    ESSA_HIP(essa_k::skinny_gemm_nt(ctx->stream, S, K, cma->B, n, cma->m, cma->sc, 1, theta_out));
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_theta_to_sigma(essa_ctx* ctx, int P, int r, int n_top, const float* sft_A, const float* sft_B,
+                                           const float* theta, int K, float* sigmaA, float* sigmaB) {
+    if (!ctx || !sft_A || !sft_B || !theta || !sigmaA || !sigmaB) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_theta_to_sigma: NULL argument");
+    if (n_top < 1) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_theta_to_sigma: floor(alpha r) = %d leaves no trainable singular value", n_top);
+    if (P < 1 || r < 1 || n_top > r || K < 1) return essa_fail(ESSA_ERR_SHAPE, "essa_theta_to_sigma: P=%d r=%d n_top=%d K=%d", P, r, n_top, K);
+    ESSA_HIP(hipSetDevice(ctx->device));
+    ESSA_HIP(essa_k::theta_to_sigma(ctx->stream, P, r, n_top, sft_A, sft_B, theta, K, sigmaA, sigmaB));
+    return ESSA_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// hot path: forward
+// ---------------------------------------------------------------------------------------------
+static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_items, int x_dtype, int y_dtype,
+                              unsigned flags, std::vector<essa_k::fwd_item>& out, const char* who) {
+    if (x_dtype != ESSA_F32 && x_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: x_dtype %d", who, x_dtype);
+    if (y_dtype != ESSA_F32 && y_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: y_dtype %d", who, y_dtype);
+    if (flags & ~(ESSA_COMPUTE_W8A8 | ESSA_LORA_ONLY | ESSA_BASE_ONLY)) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: unknown flag bits 0x%x", who, flags);
+    if ((flags & ESSA_LORA_ONLY) && (flags & ESSA_BASE_ONLY)) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: LORA_ONLY and BASE_ONLY exclude each other", who);
+    size_t total = 0;
+    out.clear();
+    for (int i = 0; i < n_items; ++i) {
+        const essa_fwd_item& it = items[i];
+        if (!it.proj) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: item %d has no projection", who, i);
+        if (it.proj->ctx != ctx) return essa_fail(ESSA_ERR_STATE, "%s: item %d belongs to another context", who, i);
+        if (it.R < 0 || it.K < 1) return essa_fail(ESSA_ERR_SHAPE, "%s: item %d has R=%d K=%d", who, i, it.R, it.K);
+        if (it.R > 0 && (!it.X || !it.row2cand || !it.sigmaA || !it.sigmaB || !it.Y))
+            return essa_fail(ESSA_ERR_INVALID_ARG, "%s: item %d has a NULL tensor", who, i);
+        if (it.sigma_stride < it.proj->r && it.K > 1)
+            return essa_fail(ESSA_ERR_SHAPE, "%s: item %d sigma_stride %lld < r", who, i, (long long)it.sigma_stride);
+        const essa_proj* p = it.proj;
+        if ((flags & ESSA_COMPUTE_W8A8) && p->quant != ESSA_QUANT_INT8_PERCH)
+            return essa_fail(ESSA_ERR_UNSUPPORTED, "%s: W8A8 needs int8 weights (item %d)", who, i);
+        if ((flags & ESSA_COMPUTE_W8A8) && x_dtype != ESSA_BF16)
+            return essa_fail(ESSA_ERR_UNSUPPORTED, "%s: W8A8 takes bf16 activations", who);
+        if (it.R == 0) continue;
+        essa_k::fwd_item k{};
+        k.X = it.X; k.row2cand = it.row2cand; k.sigmaA = it.sigmaA; k.sigmaB = it.sigmaB; k.Y = it.Y;
+        k.sigma_stride = it.sigma_stride; k.R = it.R; k.K = it.K;
+        k.d_in = p->d_in; k.d_out = p->d_out; k.r = p->r; k.rp = p->rp; k.quant = p->quant; k.groups = p->groups;
+        k.Wq = p->Wq; k.scale = p->scale; k.zero = p->zero; k.VA32 = p->VA32; k.VA16 = p->VA16;
+        k.UB32 = p->UB32; k.UB16 = p->UB16; k.M = p->M;
+        out.push_back(k);
+        const size_t R = it.R;
+        total += align256(R * p->rp * 4) + align256(R * p->rp * 4) + align256(R * (p->groups > 0 ? p->groups : 1) * 4);
+        if (flags & ESSA_COMPUTE_W8A8) total += align256(R * (size_t)p->d_in) + align256(R * 4);
+    }
+    ESSA_TRY(essa_ws_reserve(ctx, total));
+    char* w = (char*)ctx->ws;
+    for (auto& k : out) {
+        const size_t R = k.R;
+        k.U32 = (float*)w; w += align256(R * k.rp * 4);
+        k.U16 = (uint16_t*)w; w += align256(R * k.rp * 4);
+        k.xsum = (float*)w; w += align256(R * (k.groups > 0 ? k.groups : 1) * 4);
+        if (flags & ESSA_COMPUTE_W8A8) {
+            k.Xq = (int8_t*)w; w += align256(R * (size_t)k.d_in);
+            k.xscale = (float*)w; w += align256(R * 4);
+        }
+    }
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_svdlora_forward_group(essa_ctx* ctx, const essa_fwd_item* items, int n_items, int x_dtype,
+                                                  int y_dtype, uint32_t flags) {
+    if (!ctx || !items) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_svdlora_forward_group: NULL argument");
+    if (n_items < 1 || n_items > ESSA_MAX_GROUP) return essa_fail(ESSA_ERR_SHAPE, "essa_svdlora_forward_group: %d items, at most %d", n_items, ESSA_MAX_GROUP);
+    ESSA_HIP(hipSetDevice(ctx->device));
+    std::vector<essa_k::fwd_item> ks;
+    ESSA_TRY(plan_items(ctx, items, n_items, x_dtype, y_dtype, flags, ks, "essa_svdlora_forward_group"));
+    if (ks.empty()) return ESSA_OK;
+    ESSA_HIP(essa_k::forward_group(ctx->stream, ks.data(), (int)ks.size(), x_dtype, y_dtype, flags));
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_svdlora_forward(essa_ctx* ctx, const essa_proj* proj, const void* X, int x_dtype, int R,
+                                            const int32_t* row2cand, const float* sigmaA, const float* sigmaB,
+                                            int64_t sigma_stride, int K, void* Y, int y_dtype, uint32_t flags) {
+    if (!ctx) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_svdlora_forward: ctx is NULL");
+    essa_fwd_item it{proj, X, row2cand, sigmaA, sigmaB, Y, sigma_stride, R, K};
+    std::vector<essa_k::fwd_item> ks;
+    ESSA_HIP(hipSetDevice(ctx->device));
+    ESSA_TRY(plan_items(ctx, &it, 1, x_dtype, y_dtype, flags, ks, "essa_svdlora_forward"));
+    if (ks.empty()) return ESSA_OK;
+    ESSA_HIP(essa_k::forward_group(ctx->stream, ks.data(), 1, x_dtype, y_dtype, flags));
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_w8a8_accumulators(essa_ctx* ctx, const essa_proj* proj, const void* X, int x_dtype, int R,
+                                              int8_t* xq_out, float* xscale_out, int32_t* acc_out) {
+    if (!ctx || !proj || !X || !xq_out || !xscale_out || !acc_out) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_w8a8_accumulators: NULL argument");
+    if (proj->quant != ESSA_QUANT_INT8_PERCH) return essa_fail(ESSA_ERR_UNSUPPORTED, "essa_w8a8_accumulators: int8 weights only");
+    if (x_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_UNSUPPORTED, "essa_w8a8_accumulators: bf16 activations only");
+    if (R < 1) return essa_fail(ESSA_ERR_SHAPE, "essa_w8a8_accumulators: R=%d", R);
+    ESSA_HIP(hipSetDevice(ctx->device));
+    essa_k::fwd_item k{};
+    k.X = X; k.R = R; k.K = 1;
+    k.d_in = proj->d_in; k.d_out = proj->d_out; k.r = proj->r; k.rp = proj->rp; k.quant = proj->quant;
+    k.Wq = proj->Wq; k.scale = proj->scale;
+    k.Xq = xq_out; k.xscale = xscale_out;
+    ESSA_HIP(essa_k::w8a8_accumulators(ctx->stream, k, x_dtype, acc_out));
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_reward_accumulate(essa_ctx* ctx, const void* Y, int y_dtype, int R, int d_out, const float* v,
+                                              const int32_t* row2cand, int K, float* F) {
+    if (!ctx || !Y || !v || !row2cand || !F) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_reward_accumulate: NULL argument");
+    if (y_dtype != ESSA_F32 && y_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_reward_accumulate: y_dtype %d", y_dtype);
+    if (R < 1 || d_out < 1 || K < 1) return essa_fail(ESSA_ERR_SHAPE, "essa_reward_accumulate: R=%d d_out=%d K=%d", R, d_out, K);
+    ESSA_HIP(hipSetDevice(ctx->device));
+    ESSA_TRY(essa_ws_reserve(ctx, align256((size_t)R * 4)));
+    ESSA_HIP(essa_k::reward_accumulate(ctx->stream, Y, y_dtype, R, d_out, v, row2cand, K, (float*)ctx->ws, F));
+    return ESSA_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// hot path: ranking and update
+// ---------------------------------------------------------------------------------------------
+extern "C" essa_status essa_rank_rewards(essa_ctx* ctx, const float* rewards, int K, int32_t* order) {
+    if (!ctx || !rewards || !order) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_rank_rewards: NULL argument");
+    if (K < 1 || K > 1024) return essa_fail(ESSA_ERR_SHAPE, "essa_rank_rewards: K=%d not in [1, 1024]", K);
+    ESSA_HIP(hipSetDevice(ctx->device));
+    ESSA_HIP(essa_k::rank_rewards(ctx->stream, rewards, K, order));
+    return ESSA_OK;
+}
+
+static essa_k::cma_consts make_consts(int n, int K, std::vector<float>& w) {
+    // default strategy parameters, evaluated in fp64 on the host
+    essa_k::cma_consts c{};
+    c.n = n; c.K = K; c.mu = K / 2;
+    std::vector<double> wd(c.mu);
+    double sum = 0, sum2 = 0;
+    for (int i = 0; i < c.mu; ++i) { wd[i] = std::log((K + 1) / 2.0) - std::log(i + 1.0); sum += wd[i]; }
+    for (int i = 0; i < c.mu; ++i) { wd[i] /= sum; sum2 += wd[i] * wd[i]; }
+    const double mu_eff = 1.0 / sum2, nn = n;
+    const double c_sigma = (mu_eff + 2.0) / (nn + mu_eff + 5.0);
+    const double d_sigma = 1.0 + 2.0 * std::fmax(0.0, std::sqrt((mu_eff - 1.0) / (nn + 1.0)) - 1.0) + c_sigma;
+    const double c_c = (4.0 + mu_eff / nn) / (nn + 4.0 + 2.0 * mu_eff / nn);
+    const double c_1 = 2.0 / ((nn + 1.3) * (nn + 1.3) + mu_eff);
+    const double c_mu = std::fmin(1.0 - c_1, 2.0 * (mu_eff - 2.0 + 1.0 / mu_eff) / ((nn + 2.0) * (nn + 2.0) + mu_eff));
+    const double chi_n = std::sqrt(nn) * (1.0 - 1.0 / (4.0 * nn) + 1.0 / (21.0 * nn * nn));
+    c.mu_eff = (float)mu_eff; c.c_sigma = (float)c_sigma; c.d_sigma = (float)d_sigma; c.c_c = (float)c_c;
+    c.c_1 = (float)c_1; c.c_mu = (float)c_mu; c.chi_n = (float)chi_n;
+    w.resize(c.mu);
+    for (int i = 0; i < c.mu; ++i) w[i] = (float)wd[i];
+    return c;
+}
+
+extern "C" essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uint32_t* seeds, const float* rewards, int K,
+                                         int32_t* order_out) {
+    if (!ctx || !cma || !seeds || !rewards) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cmaes_update: NULL argument");
+    if (cma->ctx != ctx) return essa_fail(ESSA_ERR_STATE, "essa_cmaes_update: state belongs to another context");
+    if (K < 2 || K > 1024) return essa_fail(ESSA_ERR_SHAPE, "essa_cmaes_update: K=%d not in [2, 1024]", K);
+    ESSA_HIP(hipSetDevice(ctx->device));
+    const int n = cma->n;
+    std::vector<float> w;
+    essa_k::cma_consts c = make_consts(n, K, w);
+    if (cma->weights_K != K) {
+        ESSA_HIP(hipStreamSynchronize(ctx->stream));
+        if (cma->weights) ESSA_HIP(hipFree(cma->weights));
+        cma->weights = nullptr;
+        cma->weights_K = 0;
+        ESSA_TRY(upload(&cma->weights, w.data(), w.size()));
+        cma->weights_K = K;
+    }
+    // scratch: order[K] | S[(mu+1), n] | BY[(mu+1), n] | Z[mu, n]
+    const size_t rows = (size_t)c.mu + 1;
+    const size_t off_S = align256((size_t)K * 4), off_BY = off_S + align256(rows * n * 4);
+    const size_t off_Z = off_BY + align256(rows * n * 4);
+    ESSA_TRY(essa_ws_reserve(ctx, off_Z + align256(rows * n * 4)));
+    int32_t* order = (int32_t*)ctx->ws;
+    float* S = (float*)((char*)ctx->ws + off_S);
+    float* BY = (float*)((char*)ctx->ws + off_BY);
+    float* Z = (float*)((char*)ctx->ws + off_Z);
+    ESSA_HIP(essa_k::rank_rewards(ctx->stream, rewards, K, order));
+    if (order_out) ESSA_HIP(hipMemcpyAsync(order_out, order, (size_t)K * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    ESSA_HIP(essa_k::cma_build_rhs(ctx->stream, seeds, order, cma->weights, c, cma->D, S, Z));
+    ESSA_HIP(essa_k::skinny_gemm_nt(ctx->stream, S, (int)rows, cma->B, n, nullptr, nullptr, 0, BY));
+    ESSA_HIP(essa_k::cma_vectors(ctx->stream, c, cma->weights, BY, cma->m, cma->p_sigma, cma->p_c, cma->sc));
+    ESSA_HIP(essa_k::cma_covariance(ctx->stream, c, cma->weights, BY, cma->p_c, cma->sc, cma->C));
+    return ESSA_OK;
+}

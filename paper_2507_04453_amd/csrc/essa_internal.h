@@ -1,0 +1,133 @@
+// Internal declarations shared by the host glue and the kernel launchers of libessa.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "essa.h"
+
+// ---- error reporting ---------------------------------------------------------------------------
+essa_status essa_fail(essa_status code, const char* fmt, ...);
+#define ESSA_HIP(call)                                                                             \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess)                                                                      \
+            return essa_fail(ESSA_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_),  \
+                             __FILE__, __LINE__);                                                  \
+    } while (0)
+#define ESSA_TRY(expr)                  \
+    do {                                \
+        essa_status s_ = (expr);        \
+        if (s_ != ESSA_OK) return s_;   \
+    } while (0)
+
+// ---- objects -----------------------------------------------------------------------------------
+struct essa_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    void* ws = nullptr;        // scratch, grown on demand
+    size_t ws_bytes = 0;
+};
+essa_status essa_ws_reserve(essa_ctx* ctx, size_t bytes);
+
+struct essa_proj {
+    essa_ctx* ctx = nullptr;   // identity check only; never dereferenced after creation
+    int device = 0;
+    hipStream_t stream = nullptr;
+    int d_in = 0, d_out = 0, r = 0;
+    int rp = 0;                // rank padded to 16 or 32 (zero columns)
+    int quant = 0;
+    int groups = 0;            // d_in / 128 for int4, 0 for int8
+    void* Wq = nullptr;        // int8 [d_out,d_in]  |  packed nibbles [d_out,d_in/2]
+    float* scale = nullptr;    // int8: [d_out]      |  int4: [d_out,groups]
+    float* zero = nullptr;     // int4: [d_out,groups] (quantised units), else null
+    float* VA32 = nullptr;     // [d_in, rp]   V_A, fp32, zero padded
+    uint16_t* VA16 = nullptr;  // [rp, d_in]   V_A^T, bf16 (rows = singular directions)
+    float* UB32 = nullptr;     // [d_out, rp]
+    uint16_t* UB16 = nullptr;  // [d_out, 2, rp]  bf16 head and tail of U_B
+    float* M = nullptr;        // [rp, rp]     V_B^T U_A, zero padded
+    std::vector<float> sA, sB; // own singular values, host copies
+};
+
+struct essa_cma_scalars {      // lives on the device, updated by kernels only
+    float sigma;
+    int32_t t;
+    float h_sigma;             // last update's stall flag (diagnostic)
+    float ps_norm;             // last update's |p_sigma|
+};
+
+struct essa_cma {
+    essa_ctx* ctx = nullptr;   // identity check only; never dereferenced after creation
+    int device = 0;
+    hipStream_t stream = nullptr;
+    int n = 0;
+    float *m = nullptr, *p_sigma = nullptr, *p_c = nullptr, *D = nullptr, *C = nullptr, *B = nullptr;
+    essa_cma_scalars* sc = nullptr;
+    float* weights = nullptr;  // device [mu] for weights_K
+    int weights_K = 0;
+};
+
+// ---- host-side setup helpers ----------------------------------------------------------------------
+// Thin SVD of a tall matrix G (m x r, row-major, m >= r) by one-sided Jacobi in fp64:
+// G = U diag(s) V^T, s descending.  U: m x r, V: r x r (row-major).
+void essa_host_thin_svd(const double* G, int m, int r, double* U, double* s, double* V);
+
+// ---- launchers (each checks nothing: callers validated the arguments) -----------------------------
+namespace essa_k {
+hipError_t philox_words(hipStream_t st, const uint32_t* seeds, int K, int n_blocks, uint32_t* out);
+// S[k, :] = D * z_k (z optionally stored too)
+hipError_t normals_scaled(hipStream_t st, const uint32_t* seeds, const int32_t* sel /*null or [J]*/, int J, int n,
+                          const float* D, float* S, float* z_out);
+// Out[j, i] = bias[i] + scale * sum_l S[j,l] B[i,l]; scale = use_sigma ? sc->sigma : 1; bias may be null
+hipError_t skinny_gemm_nt(hipStream_t st, const float* S, int J, const float* B, int n, const float* bias,
+                          const essa_cma_scalars* sc, int use_sigma, float* Out);
+hipError_t theta_to_sigma(hipStream_t st, int P, int r, int n_top, const float* sftA, const float* sftB,
+                          const float* theta, int K, float* sA, float* sB);
+hipError_t rank_rewards(hipStream_t st, const float* F, int K, int32_t* order);
+
+struct cma_consts {
+    int n, K, mu;
+    float mu_eff, c_sigma, d_sigma, c_c, c_1, c_mu, chi_n;
+};
+// S rows 0..mu-1 = D*z_sel, row mu = z_w (weights applied); needs order
+hipError_t cma_build_rhs(hipStream_t st, const uint32_t* seeds, const int32_t* order, const float* w,
+                         const cma_consts& c, const float* D, float* S, float* Z /*[mu,n] scratch*/);
+hipError_t cma_vectors(hipStream_t st, const cma_consts& c, const float* w, const float* BY /*[mu+1,n]*/,
+                       float* m, float* p_sigma, float* p_c, essa_cma_scalars* sc);
+hipError_t cma_covariance(hipStream_t st, const cma_consts& c, const float* w, const float* BY, const float* p_c,
+                          const essa_cma_scalars* sc, float* C);
+
+struct fwd_item {              // one projection of a grouped forward, device pointers only
+    const void* X;
+    const int32_t* row2cand;
+    const float* sigmaA;
+    const float* sigmaB;
+    void* Y;
+    long long sigma_stride;
+    int R, K;
+    // projection
+    int d_in, d_out, r, rp, quant, groups;
+    const void* Wq;
+    const float* scale;
+    const float* zero;
+    const float* VA32;
+    const uint16_t* VA16;
+    const float* UB32;
+    const uint16_t* UB16;
+    const float* M;
+    // scratch of this item
+    float* U32;                // [R, rp]  fp32 rank-space vector u_i
+    uint16_t* U16;             // [R, 2, rp]  bf16 head and tail of u_i
+    float* xsum;               // [R, max(groups,1)] group sums of x (int4) / unused
+    int8_t* Xq;                // [R, d_in] (W8A8)
+    float* xscale;             // [R]      (W8A8)
+};
+hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int x_dtype, int y_dtype,
+                         unsigned flags);
+hipError_t w8a8_accumulators(hipStream_t st, const fwd_item& it, int x_dtype, int32_t* acc_out);
+hipError_t reward_accumulate(hipStream_t st, const void* Y, int y_dtype, int R, int d_out, const float* v,
+                             const int32_t* row2cand, int K, float* rowdot /*[R] scratch*/, float* F);
+}  // namespace essa_k

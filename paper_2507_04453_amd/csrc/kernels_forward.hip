@@ -1,0 +1,597 @@
+// Population-batched forward of SVD-parameterised LoRA projections on a shared quantised base weight
+// (paper: Algorithm 1, reconstruction step W' = W + B'A', A' = U_A diag(sA) V_A^T, B' = U_B diag(sB) V_B^T,
+// followed by the inference pass).  The candidate's dense W' is never formed:
+//     y_i = W_deq x_i + U_B ( sB_c * ( (V_B^T U_A) ( sA_c * (V_A^T x_i) ) ) ),   c = row2cand[i].
+//
+// Launch sequence of one grouped call:
+//   1. prologue: per row, the rank-space vector u_i = sB_c * (M (sA_c * V_A^T x_i)) (and, where the
+//      format needs them, per-group sums of x or the row's int8 quantisation);
+//   2. GEMM: Y = X W_q^T with the dequantisation fused (weights converted in registers on their way
+//      into LDS, scales applied to the fp32 accumulators), and the rank-r term U_B u_i added by one or
+//      two more MFMA steps in the epilogue.
+#include <type_traits>
+
+#include "essa_internal.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(16))) int i32x16;
+
+namespace {
+
+struct fwd_args {
+    essa_k::fwd_item it[ESSA_MAX_GROUP];
+    int tile_start[ESSA_MAX_GROUP + 1];   // prefix sums of GEMM tiles per item
+    int n_items;
+    unsigned flags;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+// exact for integers of at most 8 significant bits
+__device__ __forceinline__ uint32_t pack_bf16_trunc(float lo, float hi) {
+    return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u);
+}
+
+// ------------------------------------------------------------------------------------------------
+// 1. prologue: one workgroup per row
+// ------------------------------------------------------------------------------------------------
+template <int RP, bool XBF16>
+__global__ __launch_bounds__(256) void prologue_kernel(fwd_args a) {
+    const essa_k::fwd_item& it = a.it[blockIdx.y];
+    const int i = blockIdx.x;
+    if (i >= it.R) return;
+    __shared__ float part[4][RP];
+    __shared__ float tvec[RP];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int din = it.d_in;
+    float acc[RP];
+#pragma unroll
+    for (int j = 0; j < RP; ++j) acc[j] = 0.f;
+    for (int l = tid; l < din; l += 256) {
+        const float x = XBF16 ? bf16_bits_to_f32(((const uint16_t*)it.X)[(size_t)i * din + l]) : ((const float*)it.X)[(size_t)i * din + l];
+        const float4* v = reinterpret_cast<const float4*>(it.VA32 + (size_t)l * RP);
+#pragma unroll
+        for (int j4 = 0; j4 < RP / 4; ++j4) {
+            const float4 vv = v[j4];
+            acc[4 * j4 + 0] = fmaf(x, vv.x, acc[4 * j4 + 0]);
+            acc[4 * j4 + 1] = fmaf(x, vv.y, acc[4 * j4 + 1]);
+            acc[4 * j4 + 2] = fmaf(x, vv.z, acc[4 * j4 + 2]);
+            acc[4 * j4 + 3] = fmaf(x, vv.w, acc[4 * j4 + 3]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < RP; ++j) {
+        float v = acc[j];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+        if (lane == 0) part[wave][j] = v;
+    }
+    __syncthreads();
+    const int c = it.row2cand[i];
+    if (tid < RP) {
+        const float t = part[0][tid] + part[1][tid] + part[2][tid] + part[3][tid];
+        const float sa = tid < it.r ? it.sigmaA[(size_t)c * it.sigma_stride + tid] : 0.f;
+        tvec[tid] = sa * t;
+    }
+    __syncthreads();
+    if (tid < RP) {
+        float u = 0.f;
+        if (tid < it.r && !(a.flags & ESSA_BASE_ONLY)) {
+            for (int l = 0; l < it.r; ++l) u = fmaf(it.M[tid * RP + l], tvec[l], u);
+            u *= it.sigmaB[(size_t)c * it.sigma_stride + tid];
+        }
+        it.U32[(size_t)i * RP + tid] = u;
+        // bf16 head and tail: u = hi + lo to about 2^-17, so that the MFMA epilogue loses nothing
+        const uint16_t hi = f32_to_bf16_bits(u);
+        it.U16[(size_t)i * 2 * RP + tid] = hi;
+        it.U16[(size_t)i * 2 * RP + RP + tid] = f32_to_bf16_bits(u - bf16_bits_to_f32(hi));
+    }
+    if (it.groups > 0) {   // group sums of x for the asymmetric 4-bit format
+        for (int g = wave; g < it.groups; g += 4) {
+            const int l = g * 128 + 2 * lane;
+            float s;
+            if (XBF16) {
+                const uint32_t two = *reinterpret_cast<const uint32_t*>((const uint16_t*)it.X + (size_t)i * din + l);
+                s = __uint_as_float(two << 16) + __uint_as_float(two & 0xffff0000u);
+            } else {
+                const float2 two = *reinterpret_cast<const float2*>((const float*)it.X + (size_t)i * din + l);
+                s = two.x + two.y;
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+            if (lane == 0) it.xsum[(size_t)i * it.groups + g] = s;
+        }
+    }
+}
+
+// per-row dynamic int8 quantisation of bf16 activations (W8A8 mode); the decisions are taken in fp32:
+// amax = max|x|, inv = 127/amax, q = rint(x*inv) (ties to even), scale = amax/127.
+__global__ __launch_bounds__(256) void rowquant_kernel(fwd_args a) {
+    const essa_k::fwd_item& it = a.it[blockIdx.y];
+    const int i = blockIdx.x;
+    if (i >= it.R) return;
+    __shared__ float wmax[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint16_t* x = (const uint16_t*)it.X + (size_t)i * it.d_in;
+    float m = 0.f;
+    for (int l = tid; l < it.d_in; l += 256) m = fmaxf(m, fabsf(bf16_bits_to_f32(x[l])));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if (lane == 0) wmax[wave] = m;
+    __syncthreads();
+    const float amax = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    const float inv = amax > 0.f ? 127.0f / amax : 0.f;
+    for (int l = tid; l < it.d_in; l += 256) {
+        float q = rintf(bf16_bits_to_f32(x[l]) * inv);
+        q = fminf(fmaxf(q, -127.f), 127.f);
+        it.Xq[(size_t)i * it.d_in + l] = (int8_t)(int)q;
+    }
+    if (tid == 0) it.xscale[i] = amax > 0.f ? amax / 127.0f : 0.f;
+}
+
+// ------------------------------------------------------------------------------------------------
+// 2a. generic fp32 GEMM (fp32 activations, or shapes the MFMA kernels do not take)
+// ------------------------------------------------------------------------------------------------
+template <bool XBF16, bool YBF16>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(fwd_args a) {
+    int g = 0;
+    while (g + 1 < a.n_items && (int)blockIdx.x >= a.tile_start[g + 1]) ++g;
+    const essa_k::fwd_item& it = a.it[g];
+    const int tile = blockIdx.x - a.tile_start[g];
+    const int tiles_m = (it.R + 63) / 64;
+    const int m0 = (tile % tiles_m) * 64, n0 = (tile / tiles_m) * 64;
+    __shared__ float Xs[16][68], Ws[16][68];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int din = it.d_in, dout = it.d_out, G = it.groups;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < din; k0 += 16) {
+        // 64 x 16 elements of each operand, 4 per thread
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = tid + 256 * e, row = idx >> 4, kk = idx & 15, k = k0 + kk;
+            float xv = 0.f, wv = 0.f;
+            if (k < din) {
+                const int i = m0 + row, o = n0 + row;
+                if (i < it.R)
+                    xv = XBF16 ? bf16_bits_to_f32(((const uint16_t*)it.X)[(size_t)i * din + k]) : ((const float*)it.X)[(size_t)i * din + k];
+                if (o < dout) {
+                    if (it.quant == ESSA_QUANT_INT8_PERCH) {
+                        wv = (float)((const int8_t*)it.Wq)[(size_t)o * din + k];
+                    } else {
+                        const uint8_t b = ((const uint8_t*)it.Wq)[((size_t)o * din + k) >> 1];
+                        const float q = (float)((k & 1) ? (b >> 4) : (b & 15));
+                        const size_t gi = (size_t)o * G + (k >> 7);
+                        wv = it.scale[gi] * (q - it.zero[gi]);
+                    }
+                }
+            }
+            Xs[kk][row] = xv;
+            Ws[kk][row] = wv;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const float4 xa = *reinterpret_cast<const float4*>(&Xs[kk][ty * 4]);
+            const float4 wb = *reinterpret_cast<const float4*>(&Ws[kk][tx * 4]);
+            const float xv[4] = {xa.x, xa.y, xa.z, xa.w}, wv[4] = {wb.x, wb.y, wb.z, wb.w};
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+#pragma unroll
+                for (int y = 0; y < 4; ++y) acc[x][y] = fmaf(xv[x], wv[y], acc[x][y]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int i = m0 + ty * 4 + x;
+        if (i >= it.R) continue;
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+            const int o = n0 + tx * 4 + y;
+            if (o >= dout) continue;
+            float v = acc[x][y];
+            if (it.quant == ESSA_QUANT_INT8_PERCH) v *= it.scale[o];
+            if (a.flags & ESSA_LORA_ONLY) v = 0.f;
+            if (!(a.flags & ESSA_BASE_ONLY)) {
+                float l = 0.f;
+                for (int j = 0; j < it.r; ++j) l = fmaf(it.U32[(size_t)i * it.rp + j], it.UB32[(size_t)o * it.rp + j], l);
+                v += l;
+            }
+            if (YBF16) ((uint16_t*)it.Y)[(size_t)i * dout + o] = f32_to_bf16_bits(v);
+            else ((float*)it.Y)[(size_t)i * dout + o] = v;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// 2b. MFMA GEMM with fused dequantisation.  MODE 0: int8 weights x bf16 activations (bf16 MFMA);
+// MODE 1: 4-bit group-128 weights x bf16 activations (bf16 MFMA, per-group fp32 rescale);
+// MODE 2: int8 weights x int8 activations (int8 MFMA, exact int32 accumulation).
+// 256 threads = 2 x 2 waves, each wave owns a (BM/2) x (BN/2) tile made of 32x32 MFMA blocks.
+// ------------------------------------------------------------------------------------------------
+constexpr int BK = 64;
+
+template <int BM, int BN, int MODE, bool YBF16, bool DUMP_I32>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(fwd_args a, int32_t* __restrict__ acc_out) {
+    constexpr int MI = BM / 64, NI = BN / 64;
+    constexpr int ESZ = MODE == 2 ? 1 : 2;                 // bytes per LDS element
+    constexpr int LDA = (BK + (MODE == 2 ? 16 : 8));       // elements per LDS row (padded)
+    __shared__ __attribute__((aligned(16))) unsigned char As[BM * LDA * ESZ];
+    __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * LDA * ESZ];
+
+    int g = 0;
+    while (g + 1 < a.n_items && (int)blockIdx.x >= a.tile_start[g + 1]) ++g;
+    const essa_k::fwd_item& it = a.it[g];
+    const int tile = blockIdx.x - a.tile_start[g];
+    const int tiles_m = (it.R + BM - 1) / BM;
+    const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int din = it.d_in, dout = it.d_out, R = it.R, G = it.groups;
+
+    // ---- global -> register staging -------------------------------------------------------------
+    // X tile: BM rows x 64 elements; chunks of 16 bytes (8 bf16 or 16 int8)
+    constexpr int XCH_ROW = MODE == 2 ? 4 : 8;                       // chunks per row
+    constexpr int XCH = (BM * XCH_ROW + 255) / 256;                  // chunks per thread
+    // W tile: BN rows x 64 elements; int8 -> 4 chunks per row, 4-bit -> 2 chunks per row
+    constexpr int WCH_ROW = MODE == 1 ? 2 : 4;
+    constexpr int WCH = (BN * WCH_ROW + 255) / 256;
+    uint4 xr[XCH], wr[WCH];
+    const unsigned char* Xb = MODE == 2 ? (const unsigned char*)it.Xq : (const unsigned char*)it.X;
+    const size_t x_row_bytes = (size_t)din * ESZ;
+    const size_t w_row_bytes = MODE == 1 ? (size_t)din / 2 : (size_t)din;
+    const int nk = (din + BK - 1) / BK;
+
+    auto load_tiles = [&](int kt) {
+#pragma unroll
+        for (int e = 0; e < XCH; ++e) {
+            const int ch = tid + 256 * e, row = ch / XCH_ROW, part = ch % XCH_ROW;
+            const int k = kt * BK + part * (16 / ESZ);
+            xr[e] = make_uint4(0, 0, 0, 0);
+            if (ch < BM * XCH_ROW && m0 + row < R && k < din)
+                xr[e] = *reinterpret_cast<const uint4*>(Xb + (size_t)(m0 + row) * x_row_bytes + (size_t)k * ESZ);
+        }
+#pragma unroll
+        for (int e = 0; e < WCH; ++e) {
+            const int ch = tid + 256 * e, row = ch / WCH_ROW, part = ch % WCH_ROW;
+            const int k = kt * BK + part * (MODE == 1 ? 32 : 16);
+            wr[e] = make_uint4(0, 0, 0, 0);
+            if (ch < BN * WCH_ROW && n0 + row < dout && k < din)
+                wr[e] = *reinterpret_cast<const uint4*>((const unsigned char*)it.Wq + (size_t)(n0 + row) * w_row_bytes +
+                                                        (MODE == 1 ? (size_t)k / 2 : (size_t)k));
+        }
+    };
+    auto store_tiles = [&]() {
+#pragma unroll
+        for (int e = 0; e < XCH; ++e) {
+            const int ch = tid + 256 * e, row = ch / XCH_ROW, part = ch % XCH_ROW;
+            if (ch < BM * XCH_ROW) *reinterpret_cast<uint4*>(As + ((size_t)row * LDA + part * (16 / ESZ)) * ESZ) = xr[e];
+        }
+#pragma unroll
+        for (int e = 0; e < WCH; ++e) {
+            const int ch = tid + 256 * e, row = ch / WCH_ROW, part = ch % WCH_ROW;
+            if (ch >= BN * WCH_ROW) continue;
+            if (MODE == 2) {
+                *reinterpret_cast<uint4*>(Bs + (size_t)row * LDA + part * 16) = wr[e];
+            } else if (MODE == 0) {
+                // 16 int8 -> 16 bf16 (exact)
+                const uint32_t w4[4] = {wr[e].x, wr[e].y, wr[e].z, wr[e].w};
+                uint32_t o[8];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const int v = (int)w4[d];
+                    const float f0 = (float)((v << 24) >> 24), f1 = (float)((v << 16) >> 24);
+                    const float f2 = (float)((v << 8) >> 24), f3 = (float)(v >> 24);
+                    o[2 * d] = pack_bf16_trunc(f0, f1);
+                    o[2 * d + 1] = pack_bf16_trunc(f2, f3);
+                }
+                uint4* dst = reinterpret_cast<uint4*>(Bs + ((size_t)row * LDA + part * 16) * 2);
+                dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+                dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+            } else {
+                // 16 bytes = 32 nibbles -> 32 bf16 (exact): column 2j in the low nibble
+                const uint32_t w4[4] = {wr[e].x, wr[e].y, wr[e].z, wr[e].w};
+                uint4* dst = reinterpret_cast<uint4*>(Bs + ((size_t)row * LDA + part * 32) * 2);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    uint32_t o[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const uint32_t byte = (w4[d] >> (8 * b)) & 0xffu;
+                        o[b] = pack_bf16_trunc((float)(byte & 15u), (float)(byte >> 4));
+                    }
+                    dst[d] = make_uint4(o[0], o[1], o[2], o[3]);
+                }
+            }
+        }
+    };
+
+    using acc_t = typename std::conditional<MODE == 2, i32x16, f32x16>::type;
+    acc_t acc[MI][NI];
+    f32x16 tot[MODE == 1 ? MI : 1][MODE == 1 ? NI : 1];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[mi][ni][q] = 0;
+            if (MODE == 1)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) tot[mi][ni][q] = 0.f;
+        }
+
+    load_tiles(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        store_tiles();
+        __syncthreads();
+        if (kt + 1 < nk) load_tiles(kt + 1);
+        if constexpr (MODE == 2) {
+#pragma unroll
+            for (int ks = 0; ks < BK / 32; ++ks) {
+                i32x4 av[MI], bv[NI];
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+                    av[mi] = *reinterpret_cast<const i32x4*>(As + (size_t)(wm * (BM / 2) + mi * 32 + l32) * LDA + ks * 32 + 16 * h);
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    bv[ni] = *reinterpret_cast<const i32x4*>(Bs + (size_t)(wn * (BN / 2) + ni * 32 + l32) * LDA + ks * 32 + 16 * h);
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+                        acc[mi][ni] = (acc_t)__builtin_amdgcn_mfma_i32_32x32x32_i8(av[mi], bv[ni], (i32x16)acc[mi][ni], 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                bf16x8 av[MI], bv[NI];
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+                    av[mi] = *reinterpret_cast<const bf16x8*>(As + ((size_t)(wm * (BM / 2) + mi * 32 + l32) * LDA + ks * 16 + 8 * h) * 2);
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    bv[ni] = *reinterpret_cast<const bf16x8*>(Bs + ((size_t)(wn * (BN / 2) + ni * 32 + l32) * LDA + ks * 16 + 8 * h) * 2);
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < NI; ++ni)
+                        acc[mi][ni] = (acc_t)__builtin_amdgcn_mfma_f32_32x32x16_bf16(av[mi], bv[ni], (f32x16)acc[mi][ni], 0, 0, 0);
+            }
+            if constexpr (MODE == 1) if (kt & 1) {
+                // end of a 128-column group: tot += s * (acc - z * sum_group(x)), then restart acc
+                const int grp = kt >> 1;
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni) {
+                    const int o = min(n0 + wn * (BN / 2) + ni * 32 + l32, dout - 1);
+                    const float s = it.scale[(size_t)o * G + grp], z = it.zero[(size_t)o * G + grp];
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) {
+                            const int i = min(m0 + wm * (BM / 2) + mi * 32 + 8 * (q >> 2) + 4 * h + (q & 3), R - 1);
+                            const float xs = it.xsum[(size_t)i * G + grp];
+                            tot[mi][ni][q] = fmaf(s, fmaf(-z, xs, acc[mi][ni][q]), tot[mi][ni][q]);
+                            acc[mi][ni][q] = 0;
+                        }
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue ----------------------------------------------------------------------------------
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int o = n0 + wn * (BN / 2) + ni * 32 + l32;
+        const int oc = min(o, dout - 1);
+        const float wscale = MODE == 1 ? 1.f : it.scale[oc];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int rbase = m0 + wm * (BM / 2) + mi * 32;
+            if (DUMP_I32) {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int i = rbase + 8 * (q >> 2) + 4 * h + (q & 3);
+                    if (i < R && o < dout) acc_out[(size_t)i * dout + o] = (int)acc[mi][ni][q];
+                }
+                continue;
+            }
+            f32x16 v;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                if (MODE == 2) {
+                    const int i = min(rbase + 8 * (q >> 2) + 4 * h + (q & 3), R - 1);
+                    v[q] = (float)acc[mi][ni][q] * (it.xscale[i] * wscale);   // one rounding in the product of scales
+                } else if (MODE == 1) {
+                    v[q] = tot[mi][ni][q];
+                } else {
+                    v[q] = (float)acc[mi][ni][q] * wscale;
+                }
+                if (a.flags & ESSA_LORA_ONLY) v[q] = 0.f;
+            }
+            if (!(a.flags & ESSA_BASE_ONLY)) {
+                // rank-r term U_B u_i by MFMA steps of 16 rank columns.  Both operands are stored as a bf16
+                // head and tail (x = hi + lo); hi*hi + hi*lo + lo*hi keeps the term at fp32-like accuracy.
+                const int ur = min(rbase + l32, R - 1);
+                const uint16_t* up = it.U16 + (size_t)ur * 2 * it.rp + 8 * h;
+                const uint16_t* bp = it.UB16 + (size_t)oc * 2 * it.rp + 8 * h;
+                for (int ks = 0; ks < it.rp / 16; ++ks) {
+                    const bf16x8 ua_hi = *reinterpret_cast<const bf16x8*>(up + ks * 16);
+                    const bf16x8 ua_lo = *reinterpret_cast<const bf16x8*>(up + it.rp + ks * 16);
+                    const bf16x8 ub_hi = *reinterpret_cast<const bf16x8*>(bp + ks * 16);
+                    const bf16x8 ub_lo = *reinterpret_cast<const bf16x8*>(bp + it.rp + ks * 16);
+                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_lo, ub_hi, v, 0, 0, 0);
+                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_hi, ub_lo, v, 0, 0, 0);
+                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_hi, ub_hi, v, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int i = rbase + 8 * (q >> 2) + 4 * h + (q & 3);
+                if (i < R && o < dout) {
+                    if (YBF16) ((uint16_t*)it.Y)[(size_t)i * dout + o] = f32_to_bf16_bits(v[q]);
+                    else ((float*)it.Y)[(size_t)i * dout + o] = v[q];
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// synthetic reward
+// ------------------------------------------------------------------------------------------------
+template <bool YBF16>
+__global__ __launch_bounds__(256) void rowdot_kernel(const void* __restrict__ Y, int R, int d_out, const float* __restrict__ v,
+                                                    float* __restrict__ rowdot) {
+    const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= R) return;
+    float s = 0.f;
+    for (int o = lane; o < d_out; o += 64) {
+        const float y = YBF16 ? bf16_bits_to_f32(((const uint16_t*)Y)[(size_t)row * d_out + o]) : ((const float*)Y)[(size_t)row * d_out + o];
+        s = fmaf(y, v[o], s);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) rowdot[row] = s;
+}
+
+// F[k] += (sum of rowdot over the rows of candidate k) / (their number); fixed-order tree, 0/0 = NaN.
+__global__ __launch_bounds__(256) void cand_mean_kernel(const float* __restrict__ rowdot, const int32_t* __restrict__ row2cand, int R,
+                                                       float* __restrict__ F) {
+    __shared__ double ssum[256];
+    __shared__ int scnt[256];
+    const int k = blockIdx.x, tid = threadIdx.x;
+    double s = 0.0;
+    int cnt = 0;
+    for (int i = tid; i < R; i += 256)
+        if (row2cand[i] == k) { s += (double)rowdot[i]; ++cnt; }
+    ssum[tid] = s;
+    scnt[tid] = cnt;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if (tid < st) { ssum[tid] += ssum[tid + st]; scnt[tid] += scnt[tid + st]; }
+        __syncthreads();
+    }
+    if (tid == 0) F[k] += (float)(ssum[0] / (double)scnt[0]);
+}
+
+}  // namespace
+
+namespace essa_k {
+
+static bool mfma_shape_ok(const fwd_item& it) { return it.d_in % 16 == 0; }
+
+template <int BM, int BN>
+static void launch_mfma(hipStream_t st, fwd_args& a, int n_items, int mode, int y_dtype) {
+    int total = 0;
+    for (int g = 0; g < n_items; ++g) {
+        a.tile_start[g] = total;
+        total += ((a.it[g].R + BM - 1) / BM) * ((a.it[g].d_out + BN - 1) / BN);
+    }
+    a.tile_start[n_items] = total;
+    const bool yb = y_dtype == ESSA_BF16;
+#define ESSA_LAUNCH(MODE_)                                                                                        \
+    if (yb) hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, MODE_, true, false>), dim3(total), dim3(256), 0, st, a, nullptr); \
+    else hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, MODE_, false, false>), dim3(total), dim3(256), 0, st, a, nullptr)
+    if (mode == 0) { ESSA_LAUNCH(0); }
+    else if (mode == 1) { ESSA_LAUNCH(1); }
+    else { ESSA_LAUNCH(2); }
+#undef ESSA_LAUNCH
+}
+
+hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int x_dtype, int y_dtype, unsigned flags) {
+    // items are grouped by the kernel family that takes them; within a family they share one launch
+    fwd_args a{};
+    a.flags = flags;
+    int maxR = 0;
+    for (int g = 0; g < n_items; ++g) { a.it[g] = items[g]; maxR = items[g].R > maxR ? items[g].R : maxR; }
+    a.n_items = n_items;
+    const bool xb = x_dtype == ESSA_BF16;
+
+    // prologue (the rank padding is the same for every item of a launch; split by rp)
+    for (int rp : {16, 32}) {
+        fwd_args p{};
+        p.flags = flags;
+        int cnt = 0, mr = 0;
+        for (int g = 0; g < n_items; ++g)
+            if (items[g].rp == rp) { p.it[cnt++] = items[g]; mr = items[g].R > mr ? items[g].R : mr; }
+        if (!cnt) continue;
+        p.n_items = cnt;
+        dim3 grid(mr, cnt);
+        if (rp == 16) {
+            if (xb) hipLaunchKernelGGL((prologue_kernel<16, true>), grid, dim3(256), 0, st, p);
+            else hipLaunchKernelGGL((prologue_kernel<16, false>), grid, dim3(256), 0, st, p);
+        } else {
+            if (xb) hipLaunchKernelGGL((prologue_kernel<32, true>), grid, dim3(256), 0, st, p);
+            else hipLaunchKernelGGL((prologue_kernel<32, false>), grid, dim3(256), 0, st, p);
+        }
+    }
+    if (flags & ESSA_COMPUTE_W8A8) hipLaunchKernelGGL(rowquant_kernel, dim3(maxR, n_items), dim3(256), 0, st, a);
+
+    // split the items between the MFMA family (bf16 activations, d_in % 16 == 0) and the generic one
+    fwd_args am{}, ag{};
+    am.flags = ag.flags = flags;
+    int mode = -1;
+    for (int g = 0; g < n_items; ++g) {
+        const int want = (flags & ESSA_COMPUTE_W8A8) ? 2 : (items[g].quant == ESSA_QUANT_INT4_G128 ? 1 : 0);
+        if (xb && mfma_shape_ok(items[g]) && (mode < 0 || mode == want)) { am.it[am.n_items++] = items[g]; mode = want; }
+        else if (xb && mfma_shape_ok(items[g])) {   // a second format in one group: its own launch
+            fwd_args one{};
+            one.flags = flags;
+            one.it[0] = items[g];
+            one.n_items = 1;
+            launch_mfma<64, 64>(st, one, 1, want, y_dtype);
+        } else ag.it[ag.n_items++] = items[g];
+    }
+    if (am.n_items) {
+        long long tiles128 = 0;
+        for (int g = 0; g < am.n_items; ++g) tiles128 += (long long)((am.it[g].R + 127) / 128) * ((am.it[g].d_out + 127) / 128);
+        if (tiles128 >= 512) launch_mfma<128, 128>(st, am, am.n_items, mode, y_dtype);
+        else launch_mfma<64, 64>(st, am, am.n_items, mode, y_dtype);
+    }
+    if (ag.n_items) {
+        int total = 0;
+        for (int g = 0; g < ag.n_items; ++g) {
+            ag.tile_start[g] = total;
+            total += ((ag.it[g].R + 63) / 64) * ((ag.it[g].d_out + 63) / 64);
+        }
+        ag.tile_start[ag.n_items] = total;
+        const bool yb = y_dtype == ESSA_BF16;
+        if (xb && yb) hipLaunchKernelGGL((gemm_f32_kernel<true, true>), dim3(total), dim3(256), 0, st, ag);
+        else if (xb) hipLaunchKernelGGL((gemm_f32_kernel<true, false>), dim3(total), dim3(256), 0, st, ag);
+        else if (yb) hipLaunchKernelGGL((gemm_f32_kernel<false, true>), dim3(total), dim3(256), 0, st, ag);
+        else hipLaunchKernelGGL((gemm_f32_kernel<false, false>), dim3(total), dim3(256), 0, st, ag);
+    }
+    return hipGetLastError();
+}
+
+hipError_t w8a8_accumulators(hipStream_t st, const fwd_item& it, int x_dtype, int32_t* acc_out) {
+    (void)x_dtype;
+    fwd_args a{};
+    a.it[0] = it;
+    a.n_items = 1;
+    hipLaunchKernelGGL(rowquant_kernel, dim3(it.R, 1), dim3(256), 0, st, a);
+    a.tile_start[0] = 0;
+    const int total = ((it.R + 63) / 64) * ((it.d_out + 63) / 64);
+    a.tile_start[1] = total;
+    hipLaunchKernelGGL((gemm_mfma_kernel<64, 64, 2, false, true>), dim3(total), dim3(256), 0, st, a, acc_out);
+    return hipGetLastError();
+}
+
+hipError_t reward_accumulate(hipStream_t st, const void* Y, int y_dtype, int R, int d_out, const float* v,
+                             const int32_t* row2cand, int K, float* rowdot, float* F) {
+    if (y_dtype == ESSA_BF16) hipLaunchKernelGGL((rowdot_kernel<true>), dim3((R + 3) / 4), dim3(256), 0, st, Y, R, d_out, v, rowdot);
+    else hipLaunchKernelGGL((rowdot_kernel<false>), dim3((R + 3) / 4), dim3(256), 0, st, Y, R, d_out, v, rowdot);
+    hipLaunchKernelGGL(cand_mean_kernel, dim3(K), dim3(256), 0, st, rowdot, row2cand, R, F);
+    return hipGetLastError();
+}
+
+}  // namespace essa_k

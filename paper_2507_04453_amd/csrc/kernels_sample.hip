@@ -1,0 +1,178 @@
+// Seed -> candidate sampling kernels (paper: Method, "Evolutionary optimization"; Algorithm 1,
+// "sample candidate offsets from shared seeds"), the theta -> singular-value scatter, and the skinny
+// fp32 product with the covariance basis that both the sampler and the update use.
+#include "essa_internal.h"
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+namespace {
+
+// Philox4x32-10 of Salmon et al. (SC'11): ten rounds of two 32x32->64 multiplies and xors, the key
+// bumped by the Weyl constants between rounds.
+__device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k) {
+    const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int rnd = 0; rnd < 10; ++rnd) {
+        if (rnd > 0) { k.x += W0; k.y += W1; }
+        const uint32_t hi0 = __umulhi(M0, c.x), lo0 = M0 * c.x;
+        const uint32_t hi1 = __umulhi(M1, c.z), lo1 = M1 * c.z;
+        c = make_uint4(hi1 ^ c.y ^ k.x, lo1, hi0 ^ c.w ^ k.y, lo0);
+    }
+    return c;
+}
+
+// Box-Muller on 24-bit uniforms, evaluated in fp64 and rounded once to fp32 so that the value does
+// not depend on the accuracy of fp32 log / sincos near u = 1.
+__device__ __forceinline__ void box_muller(uint32_t wa, uint32_t wb, float& za, float& zb) {
+    const double ua = ((double)(wa >> 8) + 0.5) * 0x1p-24;
+    const double ub = ((double)(wb >> 8) + 0.5) * 0x1p-24;
+    const double rho = sqrt(-2.0 * log(ua));
+    double s, c;
+    sincospi(2.0 * ub, &s, &c);
+    za = (float)(rho * c);
+    zb = (float)(rho * s);
+}
+
+__global__ void philox_words_kernel(const uint32_t* __restrict__ seeds, int K, int n_blocks, uint32_t* __restrict__ out) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)K * n_blocks) return;
+    const int k = (int)(idx / n_blocks), c = (int)(idx % n_blocks);
+    const uint4 w = philox4x32_10(make_uint4((uint32_t)c, 0u, 0u, 0u), make_uint2(seeds[k], 0u));
+    reinterpret_cast<uint4*>(out)[idx] = w;
+}
+
+// S[j, l] = D[l] * z_{cand(j)}[l],  cand(j) = sel ? sel[j] : j ; optional copy of z itself.
+__global__ void normals_scaled_kernel(const uint32_t* __restrict__ seeds, const int32_t* __restrict__ sel, int J, int n,
+                                      const float* __restrict__ D, float* __restrict__ S, float* __restrict__ z_out) {
+    const int nb = (n + 3) / 4;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)J * nb) return;
+    const int j = (int)(idx / nb), c = (int)(idx % nb);
+    const int cand = sel ? sel[j] : j;
+    const uint4 w = philox4x32_10(make_uint4((uint32_t)c, 0u, 0u, 0u), make_uint2(seeds[cand], 0u));
+    float z[4];
+    box_muller(w.x, w.y, z[0], z[1]);
+    box_muller(w.z, w.w, z[2], z[3]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int l = 4 * c + e;
+        if (l < n) {
+            S[(size_t)j * n + l] = D[l] * z[e];
+            if (z_out) z_out[(size_t)j * n + l] = z[e];
+        }
+    }
+}
+
+__global__ void theta_to_sigma_kernel(int P, int r, int n_top, const float* __restrict__ sftA, const float* __restrict__ sftB,
+                                      const float* __restrict__ theta, int K, float* __restrict__ sA, float* __restrict__ sB) {
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)K * P * r;
+    if (idx >= total) return;
+    const int j = (int)(idx % r), p = (int)((idx / r) % P), k = (int)(idx / ((long long)r * P));
+    const size_t n = (size_t)P * 2 * n_top;
+    float a = sftA[p * r + j], b = sftB[p * r + j];
+    if (j < n_top) {
+        a += theta[k * n + (size_t)p * 2 * n_top + j];
+        b += theta[k * n + (size_t)p * 2 * n_top + n_top + j];
+    }
+    sA[idx] = a;
+    sB[idx] = b;
+}
+
+// Out[j, i] = bias[i] + scale * sum_l S[j,l] * B[i,l]        (fp32 MFMA 32x32x2)
+// One workgroup = 32 rows of B x 64 rows of S; its 8 waves interleave over chunks of 8 columns and
+// their partial tiles are summed through LDS in a fixed order (bit-reproducible).
+constexpr int SG_WAVES = 8;
+template <bool ALIGNED>
+__global__ __launch_bounds__(SG_WAVES * 64) void skinny_gemm_nt_kernel(const float* __restrict__ S, int J, const float* __restrict__ B,
+                                                                      int n, const float* __restrict__ bias,
+                                                                      const essa_cma_scalars* __restrict__ sc, int use_sigma,
+                                                                      float* __restrict__ Out) {
+    __shared__ float red[SG_WAVES][2][16][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i0 = blockIdx.x * 32, j0 = blockIdx.y * 64;
+    const int li = lane & 31, h = lane >> 5;
+    const int i = i0 + li;
+    const int ja = j0 + li, jb = j0 + 32 + li;
+    f32x16 acc0 = {0}, acc1 = {0};
+    const int nchunks = (n + 7) / 8;
+    for (int ch = wave; ch < nchunks; ch += SG_WAVES) {
+        const int l = ch * 8 + 4 * h;
+        float a[4] = {0, 0, 0, 0}, s0[4] = {0, 0, 0, 0}, s1[4] = {0, 0, 0, 0};
+        if (ALIGNED) {
+            if (l < n) {
+                if (i < n) *reinterpret_cast<float4*>(a) = *reinterpret_cast<const float4*>(B + (size_t)i * n + l);
+                if (ja < J) *reinterpret_cast<float4*>(s0) = *reinterpret_cast<const float4*>(S + (size_t)ja * n + l);
+                if (jb < J) *reinterpret_cast<float4*>(s1) = *reinterpret_cast<const float4*>(S + (size_t)jb * n + l);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (l + e < n) {
+                    if (i < n) a[e] = B[(size_t)i * n + l + e];
+                    if (ja < J) s0[e] = S[(size_t)ja * n + l + e];
+                    if (jb < J) s1[e] = S[(size_t)jb * n + l + e];
+                }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], s0[e], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], s1[e], acc1, 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        red[wave][0][q][lane] = acc0[q];
+        red[wave][1][q][lane] = acc1[q];
+    }
+    __syncthreads();
+    const float scale = use_sigma ? sc->sigma : 1.0f;
+    // 2 x 16 x 64 results, 512 threads: 4 each
+    for (int idx = threadIdx.x; idx < 2 * 16 * 64; idx += SG_WAVES * 64) {
+        const int ln = idx & 63, q = (idx >> 6) & 15, blk = idx >> 10;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < SG_WAVES; ++w) sum += red[w][blk][q][ln];
+        // accumulator element q of lane ln: row (of B) 8*(q/4) + 4*(ln/32) + q%4, column (of S) ln%32
+        const int ii = i0 + 8 * (q >> 2) + 4 * (ln >> 5) + (q & 3);
+        const int jj = j0 + 32 * blk + (ln & 31);
+        if (ii < n && jj < J) Out[(size_t)jj * n + ii] = (bias ? bias[ii] : 0.f) + scale * sum;
+    }
+}
+
+}  // namespace
+
+namespace essa_k {
+
+hipError_t philox_words(hipStream_t st, const uint32_t* seeds, int K, int n_blocks, uint32_t* out) {
+    const long long total = (long long)K * n_blocks;
+    hipLaunchKernelGGL(philox_words_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, seeds, K, n_blocks, out);
+    return hipGetLastError();
+}
+
+hipError_t normals_scaled(hipStream_t st, const uint32_t* seeds, const int32_t* sel, int J, int n, const float* D, float* S,
+                          float* z_out) {
+    const long long total = (long long)J * ((n + 3) / 4);
+    hipLaunchKernelGGL(normals_scaled_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, seeds, sel, J, n, D, S, z_out);
+    return hipGetLastError();
+}
+
+hipError_t skinny_gemm_nt(hipStream_t st, const float* S, int J, const float* B, int n, const float* bias,
+                          const essa_cma_scalars* sc, int use_sigma, float* Out) {
+    dim3 grid((n + 31) / 32, (J + 63) / 64);
+    if (n % 4 == 0)
+        hipLaunchKernelGGL(skinny_gemm_nt_kernel<true>, grid, dim3(SG_WAVES * 64), 0, st, S, J, B, n, bias, sc, use_sigma, Out);
+    else
+        hipLaunchKernelGGL(skinny_gemm_nt_kernel<false>, grid, dim3(SG_WAVES * 64), 0, st, S, J, B, n, bias, sc, use_sigma, Out);
+    return hipGetLastError();
+}
+
+hipError_t theta_to_sigma(hipStream_t st, int P, int r, int n_top, const float* sftA, const float* sftB, const float* theta,
+                          int K, float* sA, float* sB) {
+    const long long total = (long long)K * P * r;
+    hipLaunchKernelGGL(theta_to_sigma_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, P, r, n_top, sftA, sftB, theta,
+                       K, sA, sB);
+    return hipGetLastError();
+}
+
+}  // namespace essa_k

@@ -1,0 +1,386 @@
+"""ctypes binding of include/essa.h.  Function names mirror the C entry points; arguments are torch
+tensors living on the GPU (device memory) or numpy arrays (host memory), exactly as essa.h says."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+__all__ = [
+    "EssaError", "lib", "LIB_PATH", "Context", "Projection", "CmaState",
+    "F32", "BF16", "QUANT_INT8_PERCH", "QUANT_INT4_G128", "COMPUTE_W8A8", "LORA_ONLY", "BASE_ONLY",
+    "essa_create", "essa_proj_create", "essa_cma_create", "essa_sample_candidates", "essa_philox_words",
+    "essa_theta_to_sigma", "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
+    "essa_reward_accumulate", "essa_cmaes_update", "essa_rank_rewards", "essa_version", "EXPORTED_SYMBOLS",
+]
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libessa.so")
+
+F32, BF16 = 0, 1
+QUANT_INT8_PERCH, QUANT_INT4_G128 = 0, 1
+COMPUTE_W8A8, LORA_ONLY, BASE_ONLY = 1, 2, 4
+MAX_GROUP = 8
+
+EXPORTED_SYMBOLS = [
+    "essa_create", "essa_destroy", "essa_last_error", "essa_version", "essa_synchronize",
+    "essa_proj_create", "essa_proj_destroy", "essa_proj_spectrum",
+    "essa_cma_create", "essa_cma_destroy", "essa_cma_set_basis", "essa_cma_export", "essa_cma_import",
+    "essa_sample_candidates", "essa_philox_words", "essa_theta_to_sigma",
+    "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
+    "essa_reward_accumulate", "essa_cmaes_update", "essa_rank_rewards",
+]
+
+
+class EssaError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("essa status %d: %s" % (code, msg))
+        self.code = code
+
+
+class _ProjDesc(C.Structure):
+    _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("r", C.c_int32), ("quant", C.c_int32),
+                ("Wq", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p),
+                ("lora_A", C.c_void_p), ("lora_B", C.c_void_p)]
+
+
+class _FwdItem(C.Structure):
+    _fields_ = [("proj", C.c_void_p), ("X", C.c_void_p), ("row2cand", C.c_void_p), ("sigmaA", C.c_void_p),
+                ("sigmaB", C.c_void_p), ("Y", C.c_void_p), ("sigma_stride", C.c_int64), ("R", C.c_int32),
+                ("K", C.c_int32)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libessa.so is not built (%s); run `python -m paper_2507_04453_amd.build`. "
+                          "There is no fallback path." % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, u32, f32 = C.c_void_p, C.c_int, C.c_int64, C.c_uint32, C.c_float
+    sig = {
+        "essa_create": (i32, [C.POINTER(vp), i32, vp]),
+        "essa_destroy": (None, [vp]),
+        "essa_last_error": (C.c_char_p, []),
+        "essa_version": (C.c_char_p, []),
+        "essa_synchronize": (i32, [vp]),
+        "essa_proj_create": (i32, [vp, C.POINTER(_ProjDesc), C.POINTER(vp)]),
+        "essa_proj_destroy": (None, [vp]),
+        "essa_proj_spectrum": (i32, [vp, vp, vp]),
+        "essa_cma_create": (i32, [vp, i32, f32, vp, C.POINTER(vp)]),
+        "essa_cma_destroy": (None, [vp]),
+        "essa_cma_set_basis": (i32, [vp, vp, vp]),
+        "essa_cma_export": (i32, [vp, vp, C.POINTER(C.c_size_t)]),
+        "essa_cma_import": (i32, [vp, vp, C.c_size_t]),
+        "essa_sample_candidates": (i32, [vp, vp, vp, i32, vp, vp]),
+        "essa_philox_words": (i32, [vp, vp, i32, i32, vp]),
+        "essa_theta_to_sigma": (i32, [vp, i32, i32, i32, vp, vp, vp, i32, vp, vp]),
+        "essa_svdlora_forward": (i32, [vp, vp, vp, i32, i32, vp, vp, vp, i64, i32, vp, i32, u32]),
+        "essa_svdlora_forward_group": (i32, [vp, C.POINTER(_FwdItem), i32, i32, i32, u32]),
+        "essa_w8a8_accumulators": (i32, [vp, vp, vp, i32, i32, vp, vp, vp]),
+        "essa_reward_accumulate": (i32, [vp, vp, i32, i32, i32, vp, vp, i32, vp]),
+        "essa_cmaes_update": (i32, [vp, vp, vp, vp, i32, vp]),
+        "essa_rank_rewards": (i32, [vp, vp, i32, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    return L
+
+
+lib = _load()
+
+
+def _check(code):
+    if code != 0:
+        raise EssaError(code, lib.essa_last_error().decode("utf-8", "replace"))
+
+
+def essa_version() -> str:
+    return lib.essa_version().decode()
+
+
+def _dev(t, dtype=None, name="tensor"):
+    """Device pointer of a contiguous CUDA/HIP tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a torch tensor on the GPU" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return C.c_void_p(t.data_ptr())
+
+
+def _host(a, dtype, name="array"):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, C.c_void_p(a.ctypes.data)
+
+
+def _xdtype(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("activations must be float32 or bfloat16, got %s" % t.dtype)
+
+
+class Context:
+    """essa_ctx: one GPU, one stream (the current torch stream at creation unless given)."""
+
+    def __init__(self, device: int = 0, stream: "torch.cuda.Stream | None" = None):
+        self._h = C.c_void_p()
+        self.device = device
+        torch.cuda.set_device(device)
+        self.stream = stream
+        sp = C.c_void_p(stream.cuda_stream) if stream is not None else None
+        _check(lib.essa_create(C.byref(self._h), device, sp))
+
+    def synchronize(self):
+        _check(lib.essa_synchronize(self._h))
+
+    def close(self):
+        if self._h:
+            lib.essa_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def essa_create(device: int = 0, stream=None) -> Context:
+    return Context(device, stream)
+
+
+class Projection:
+    """essa_proj: built from HOST arrays (quantised weight, scales, zeros, raw LoRA factors)."""
+
+    def __init__(self, ctx: Context, Wq, scales, zeros, lora_A, lora_B, quant: int):
+        self.ctx = ctx
+        lora_A = np.ascontiguousarray(lora_A, np.float32)
+        lora_B = np.ascontiguousarray(lora_B, np.float32)
+        r, d_in = lora_A.shape
+        d_out = lora_B.shape[0]
+        if lora_B.shape[1] != r:
+            raise ValueError("lora_B must be [d_out, r]")
+        keep = [lora_A, lora_B]
+        if quant == QUANT_INT8_PERCH:
+            Wq = np.ascontiguousarray(Wq, np.int8)
+            scales = np.ascontiguousarray(scales, np.float32)
+            if Wq.shape != (d_out, d_in) or scales.shape != (d_out,):
+                raise ValueError("int8: Wq [d_out,d_in], scales [d_out]")
+            zp = None
+        elif quant == QUANT_INT4_G128:
+            Wq = np.ascontiguousarray(Wq, np.uint8)
+            scales = np.ascontiguousarray(scales, np.float16)
+            zeros = np.ascontiguousarray(zeros, np.float16)
+            if Wq.shape != (d_out, d_in // 2) or scales.shape != (d_out, d_in // 128) or zeros.shape != scales.shape:
+                raise ValueError("int4: Wq [d_out,d_in/2], scales/zeros [d_out,d_in/128]")
+            zp = C.c_void_p(zeros.ctypes.data)
+            keep.append(zeros)
+        else:
+            raise ValueError("unknown quant")
+        keep += [Wq, scales]
+        d = _ProjDesc(d_in, d_out, r, quant, C.c_void_p(Wq.ctypes.data), C.c_void_p(scales.ctypes.data), zp,
+                      C.c_void_p(lora_A.ctypes.data), C.c_void_p(lora_B.ctypes.data))
+        self._h = C.c_void_p()
+        _check(lib.essa_proj_create(ctx._h, C.byref(d), C.byref(self._h)))
+        self.d_in, self.d_out, self.r, self.quant = d_in, d_out, r, quant
+
+    def spectrum(self):
+        """(S_A[r], S_B[r]): the factors' own singular values, descending (host float32)."""
+        sA, sB = np.empty(self.r, np.float32), np.empty(self.r, np.float32)
+        _check(lib.essa_proj_spectrum(self._h, C.c_void_p(sA.ctypes.data), C.c_void_p(sB.ctypes.data)))
+        return sA, sB
+
+    def close(self):
+        if self._h:
+            lib.essa_proj_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def essa_proj_create(ctx, Wq, scales, zeros, lora_A, lora_B, quant) -> Projection:
+    return Projection(ctx, Wq, scales, zeros, lora_A, lora_B, quant)
+
+
+_BLOB_HEADER = np.dtype([("magic", "<u4"), ("version", "<u4"), ("n", "<i4"), ("t", "<i4"), ("sigma", "<f4"), ("reserved", "<u4")])
+
+
+class CmaState:
+    """essa_cma: the search distribution on the device."""
+
+    def __init__(self, ctx: Context, n: int, sigma0: float, m0=None):
+        self.ctx, self.n = ctx, n
+        self._h = C.c_void_p()
+        if m0 is not None:
+            m0, mp = _host(m0, np.float32)
+            if m0.shape != (n,):
+                raise ValueError("m0 must be [n]")
+        else:
+            mp = None
+        _check(lib.essa_cma_create(ctx._h, n, C.c_float(sigma0), mp, C.byref(self._h)))
+
+    def set_basis(self, B: torch.Tensor, D: torch.Tensor):
+        if tuple(B.shape) != (self.n, self.n) or tuple(D.shape) != (self.n,):
+            raise ValueError("B [n,n], D [n]")
+        _check(lib.essa_cma_set_basis(self._h, _dev(B, torch.float32, "B"), _dev(D, torch.float32, "D")))
+
+    def export_blob(self) -> bytes:
+        size = C.c_size_t(0)
+        _check(lib.essa_cma_export(self._h, None, C.byref(size)))
+        buf = (C.c_char * size.value)()
+        _check(lib.essa_cma_export(self._h, C.cast(buf, C.c_void_p), C.byref(size)))
+        return bytes(buf)
+
+    def import_blob(self, blob: bytes):
+        buf = (C.c_char * len(blob)).from_buffer_copy(blob)
+        _check(lib.essa_cma_import(self._h, C.cast(buf, C.c_void_p), len(blob)))
+
+    def export(self) -> dict:
+        """The blob parsed into numpy arrays (t, sigma, m, p_sigma, p_c, D, C, B)."""
+        blob = self.export_blob()
+        h = np.frombuffer(blob, _BLOB_HEADER, 1)[0]
+        n = int(h["n"])
+        body = np.frombuffer(blob, np.float32, offset=_BLOB_HEADER.itemsize)
+        out = dict(n=n, t=int(h["t"]), sigma=float(h["sigma"]))
+        off = 0
+        for name in ("m", "p_sigma", "p_c", "D"):
+            out[name] = body[off:off + n].copy()
+            off += n
+        out["C"] = body[off:off + n * n].reshape(n, n).copy()
+        off += n * n
+        out["B"] = body[off:off + n * n].reshape(n, n).copy()
+        return out
+
+    @staticmethod
+    def pack_blob(n, t, sigma, m, p_sigma, p_c, D, Cm, B) -> bytes:
+        h = np.zeros(1, _BLOB_HEADER)
+        h["magic"], h["version"], h["n"], h["t"], h["sigma"] = 0x41535345, 1, n, t, sigma
+        parts = [h.tobytes()] + [np.ascontiguousarray(a, np.float32).tobytes() for a in (m, p_sigma, p_c, D, Cm, B)]
+        return b"".join(parts)
+
+    def close(self):
+        if self._h:
+            lib.essa_cma_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def essa_cma_create(ctx, n, sigma0, m0=None) -> CmaState:
+    return CmaState(ctx, n, sigma0, m0)
+
+
+def essa_sample_candidates(ctx: Context, cma: CmaState, seeds: torch.Tensor, theta_out: torch.Tensor, z_out: torch.Tensor | None = None):
+    K = seeds.numel()
+    if tuple(theta_out.shape) != (K, cma.n) or (z_out is not None and tuple(z_out.shape) != (K, cma.n)):
+        raise ValueError("theta_out / z_out must be [K, n]")
+    _check(lib.essa_sample_candidates(ctx._h, cma._h, _dev(seeds, torch.int32, "seeds"), K, _dev(theta_out, torch.float32, "theta_out"),
+                                      _dev(z_out, torch.float32, "z_out")))
+
+
+def essa_philox_words(ctx: Context, seeds: torch.Tensor, n_blocks: int, words_out: torch.Tensor):
+    K = seeds.numel()
+    if words_out.numel() != K * n_blocks * 4:
+        raise ValueError("words_out must hold K*n_blocks*4 words")
+    _check(lib.essa_philox_words(ctx._h, _dev(seeds, torch.int32, "seeds"), K, n_blocks, _dev(words_out, torch.int32, "words_out")))
+
+
+def essa_theta_to_sigma(ctx: Context, n_top: int, sft_A: torch.Tensor, sft_B: torch.Tensor, theta: torch.Tensor,
+                        sigmaA: torch.Tensor, sigmaB: torch.Tensor):
+    P, r = sft_A.shape
+    K = theta.shape[0]
+    if n_top >= 1 and theta.shape[1] != P * 2 * n_top:
+        raise ValueError("theta must be [K, P*2*n_top]")
+    if tuple(sigmaA.shape) != (K, P, r) or tuple(sigmaB.shape) != (K, P, r) or tuple(sft_B.shape) != (P, r):
+        raise ValueError("sigma outputs must be [K,P,r], spectra [P,r]")
+    _check(lib.essa_theta_to_sigma(ctx._h, P, r, n_top, _dev(sft_A, torch.float32), _dev(sft_B, torch.float32),
+                                   _dev(theta, torch.float32), K, _dev(sigmaA, torch.float32), _dev(sigmaB, torch.float32)))
+
+
+def _ydtype(t):
+    return _xdtype(t)
+
+
+def _sigma_args(proj, sigmaA, sigmaB, K):
+    if sigmaA.dtype != torch.float32 or sigmaB.dtype != torch.float32 or not sigmaA.is_cuda or not sigmaB.is_cuda:
+        raise TypeError("sigmaA/sigmaB must be float32 GPU tensors")
+    if sigmaA.shape != sigmaB.shape or sigmaA.dim() != 2 or sigmaA.shape[0] != K or sigmaA.shape[1] != proj.r:
+        raise ValueError("sigmaA/sigmaB must be [K, r] views")
+    if sigmaA.stride(1) != 1 or sigmaB.stride(1) != 1 or sigmaA.stride(0) != sigmaB.stride(0):
+        raise ValueError("sigmaA/sigmaB must have unit inner stride and equal candidate stride")
+    return C.c_void_p(sigmaA.data_ptr()), C.c_void_p(sigmaB.data_ptr()), int(sigmaA.stride(0))
+
+
+def essa_svdlora_forward(ctx: Context, proj: Projection, X: torch.Tensor, row2cand: torch.Tensor, sigmaA: torch.Tensor,
+                         sigmaB: torch.Tensor, Y: torch.Tensor, flags: int = 0):
+    """sigmaA/sigmaB: [K, r] float32 views (any candidate stride, unit inner stride)."""
+    R = X.shape[0]
+    K = sigmaA.shape[0]
+    if X.dim() != 2 or X.shape[1] != proj.d_in or tuple(Y.shape) != (R, proj.d_out) or row2cand.numel() != R:
+        raise ValueError("X [R,d_in], Y [R,d_out], row2cand [R]")
+    pa, pb, stride = _sigma_args(proj, sigmaA, sigmaB, K)
+    _check(lib.essa_svdlora_forward(ctx._h, proj._h, _dev(X, None, "X"), _xdtype(X), R, _dev(row2cand, torch.int32, "row2cand"),
+                                    pa, pb, stride, K, _dev(Y, None, "Y"), _ydtype(Y), flags))
+
+
+def essa_svdlora_forward_group(ctx: Context, items, flags: int = 0):
+    """items: list of (proj, X, row2cand, sigmaA, sigmaB, Y); all X share a dtype and all Y share a dtype."""
+    if not 1 <= len(items) <= MAX_GROUP:
+        raise ValueError("1..%d items" % MAX_GROUP)
+    arr = (_FwdItem * len(items))()
+    xd = yd = None
+    for i, (proj, X, row2cand, sigmaA, sigmaB, Y) in enumerate(items):
+        R, K = X.shape[0], sigmaA.shape[0]
+        if X.dim() != 2 or X.shape[1] != proj.d_in or tuple(Y.shape) != (R, proj.d_out) or row2cand.numel() != R:
+            raise ValueError("item %d: X [R,d_in], Y [R,d_out], row2cand [R]" % i)
+        pa, pb, stride = _sigma_args(proj, sigmaA, sigmaB, K)
+        if xd is None:
+            xd, yd = _xdtype(X), _ydtype(Y)
+        elif xd != _xdtype(X) or yd != _ydtype(Y):
+            raise TypeError("all items of a group share the activation and output dtypes")
+        arr[i] = _FwdItem(proj._h, _dev(X, None, "X"), _dev(row2cand, torch.int32, "row2cand"), pa, pb, _dev(Y, None, "Y"), stride, R, K)
+    _check(lib.essa_svdlora_forward_group(ctx._h, arr, len(items), xd, yd, flags))
+
+
+def essa_w8a8_accumulators(ctx: Context, proj: Projection, X: torch.Tensor, xq_out: torch.Tensor, xscale_out: torch.Tensor,
+                           acc_out: torch.Tensor):
+    R = X.shape[0]
+    if tuple(xq_out.shape) != (R, proj.d_in) or xscale_out.numel() != R or tuple(acc_out.shape) != (R, proj.d_out):
+        raise ValueError("xq_out [R,d_in], xscale_out [R], acc_out [R,d_out]")
+    _check(lib.essa_w8a8_accumulators(ctx._h, proj._h, _dev(X, None, "X"), _xdtype(X), R, _dev(xq_out, torch.int8), _dev(xscale_out, torch.float32),
+                                      _dev(acc_out, torch.int32)))
+
+
+def essa_reward_accumulate(ctx: Context, Y: torch.Tensor, v: torch.Tensor, row2cand: torch.Tensor, F: torch.Tensor):
+    R, d_out = Y.shape
+    _check(lib.essa_reward_accumulate(ctx._h, _dev(Y, None, "Y"), _ydtype(Y), R, d_out, _dev(v, torch.float32, "v"),
+                                      _dev(row2cand, torch.int32, "row2cand"), F.numel(), _dev(F, torch.float32, "F")))
+
+
+def essa_cmaes_update(ctx: Context, cma: CmaState, seeds: torch.Tensor, rewards: torch.Tensor, order_out: torch.Tensor | None = None):
+    K = seeds.numel()
+    if rewards.numel() != K or (order_out is not None and order_out.numel() != K):
+        raise ValueError("seeds, rewards, order_out must all hold K entries")
+    _check(lib.essa_cmaes_update(ctx._h, cma._h, _dev(seeds, torch.int32, "seeds"), _dev(rewards, torch.float32, "rewards"), K,
+                                 _dev(order_out, torch.int32, "order_out")))
+
+
+def essa_rank_rewards(ctx: Context, rewards: torch.Tensor, order: torch.Tensor):
+    K = rewards.numel()
+    if order.numel() != K:
+        raise ValueError("order must hold K entries")
+    _check(lib.essa_rank_rewards(ctx._h, _dev(rewards, torch.float32, "rewards"), K, _dev(order, torch.int32, "order")))

@@ -1,0 +1,523 @@
+"""GPU parity: the HIP library (through its C ABI binding) against the CPU oracle on the same seeded inputs.
+
+Tolerances (relative to the whole reference tensor: max|d|/max|ref| and ||d||/||ref||):
+  bit-exact      Philox words, int8 activation codes, int32 accumulators, ranking
+  fp32 paths     rms 1e-5, max 1e-4   (tiny config, sampler, update)
+  bf16 inputs    rms 1e-3, max 2e-2   (the stated bar); the fp32-output variants are held to rms 2e-5,
+                 max 2e-4: inputs are exact there and every accumulation is fp32 (the rank-r term uses
+                 bf16 head+tail operands).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import essa_workloads as wl
+import oracle as orc
+from helpers import bf16_dev, bf16_host, candidate_sigmas, gpu_proj, oracle_proj, sample_rows, seeds_dev, to_dev
+
+pytestmark = pytest.mark.gpu
+
+FP32_RMS, FP32_MAX = 1e-5, 1e-4
+BF16_RMS, BF16_MAX = 1e-3, 2e-2
+
+
+@pytest.fixture(scope="module")
+def ctx(essa):
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = essa.Context(0)
+    yield c
+    c.close()
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------------------------ sampler
+def test_philox_words_bit_exact(essa, ctx):
+    seeds = [0, 1, 2, 0xFFFFFFFF, 20250704]
+    nb = 1000
+    out = torch.empty(len(seeds) * nb * 4, dtype=torch.int32, device="cuda")
+    essa.essa_philox_words(ctx, seeds_dev(seeds), nb, out)
+    got = out.cpu().numpy().view(np.uint32).reshape(len(seeds), nb, 4)
+    for i, s in enumerate(seeds):
+        assert np.array_equal(got[i], orc.philox_words_for_seed(s, nb)), "seed %d" % s
+
+
+@pytest.mark.parametrize("n,K", [(16, 4), (50, 3), (257, 70), (3584, 64)])
+def test_sample_candidates(essa, ctx, n, K):
+    _say("sample n=%d K=%d" % (n, K))
+    Q, d = wl.random_covariance_basis(n, basis_id=n)
+    m0 = np.linspace(-1, 1, n).astype(np.float32)
+    cma = essa.CmaState(ctx, n, 0.32, m0)
+    cma.set_basis(to_dev(Q), to_dev(d))
+    seeds = list(range(1, K + 1))
+    theta = torch.empty(K, n, device="cuda")
+    z = torch.empty(K, n, device="cuda")
+    essa.essa_sample_candidates(ctx, cma, seeds_dev(seeds), theta, z)
+    theta2 = torch.empty_like(theta)
+    essa.essa_sample_candidates(ctx, cma, seeds_dev(seeds), theta2, None)
+    ref_theta, ref_z = orc.sample_candidates(m0, np.float32(0.32), Q, d, seeds)
+    zg = z.cpu().numpy()
+    assert np.all(np.abs(zg - ref_z) <= 2e-6 + 2e-6 * np.abs(ref_z))
+    assert np.mean(zg == ref_z) > 0.999          # fp64 Box-Muller on both sides: almost always the same float
+    e_max, e_rms = orc.rel_errors(theta.cpu().numpy(), ref_theta)
+    assert e_rms <= FP32_RMS and e_max <= FP32_MAX, (e_max, e_rms)
+    assert torch.equal(theta, theta2)            # same seed, same candidate, bit for bit
+    # a candidate does not depend on who else is in the call
+    one = torch.empty(1, n, device="cuda")
+    essa.essa_sample_candidates(ctx, cma, seeds_dev([seeds[-1]]), one, None)
+    assert torch.equal(one[0], theta[-1])
+    cma.close()
+
+
+def test_sample_identity_basis_is_exact(essa, ctx):
+    n, K = 64, 5
+    cma = essa.CmaState(ctx, n, 0.5, None)
+    theta = torch.empty(K, n, device="cuda")
+    z = torch.empty(K, n, device="cuda")
+    essa.essa_sample_candidates(ctx, cma, seeds_dev([9, 8, 7, 6, 5]), theta, z)
+    assert torch.equal(theta, 0.5 * z)
+    cma.close()
+
+
+def test_theta_to_sigma(essa, ctx):
+    P, r, K = 6, 16, 5
+    g = np.random.default_rng(0)
+    sA0 = g.uniform(0.5, 2, (P, r)).astype(np.float32)
+    sB0 = g.uniform(0.5, 2, (P, r)).astype(np.float32)
+    for n_top in (16, 8, 1):
+        th = g.standard_normal((K, P * 2 * n_top)).astype(np.float32)
+        sA = torch.empty(K, P, r, device="cuda")
+        sB = torch.empty(K, P, r, device="cuda")
+        essa.essa_theta_to_sigma(ctx, n_top, to_dev(sA0), to_dev(sB0), to_dev(th), sA, sB)
+        rA, rB = orc.theta_to_sigma(th, sA0, sB0, n_top / r)
+        assert np.array_equal(sA.cpu().numpy(), rA.astype(np.float32))
+        assert np.array_equal(sB.cpu().numpy(), rB.astype(np.float32))
+    with pytest.raises(essa.EssaError):
+        essa.essa_theta_to_sigma(ctx, 0, to_dev(sA0), to_dev(sB0), to_dev(np.zeros((K, 1), np.float32)),
+                                 torch.empty(K, P, r, device="cuda"), torch.empty(K, P, r, device="cuda"))
+
+
+# ------------------------------------------------------------------------------------------------ forward
+def test_forward_c1_tiny_fp32(essa, ctx):
+    """Configuration 1 as stated: 512x512 int8, r=8, K=4 candidates from seeds through the sampler."""
+    p = wl.make_projection("q", 512, 512, 8, "int8")
+    W, f = oracle_proj(p)
+    gp = gpu_proj(essa, ctx, p)
+    gA, gB = gp.spectrum()
+    np.testing.assert_allclose(gA, f["S_A"], rtol=2e-6)
+    np.testing.assert_allclose(gB, f["S_B"], rtol=2e-6)
+    # sigma_k = sigma_0 (1 + 0.1 z): sampler with m = 0, step 0.1, B = I, D = own spectrum, then offsets
+    n, K = 16, 4
+    D = np.concatenate([f["S_A"], f["S_B"]]).astype(np.float32)
+    cma = essa.CmaState(ctx, n, 0.1, None)
+    cma.set_basis(to_dev(np.eye(n, dtype=np.float32)), to_dev(D))
+    seeds = [1, 2, 3, 4]
+    theta = torch.empty(K, n, device="cuda")
+    essa.essa_sample_candidates(ctx, cma, seeds_dev(seeds), theta, None)
+    sA = torch.empty(K, 1, 8, device="cuda")
+    sB = torch.empty(K, 1, 8, device="cuda")
+    essa.essa_theta_to_sigma(ctx, 8, to_dev(f["S_A"][None].astype(np.float32)), to_dev(f["S_B"][None].astype(np.float32)), theta, sA, sB)
+    ref_theta, _ = orc.sample_candidates(np.zeros(n), np.float32(0.1), np.eye(n), D, seeds)
+    rA, rB = orc.theta_to_sigma(ref_theta, f["S_A"][None].astype(np.float32), f["S_B"][None].astype(np.float32), 1.0)
+    np.testing.assert_allclose(sA.cpu().numpy(), rA, rtol=1e-5)
+    X = wl.make_x_f32(64, 512)
+    r2c = wl.row2cand_contiguous(4, 16)
+    Y = torch.empty(64, 512, device="cuda")
+    essa.essa_svdlora_forward(ctx, gp, to_dev(X), to_dev(r2c), sA[:, 0, :], sB[:, 0, :], Y)
+    ref = orc.svdlora_forward(W, f, X, r2c, rA[:, 0, :], rB[:, 0, :])
+    e_max, e_rms = orc.rel_errors(Y.cpu().numpy(), ref)
+    _say("c1 err max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= FP32_RMS and e_max <= FP32_MAX
+    cma.close()
+    gp.close()
+
+
+@pytest.mark.parametrize("quant,d_in,d_out,r,K,R", [
+    ("int8", 320, 200, 8, 7, 203),       # ragged rows and columns, five k-tiles
+    ("int8", 1024, 384, 16, 5, 640),     # several 128x128 tiles
+    ("int8", 512, 256, 32, 3, 65),
+    ("int8", 328, 96, 4, 2, 9),          # d_in not a multiple of 16: generic kernel
+    ("int4", 384, 200, 16, 6, 130),
+    ("int4", 1024, 512, 32, 9, 300),
+])
+def test_forward_small_shapes_bf16(essa, ctx, quant, d_in, d_out, r, K, R):
+    _say("forward %s d_in=%d d_out=%d r=%d K=%d R=%d" % (quant, d_in, d_out, r, K, R))
+    p = wl.make_projection("t", d_in, d_out, r, quant, layer=3, proj=1)
+    W, f = oracle_proj(p)
+    gp = gpu_proj(essa, ctx, p)
+    sA, sB = candidate_sigmas(f, K, 0.05)
+    xb, xv = wl.make_x_bf16(R, d_in, x_id=7)
+    g = np.random.default_rng(1)
+    r2c = g.integers(0, K, R).astype(np.int32)
+    r2c[r2c == K - 1] = 0                                  # one candidate owns no row
+    ref = orc.svdlora_forward(W, f, xv, r2c, sA, sB)
+    Xd, rd, sAd, sBd = bf16_dev(xb), to_dev(r2c), to_dev(sA), to_dev(sB)
+    Y32 = torch.empty(R, d_out, device="cuda")
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32)
+    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref)
+    _say("  fp32 out: max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= 2e-5 and e_max <= 2e-4
+    Y16 = torch.empty(R, d_out, device="cuda", dtype=torch.bfloat16)
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y16)
+    e_max, e_rms = orc.rel_errors(bf16_host(Y16), orc.round_to_bf16(ref))
+    _say("  bf16 out: max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= BF16_RMS and e_max <= BF16_MAX
+    # the rank-r term alone and the base alone
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, essa.LORA_ONLY)
+    ref_l = orc.svdlora_forward(W, f, xv, r2c, sA, sB, lora_only=True)
+    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref_l)
+    _say("  lora only: max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= 1e-4 and e_max <= 1e-3
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, essa.BASE_ONLY)
+    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), xv.astype(np.float64) @ W.T)
+    assert e_rms <= 1e-5 and e_max <= 1e-4
+    # sigma = 0 reproduces the base layer; own spectrum reproduces W + BA of the unfactored factors
+    z = torch.zeros(K, r, device="cuda")
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, z, sBd, Y32)
+    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), xv.astype(np.float64) @ W.T)
+    assert e_rms <= 1e-5
+    own_A = to_dev(np.tile(f["S_A"].astype(np.float32), (K, 1)))
+    own_B = to_dev(np.tile(f["S_B"].astype(np.float32), (K, 1)))
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, own_A, own_B, Y32)
+    ref_own = xv.astype(np.float64) @ W.T + (xv.astype(np.float64) @ p.A.astype(np.float64).T) @ p.B.astype(np.float64).T
+    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref_own)
+    assert e_rms <= 2e-5
+    gp.close()
+
+
+def test_forward_edge_cases(essa, ctx):
+    p = wl.make_projection("t", 256, 128, 8, "int8", layer=5)
+    W, f = oracle_proj(p)
+    gp = gpu_proj(essa, ctx, p)
+    sA, sB = candidate_sigmas(f, 1, 0.05)
+    # R = 1, K = 1
+    xb, xv = wl.make_x_bf16(1, 256, x_id=3)
+    Y = torch.empty(1, 128, device="cuda")
+    essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb), to_dev(np.zeros(1, np.int32)), to_dev(sA), to_dev(sB), Y)
+    e_max, e_rms = orc.rel_errors(Y.cpu().numpy(), orc.svdlora_forward(W, f, xv, np.zeros(1, np.int32), sA, sB))
+    assert e_rms <= 2e-5
+    # R = 0 is a no-op
+    essa.essa_svdlora_forward(ctx, gp, torch.empty(0, 256, device="cuda", dtype=torch.bfloat16), torch.empty(0, dtype=torch.int32, device="cuda"),
+                              to_dev(sA), to_dev(sB), torch.empty(0, 128, device="cuda"))
+    # argument errors are reported, not launched
+    with pytest.raises(essa.EssaError):
+        essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb), to_dev(np.zeros(1, np.int32)), to_dev(sA), to_dev(sB), Y, 0x80)
+    with pytest.raises(essa.EssaError):
+        essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb), to_dev(np.zeros(1, np.int32)), to_dev(sA), to_dev(sB), Y, essa.LORA_ONLY | essa.BASE_ONLY)
+    gp.close()
+    # population sizes and ranks from the paper's sweeps that are not powers of two
+    for K, r in ((24, 2), (42, 4), (400, 8)):
+        p = wl.make_projection("t", 128, 64, r, "int8", layer=6)
+        W, f = oracle_proj(p)
+        gp = gpu_proj(essa, ctx, p)
+        sA, sB = candidate_sigmas(f, K, 0.05)
+        xb, xv = wl.make_x_bf16(K, 128, x_id=4)
+        r2c = np.arange(K, dtype=np.int32)[::-1].copy()
+        Y = torch.empty(K, 64, device="cuda")
+        essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb), to_dev(r2c), to_dev(sA), to_dev(sB), Y)
+        e_max, e_rms = orc.rel_errors(Y.cpu().numpy(), orc.svdlora_forward(W, f, xv, r2c, sA, sB))
+        assert e_rms <= 2e-5, (K, r, e_rms)
+        gp.close()
+
+
+def test_forward_row_permutation_and_strided_sigma(essa, ctx):
+    p = wl.make_projection("t", 512, 192, 16, "int8", layer=7)
+    W, f = oracle_proj(p)
+    gp = gpu_proj(essa, ctx, p)
+    K, R = 6, 150
+    sA, sB = candidate_sigmas(f, K, 0.05)
+    xb, xv = wl.make_x_bf16(R, 512, x_id=5)
+    r2c = wl.row2cand_contiguous(K, 25)
+    perm = np.random.default_rng(2).permutation(R)
+    Y1 = torch.empty(R, 192, device="cuda")
+    Y2 = torch.empty(R, 192, device="cuda")
+    # sigma handed over as a slice of a [K, P, r] tensor
+    big_A = torch.zeros(K, 3, 16, device="cuda")
+    big_B = torch.zeros(K, 3, 16, device="cuda")
+    big_A[:, 1, :] = to_dev(sA)
+    big_B[:, 1, :] = to_dev(sB)
+    essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb), to_dev(r2c), big_A[:, 1, :], big_B[:, 1, :], Y1)
+    essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb[perm]), to_dev(r2c[perm]), to_dev(sA), to_dev(sB), Y2)
+    assert torch.equal(Y1[torch.from_numpy(perm).cuda()], Y2)      # a row's result does not depend on where it sits
+    e_max, e_rms = orc.rel_errors(Y1.cpu().numpy(), orc.svdlora_forward(W, f, xv, r2c, sA, sB))
+    assert e_rms <= 2e-5
+    gp.close()
+
+
+def test_w8a8_bit_exact_and_forward(essa, ctx):
+    p = wl.make_projection("t", 448, 200, 16, "int8", layer=8)
+    W, f = oracle_proj(p)
+    gp = gpu_proj(essa, ctx, p)
+    K, R = 4, 131
+    xb, xv = wl.make_x_bf16(R, 448, x_id=6)
+    xv[5] = 0
+    xb[5] = 0
+    xq = torch.empty(R, 448, dtype=torch.int8, device="cuda")
+    xs = torch.empty(R, device="cuda")
+    acc = torch.empty(R, 200, dtype=torch.int32, device="cuda")
+    essa.essa_w8a8_accumulators(ctx, gp, bf16_dev(xb), xq, xs, acc)
+    rq, rs = orc.quantize_rows_int8(xv)
+    assert np.array_equal(xq.cpu().numpy(), rq)
+    assert np.array_equal(xs.cpu().numpy(), rs)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), orc.int8_accumulators(rq, p.Wq))
+    sA, sB = candidate_sigmas(f, K, 0.05)
+    r2c = np.random.default_rng(3).integers(0, K, R).astype(np.int32)
+    Y = torch.empty(R, 200, device="cuda")
+    essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb), to_dev(r2c), to_dev(sA), to_dev(sB), Y, essa.COMPUTE_W8A8)
+    ref = orc.svdlora_forward_w8a8(p.Wq, p.scales, f, xv, r2c, sA, sB)
+    e_max, e_rms = orc.rel_errors(Y.cpu().numpy(), ref)
+    _say("w8a8 fp32 out: max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= 2e-5 and e_max <= 2e-4
+    Yb = torch.empty(R, 200, device="cuda", dtype=torch.bfloat16)
+    essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb), to_dev(r2c), to_dev(sA), to_dev(sB), Yb, essa.COMPUTE_W8A8)
+    e_max, e_rms = orc.rel_errors(bf16_host(Yb), orc.round_to_bf16(ref))
+    assert e_rms <= BF16_RMS and e_max <= BF16_MAX
+    gp.close()
+
+
+def _layer_case(essa, ctx, cfg, layer, n_cands_checked, rows_per_cand_checked, flags=0):
+    """One layer of a configuration at its full shape, q/k/v sharing X and o with its own, grouped launch."""
+    projs = wl.make_layer(cfg.hidden, cfg.kv, cfg.r, cfg.quant, layer)
+    K, R = cfg.K, cfg.R
+    r2c = wl.row2cand_interleaved(K, cfg.rows_per_cand, layer) if cfg.interleaved else wl.row2cand_contiguous(K, cfg.rows_per_cand)
+    xb1, xv1 = wl.make_x_bf16(R, cfg.hidden, x_id=2 * layer)
+    xb2, xv2 = wl.make_x_bf16(R, cfg.hidden, x_id=2 * layer + 1)
+    X1, X2, rd = bf16_dev(xb1), bf16_dev(xb2), to_dev(r2c)
+    gps, items, outs, refs = [], [], [], []
+    cands = list(range(K)) if n_cands_checked >= K else sorted(np.random.default_rng(layer).choice(K, n_cands_checked, replace=False).tolist())
+    rows = np.arange(R) if (n_cands_checked >= K and rows_per_cand_checked >= cfg.rows_per_cand) else sample_rows(r2c, cands, rows_per_cand_checked, seed=layer)
+    for pi, p in enumerate(projs):
+        W, f = oracle_proj(p)
+        sA, sB = candidate_sigmas(f, K, cfg.sigma_step, pert_id=layer * 4 + pi)
+        gp = gpu_proj(essa, ctx, p)
+        Y = torch.empty(R, p.d_out, device="cuda", dtype=torch.bfloat16)
+        X, xv = (X2, xv2) if p.name == "o" else (X1, xv1)
+        items.append((gp, X, rd, to_dev(sA), to_dev(sB), Y))
+        gps.append(gp)
+        outs.append(Y)
+        if flags & essa.COMPUTE_W8A8:
+            ref = orc.svdlora_forward_w8a8(p.Wq, p.scales, f, xv[rows], r2c[rows], sA, sB)
+        else:
+            ref = orc.svdlora_forward_rows(W, f, xv, r2c, sA, sB, rows)
+        refs.append(orc.round_to_bf16(ref))
+        _say("  oracle done for %s.%s (%d rows)" % (cfg.name, p.name, len(rows)))
+    essa.essa_svdlora_forward_group(ctx, items, flags)
+    torch.cuda.synchronize()
+    rows_t = torch.from_numpy(rows).cuda()
+    for p, Y, ref in zip(projs, outs, refs):
+        e_max, e_rms = orc.rel_errors(bf16_host(Y[rows_t]), ref)
+        _say("  %s.%s: max %.3g rms %.3g" % (cfg.name, p.name, e_max, e_rms))
+        assert e_rms <= BF16_RMS and e_max <= BF16_MAX, (p.name, e_max, e_rms)
+        assert torch.isfinite(Y.float()).all()
+    # grouped and single launches agree bit for bit
+    gp, X, rd_, a_, b_, Y = items[1]
+    Y1 = torch.empty_like(Y)
+    essa.essa_svdlora_forward(ctx, gp, X, rd_, a_, b_, Y1, flags)
+    assert torch.equal(Y, Y1)
+    for gp in gps:
+        gp.close()
+
+
+def test_forward_c2_full_layer(essa, ctx):
+    _say("c2: 7B-shaped decode layer, all rows against the oracle")
+    _layer_case(essa, ctx, wl.CONFIGS["c2_7b_decode"], layer=0, n_cands_checked=32, rows_per_cand_checked=8)
+
+
+def test_forward_c2_full_layer_w8a8(essa, ctx):
+    _say("c2 W8A8")
+    _layer_case(essa, ctx, wl.CONFIGS["c2_7b_decode"], layer=1, n_cands_checked=32, rows_per_cand_checked=8, flags=1)
+
+
+def test_forward_c3_prefill_sampled(essa, ctx):
+    _say("c3: 32B-shaped prefill layer, sampled rows of 6 candidates")
+    _layer_case(essa, ctx, wl.CONFIGS["c3_32b_prefill"], layer=0, n_cands_checked=6, rows_per_cand_checked=6)
+
+
+def test_forward_c4_int4_interleaved_sampled(essa, ctx):
+    _say("c4: 72B-shaped int4 decode layer, interleaved rows, sampled candidates")
+    _layer_case(essa, ctx, wl.CONFIGS["c4_72b_decode"], layer=0, n_cands_checked=5, rows_per_cand_checked=4)
+
+
+# ------------------------------------------------------------------------------------------------ reward, ranking, update
+def test_reward_accumulate(essa, ctx):
+    g = np.random.default_rng(4)
+    R, d, K = 300, 96, 7
+    Yb = wl.f32_to_bf16_bits(g.standard_normal((R, d)).astype(np.float32))
+    v = g.standard_normal(d).astype(np.float32)
+    r2c = g.integers(0, K - 1, R).astype(np.int32)          # candidate K-1 has no rows
+    F = torch.zeros(K, device="cuda")
+    essa.essa_reward_accumulate(ctx, bf16_dev(Yb), to_dev(v), to_dev(r2c), F)
+    essa.essa_reward_accumulate(ctx, bf16_dev(Yb), to_dev(v), to_dev(r2c), F)
+    ref = orc.reward_accumulate(np.zeros(K), wl.bf16_bits_to_f32(Yb), v, r2c, K)
+    ref = orc.reward_accumulate(ref, wl.bf16_bits_to_f32(Yb), v, r2c, K)
+    got = F.cpu().numpy()
+    assert math.isnan(got[K - 1]) and math.isnan(ref[K - 1])
+    np.testing.assert_allclose(got[:K - 1], ref[:K - 1], rtol=1e-5, atol=1e-6)
+    Y32 = g.standard_normal((R, d)).astype(np.float32)
+    F = torch.zeros(K, device="cuda")
+    essa.essa_reward_accumulate(ctx, to_dev(Y32), to_dev(v), to_dev(r2c), F)
+    np.testing.assert_allclose(F.cpu().numpy()[:K - 1], orc.reward_accumulate(np.zeros(K), Y32, v, r2c, K)[:K - 1], rtol=1e-5, atol=1e-6)
+
+
+@pytest.mark.parametrize("K", [1, 4, 32, 64, 128, 400, 1024])
+def test_rank_bit_exact(essa, ctx, K):
+    g = np.random.default_rng(K)
+    F = g.integers(0, max(2, K // 3), K).astype(np.float32)      # many ties
+    if K >= 4:
+        F[1] = np.nan
+        F[2] = np.inf
+        F[3] = -np.inf
+    order = torch.empty(K, dtype=torch.int32, device="cuda")
+    essa.essa_rank_rewards(ctx, to_dev(F), order)
+    assert np.array_equal(order.cpu().numpy(), orc.rank_desc_stable(F))
+    F = g.standard_normal(K).astype(np.float32)
+    essa.essa_rank_rewards(ctx, to_dev(F), order)
+    assert np.array_equal(order.cpu().numpy(), orc.rank_desc_stable(F))
+
+
+def _state_errors(exp, ref):
+    out = {}
+    for name in ("m", "p_sigma", "p_c", "C"):
+        out[name] = orc.rel_errors(exp[name], getattr(ref, name))
+    out["sigma"] = abs(exp["sigma"] - ref.sigma) / ref.sigma
+    return out
+
+
+@pytest.mark.parametrize("n,K,gens", [(16, 4, 3), (50, 13, 3), (257, 24, 2), (3584, 64, 2)])
+def test_cmaes_update(essa, ctx, n, K, gens):
+    _say("update n=%d K=%d" % (n, K))
+    Q, d = wl.random_covariance_basis(n, basis_id=1000 + n)
+    g = np.random.default_rng(n)
+    m0 = g.standard_normal(n).astype(np.float32)
+    C0 = (Q.astype(np.float64) * d.astype(np.float64) ** 2) @ Q.astype(np.float64).T
+    C0 = ((C0 + C0.T) / 2).astype(np.float32)
+    cma = essa.CmaState(ctx, n, 0.32, m0)
+    z = np.zeros(n, np.float32)
+    cma.import_blob(essa.CmaState.pack_blob(n, 0, 0.32, m0, z, z, d, C0, Q))
+    st = orc.cma_state_init(n, np.float32(0.32), m0)
+    st.B, st.D, st.C = Q.astype(np.float64), d.astype(np.float64), C0.astype(np.float64)
+    seed = 1
+    for gen in range(gens):
+        seeds = list(range(seed, seed + K))
+        seed += K
+        F = g.standard_normal(K).astype(np.float32)
+        F[0] = F[K - 1]                                        # a tie
+        order = torch.empty(K, dtype=torch.int32, device="cuda")
+        essa.essa_cmaes_update(ctx, cma, seeds_dev(seeds), to_dev(F), order)
+        st, ref_order = orc.cma_update(st, seeds, F)
+        assert np.array_equal(order.cpu().numpy(), ref_order)
+        exp = cma.export()
+        errs = _state_errors(exp, st)
+        _say("  gen %d: %s" % (gen, {k: (("%.2g/%.2g" % v) if isinstance(v, tuple) else "%.2g" % v) for k, v in errs.items()}))
+        assert exp["t"] == st.t
+        for name in ("m", "p_sigma", "p_c", "C"):
+            assert errs[name][1] <= FP32_RMS and errs[name][0] <= FP32_MAX, (name, errs[name])
+        assert errs["sigma"] <= 1e-5
+        assert np.array_equal(exp["C"], exp["C"].T)            # exactly symmetric
+    cma.close()
+
+
+def test_cmaes_update_is_reproducible_and_resumable(essa, ctx):
+    n, K = 96, 10
+    g = np.random.default_rng(5)
+    Fs = [g.standard_normal(K).astype(np.float32) for _ in range(4)]
+
+    def run(import_after=None):
+        cma = essa.CmaState(ctx, n, 0.32, None)
+        for gen in range(4):
+            if import_after is not None and gen == 2:
+                blob = cma.export_blob()
+                cma.close()
+                cma = essa.CmaState(ctx, n, 1.0, None)
+                cma.import_blob(blob)
+            essa.essa_cmaes_update(ctx, cma, seeds_dev(range(gen * K, gen * K + K)), to_dev(Fs[gen]), None)
+        out = cma.export_blob()
+        cma.close()
+        return out
+
+    a, b, c = run(), run(), run(import_after=2)
+    assert a == b          # every worker performs the same update, bit for bit
+    assert a == c          # export -> import -> continue equals the uninterrupted run
+    # NaN rewards rank last and never reach the state
+    cma = essa.CmaState(ctx, n, 0.32, None)
+    F = Fs[0].copy()
+    F[3] = np.nan
+    essa.essa_cmaes_update(ctx, cma, seeds_dev(range(K)), to_dev(F), None)
+    e = cma.export()
+    assert np.isfinite(e["C"]).all() and np.isfinite(e["m"]).all() and math.isfinite(e["sigma"])
+    with pytest.raises(essa.EssaError):
+        cma.import_blob(a[:-4])
+    with pytest.raises(essa.EssaError):
+        essa.essa_cmaes_update(ctx, cma, seeds_dev([1]), to_dev(np.zeros(1, np.float32)), None)
+    cma.close()
+
+
+def test_full_iteration_small(essa, ctx):
+    """A whole generation (configuration 5's structure at a small size): seeds -> theta -> sigma -> all
+    projections -> reward -> update, each stage against the oracle; the update is fed the oracle's rewards
+    on both sides so that a near-tie cannot flip the comparison."""
+    layers, hidden, kv, r, K, rows_per = 2, 256, 64, 8, 6, 10
+    P = layers * 4
+    n = P * 2 * r
+    R = K * rows_per
+    projs = [p for l in range(layers) for p in wl.make_layer(hidden, kv, r, "int8", layer=20 + l)]
+    orcs = [oracle_proj(p) for p in projs]
+    gps = [gpu_proj(essa, ctx, p) for p in projs]
+    sft_A = np.stack([f["S_A"] for _, f in orcs]).astype(np.float32)
+    sft_B = np.stack([f["S_B"] for _, f in orcs]).astype(np.float32)
+    Q, d = wl.random_covariance_basis(n, basis_id=77)
+    d = (d * 0.05).astype(np.float32)
+    cma = essa.CmaState(ctx, n, 0.32, None)
+    C0 = ((Q.astype(np.float64) * d.astype(np.float64) ** 2) @ Q.astype(np.float64).T).astype(np.float32)
+    zero = np.zeros(n, np.float32)
+    cma.import_blob(essa.CmaState.pack_blob(n, 0, 0.32, zero, zero, zero, d, C0, Q))
+    st = orc.cma_state_init(n, np.float32(0.32))
+    st.B, st.D, st.C = Q.astype(np.float64), d.astype(np.float64), C0.astype(np.float64)
+    seeds = list(range(1, K + 1))
+    xb, xv = wl.make_x_bf16(R, hidden, x_id=99)
+    r2c = wl.row2cand_contiguous(K, rows_per)
+    Xd, rd = bf16_dev(xb), to_dev(r2c)
+    # GPU pipeline
+    theta = torch.empty(K, n, device="cuda")
+    essa.essa_sample_candidates(ctx, cma, seeds_dev(seeds), theta, None)
+    sA = torch.empty(K, P, r, device="cuda")
+    sB = torch.empty(K, P, r, device="cuda")
+    essa.essa_theta_to_sigma(ctx, r, to_dev(sft_A), to_dev(sft_B), theta, sA, sB)
+    F = torch.zeros(K, device="cuda")
+    Ys = []
+    for l in range(layers):
+        items = []
+        for pi in range(4):
+            j = l * 4 + pi
+            Y = torch.empty(R, projs[j].d_out, device="cuda", dtype=torch.bfloat16)
+            items.append((gps[j], Xd, rd, sA[:, j, :], sB[:, j, :], Y))
+            Ys.append(Y)
+        essa.essa_svdlora_forward_group(ctx, items)
+        for pi in range(4):
+            j = l * 4 + pi
+            essa.essa_reward_accumulate(ctx, Ys[j], to_dev(wl.reward_vector(projs[j].d_out, 20 + l, pi)), rd, F)
+    # oracle pipeline
+    ref_theta, _ = orc.sample_candidates(np.zeros(n), np.float32(0.32), Q, d, seeds)
+    rA, rB = orc.theta_to_sigma(ref_theta, sft_A, sft_B, 1.0)
+    refF = np.zeros(K)
+    for j, (W, f) in enumerate(orcs):
+        ref = orc.round_to_bf16(orc.svdlora_forward(W, f, xv, r2c, rA[:, j, :], rB[:, j, :]))
+        e_max, e_rms = orc.rel_errors(bf16_host(Ys[j]), ref)
+        assert e_rms <= BF16_RMS and e_max <= BF16_MAX
+        refF = orc.reward_accumulate(refF, ref, wl.reward_vector(projs[j].d_out, 20 + j // 4, j % 4), r2c, K)
+    e_max, e_rms = orc.rel_errors(F.cpu().numpy(), refF)
+    _say("full iteration: reward err max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= 1e-3
+    refF32 = refF.astype(np.float32)
+    essa.essa_cmaes_update(ctx, cma, seeds_dev(seeds), to_dev(refF32), None)
+    st, _ = orc.cma_update(st, seeds, refF32)
+    errs = _state_errors(cma.export(), st)
+    for name in ("m", "p_sigma", "p_c", "C"):
+        assert errs[name][1] <= FP32_RMS and errs[name][0] <= FP32_MAX, (name, errs[name])
+    for gp in gps:
+        gp.close()
+    cma.close()
