@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the ESSA hot path on one MI355X.
+
+Workload (config.workload = c2_7b_decode): Qwen2.5-7B-shaped decode.  One "step" is one generation of the
+whole hot path over one batch: K=32 seeds -> candidates (n = 28*4*2*16 = 3584, dense covariance basis) ->
+singular values -> the q/k/v/o SVD-LoRA projections of 28 distinct layers (int8 per-channel weights, bf16
+activations, r=16, 32 candidates x 8 sequences x 1 token = 256 rows; 822 MB of weights, more than the
+256 MB Infinity Cache) -> synthetic reward -> rank-weighted CMA-ES update.  A candidate-token is one row
+taken through the four projections of one layer, so a step processes 28 * 256 of them.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"w8a16": 2500.0, "w8a8": 5000.0}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--mode", choices=["w8a16", "w8a8"], default="w8a16", help="bf16 MFMA on bf16 activations, or int8 MFMA on per-row quantised ones")
+    ap.add_argument("--layers", type=int, default=28)
+    ap.add_argument("--rows-per-cand", type=int, default=8)
+    ap.add_argument("--forward-only", action="store_true", help="time only the projections (no sampler / reward / update)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import essa_workloads as wl
+    import paper_2507_04453_amd as essa
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(2)
+    cfg = wl.CONFIGS["c2_7b_decode"]
+    hidden, kv, r, K = cfg.hidden, cfg.kv, cfg.r, cfg.K
+    layers, rows_per = args.layers, args.rows_per_cand
+    R = K * rows_per
+    P = layers * 4
+    n = P * 2 * r
+    flags = essa.COMPUTE_W8A8 if args.mode == "w8a8" else 0
+    torch.cuda.set_device(0)
+    ctx = essa.Context(0)
+
+    t0 = time.time()
+    projs, sft_A, sft_B, vecs = [], [], [], []
+    for l in range(layers):
+        for pi, p in enumerate(wl.make_layer(hidden, kv, r, cfg.quant, l)):
+            gp = essa.Projection(ctx, p.Wq, p.scales, None, p.A, p.B, essa.QUANT_INT8_PERCH)
+            a, b = gp.spectrum()
+            projs.append(gp)
+            sft_A.append(a)
+            sft_B.append(b)
+            vecs.append(torch.from_numpy(wl.reward_vector(p.d_out, l, pi)).cuda())
+    log("bench: %d projections set up in %.1f s" % (len(projs), time.time() - t0))
+    sft_A = torch.from_numpy(np.stack(sft_A)).cuda()
+    sft_B = torch.from_numpy(np.stack(sft_B)).cuda()
+
+    def bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+    X1 = bf16(wl.make_x_bf16(R, hidden, 0)[0])
+    X2 = bf16(wl.make_x_bf16(R, hidden, 1)[0])
+    r2c = torch.from_numpy(wl.row2cand_contiguous(K, rows_per)).cuda()
+    Q, d = wl.random_covariance_basis(n, 0)
+    d = (d * 0.05).astype(np.float32)           # offsets of the order of 1% of a singular value
+    cma = essa.CmaState(ctx, n, 0.32, None)
+    C0 = ((Q.astype(np.float64) * d.astype(np.float64) ** 2) @ Q.astype(np.float64).T).astype(np.float32)
+    zero = np.zeros(n, np.float32)
+    blob0 = essa.CmaState.pack_blob(n, 0, 0.32, zero, zero, zero, d, C0, Q)
+    cma.import_blob(blob0)
+    seeds = torch.arange(1, K + 1, dtype=torch.int32, device="cuda")
+    theta = torch.empty(K, n, device="cuda")
+    sA = torch.empty(K, P, r, device="cuda")
+    sB = torch.empty(K, P, r, device="cuda")
+    F = torch.zeros(K, device="cuda")
+    Ys = [torch.empty(R, p.d_out, device="cuda", dtype=torch.bfloat16) for p in projs[:4]]
+    items = []
+    for l in range(layers):
+        it = []
+        for pi in range(4):
+            j = l * 4 + pi
+            it.append((projs[j], X2 if pi == 3 else X1, r2c, sA[:, j, :], sB[:, j, :], Ys[pi]))
+        items.append(it)
+
+    def forward_all(with_reward):
+        for l in range(layers):
+            essa.essa_svdlora_forward_group(ctx, items[l], flags)
+            if with_reward:
+                for pi in range(4):
+                    essa.essa_reward_accumulate(ctx, Ys[pi], vecs[l * 4 + pi], r2c, F)
+
+    def step():
+        if args.forward_only:
+            forward_all(False)
+            return
+        essa.essa_sample_candidates(ctx, cma, seeds, theta, None)
+        essa.essa_theta_to_sigma(ctx, r, sft_A, sft_B, theta, sA, sB)
+        F.zero_()
+        forward_all(True)
+        essa.essa_cmaes_update(ctx, cma, seeds, F, None)
+
+    if args.forward_only:   # sigma must exist
+        essa.essa_sample_candidates(ctx, cma, seeds, theta, None)
+        essa.essa_theta_to_sigma(ctx, r, sft_A, sft_B, theta, sA, sB)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    gemm_ms, gemm_launches = ctx.profile_read()
+    ctx.profile_enable(False)
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = layers * R / (elapsed / args.steps)
+
+    # per-stage times (outside the timed region, events on the library's stream = torch's current stream)
+    def timed(fn, reps=20):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    breakdown = {
+        "forward_28_layers_ms": timed(lambda: forward_all(False), 5),
+        "forward_plus_reward_ms": timed(lambda: forward_all(True), 5),
+        "sample_ms": timed(lambda: essa.essa_sample_candidates(ctx, cma, seeds, theta, None)),
+        "theta_to_sigma_ms": timed(lambda: essa.essa_theta_to_sigma(ctx, r, sft_A, sft_B, theta, sA, sB)),
+        "update_ms": timed(lambda: essa.essa_cmaes_update(ctx, cma, seeds, F, None)),
+    }
+
+    # roofline of the dominant kernel (the fused-dequant MFMA GEMM, one launch per layer)
+    dsum = sum(p.d_out for p in projs[:4])
+    flops_per_launch = 2.0 * R * sum(p.d_out * (p.d_in + r) for p in projs[:4])
+    bytes_per_launch = sum(p.d_out * p.d_in + 4 * p.d_out + 2 * 2 * 16 * p.d_out for p in projs[:4]) \
+        + 2 * R * hidden * (1 if args.mode == "w8a8" else 2) + 2 * R * dsum + 4 * R * 2 * 16 * 2
+    avg_s = (gemm_ms / max(gemm_launches, 1)) * 1e-3
+    t_mfma = flops_per_launch / (MFMA_PEAK_TFLOPS[args.mode] * 1e12)
+    t_hbm = bytes_per_launch / (HBM_PEAK_GBS * 1e9)
+    if t_mfma >= t_hbm:
+        ach = flops_per_launch / avg_s / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_PEAK_TFLOPS[args.mode], "unit": "TFLOP/s", "frac": ach / MFMA_PEAK_TFLOPS[args.mode], "traffic": None}
+    else:
+        ach = bytes_per_launch / avg_s / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
+    roof.update({"kernel": "gemm_mfma_kernel", "avg_launch_us": avg_s * 1e6, "launches": gemm_launches,
+                 "flops_per_launch": flops_per_launch, "bytes_per_launch": bytes_per_launch,
+                 "achieved_GBs": bytes_per_launch / avg_s / 1e9, "achieved_TFLOPs": flops_per_launch / avg_s / 1e12})
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, R, rows_per, args.mode)
+
+    out = {
+        "metric": "candidate-tokens/s through batched SVD-LoRA projections", "value": value, "unit": "candidate-tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if args.mode == "w8a16" else "int8", "data": "synthetic",
+        "config": {"workload": "c2_7b_decode", "layers": layers, "hidden": hidden, "kv": kv, "rank": r, "population": K,
+                   "rows": R, "weights": "int8 per-channel", "activations": "bf16", "mode": args.mode,
+                   "step": "forward only" if args.forward_only else "sample + sigma + %d layers x (q,k,v,o) + reward + update" % layers},
+        "roofline": roof, "cpu_baseline": cpu, "breakdown_ms": breakdown,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(cfg, R, rows_per, mode):
+    """The oracle as it stands, timed on this machine's host cores on one layer of the same workload."""
+    import numpy as np
+
+    import essa_workloads as wl
+    import oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    K = cfg.K
+    projs = wl.make_layer(cfg.hidden, cfg.kv, cfg.r, cfg.quant, 0)
+    xv1 = wl.make_x_bf16(R, cfg.hidden, 0)[1]
+    xv2 = wl.make_x_bf16(R, cfg.hidden, 1)[1]
+    r2c = wl.row2cand_contiguous(K, rows_per)
+    prepared = []
+    for pi, p in enumerate(projs):      # set-up (SVD, dequantisation) is not timed, as on the GPU side
+        W = orc.dequant_int8(p.Wq, p.scales)
+        f = orc.thin_svd_factors(p.A, p.B)
+        dA, dB = wl.sigma_perturbation(K, 1, cfg.r, cfg.sigma_step, pi)
+        prepared.append((p, W, f, (f["S_A"][None] + dA[:, 0]), (f["S_B"][None] + dB[:, 0])))
+    t0 = time.perf_counter()
+    for p, W, f, sA, sB in prepared:
+        xv = xv2 if p.name == "o" else xv1
+        if mode == "w8a8":
+            orc.svdlora_forward_w8a8(p.Wq, p.scales, f, xv, r2c, sA, sB)
+        else:
+            orc.svdlora_forward(W, f, xv, r2c, sA, sB)
+    dt = time.perf_counter() - t0
+    return {"value": R / dt, "unit": "candidate-tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "one layer (q,k,v,o) of c2_7b_decode, all %d rows, candidate weights W + B_k A_k formed explicitly in fp64; %.2f s" % (R, dt)}
+
+
+if __name__ == "__main__":
+    main()

@@ -66,6 +66,12 @@ const char* essa_version(void);
 /* Blocks until everything queued on the context's stream has finished. */
 essa_status essa_synchronize(essa_ctx* ctx);
 
+/* Measurement aid: while enabled, every launch of the forward's GEMM kernel is bracketed by HIP
+ * events on the context's stream.  essa_profile_read synchronises the stream, returns the summed
+ * kernel time in milliseconds and the number of launches since the last read, and resets both. */
+essa_status essa_profile_enable(essa_ctx* ctx, int on);
+essa_status essa_profile_read(essa_ctx* ctx, double* total_ms, int* launches);
+
 /* ---------------------------------------------------------------------------------------------
  * One adapted projection  (paper: Method, "LoRA + SVD parameterization"; Algorithm 1, SVD-init step)
  *

@@ -49,12 +49,53 @@ extern "C" void essa_destroy(essa_ctx* ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->ws) (void)hipFree(ctx->ws);
+    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
     delete ctx;
 }
 
 extern "C" essa_status essa_synchronize(essa_ctx* ctx) {
     if (!ctx) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_synchronize: ctx is NULL");
     ESSA_HIP(hipStreamSynchronize(ctx->stream));
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_profile_enable(essa_ctx* ctx, int on) {
+    if (!ctx) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_profile_enable: ctx is NULL");
+    ESSA_HIP(hipSetDevice(ctx->device));
+    ESSA_HIP(hipStreamSynchronize(ctx->stream));
+    ctx->profiling = on != 0;
+    ctx->ev_used = 0;
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_profile_read(essa_ctx* ctx, double* total_ms, int* launches) {
+    if (!ctx || !total_ms || !launches) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_profile_read: NULL argument");
+    ESSA_HIP(hipSetDevice(ctx->device));
+    ESSA_HIP(hipStreamSynchronize(ctx->stream));
+    double sum = 0;
+    for (size_t i = 0; i + 1 < ctx->ev_used; i += 2) {
+        float ms = 0.f;
+        ESSA_HIP(hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1]));
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = (int)(ctx->ev_used / 2);
+    ctx->ev_used = 0;
+    return ESSA_OK;
+}
+
+// next (start, stop) event pair while profiling, else (null, null)
+static essa_status next_events(essa_ctx* ctx, hipEvent_t* a, hipEvent_t* b) {
+    *a = *b = nullptr;
+    if (!ctx->profiling) return ESSA_OK;
+    while (ctx->ev.size() < ctx->ev_used + 2) {
+        hipEvent_t e;
+        ESSA_HIP(hipEventCreate(&e));
+        ctx->ev.push_back(e);
+    }
+    *a = ctx->ev[ctx->ev_used];
+    *b = ctx->ev[ctx->ev_used + 1];
+    ctx->ev_used += 2;
     return ESSA_OK;
 }
 
@@ -410,7 +451,9 @@ extern "C" essa_status essa_svdlora_forward_group(essa_ctx* ctx, const essa_fwd_
     std::vector<essa_k::fwd_item> ks;
     ESSA_TRY(plan_items(ctx, items, n_items, x_dtype, y_dtype, flags, ks, "essa_svdlora_forward_group"));
     if (ks.empty()) return ESSA_OK;
-    ESSA_HIP(essa_k::forward_group(ctx->stream, ks.data(), (int)ks.size(), x_dtype, y_dtype, flags));
+    hipEvent_t e0, e1;
+    ESSA_TRY(next_events(ctx, &e0, &e1));
+    ESSA_HIP(essa_k::forward_group(ctx->stream, ks.data(), (int)ks.size(), x_dtype, y_dtype, flags, e0, e1));
     return ESSA_OK;
 }
 
@@ -423,7 +466,9 @@ extern "C" essa_status essa_svdlora_forward(essa_ctx* ctx, const essa_proj* proj
     ESSA_HIP(hipSetDevice(ctx->device));
     ESSA_TRY(plan_items(ctx, &it, 1, x_dtype, y_dtype, flags, ks, "essa_svdlora_forward"));
     if (ks.empty()) return ESSA_OK;
-    ESSA_HIP(essa_k::forward_group(ctx->stream, ks.data(), 1, x_dtype, y_dtype, flags));
+    hipEvent_t e0, e1;
+    ESSA_TRY(next_events(ctx, &e0, &e1));
+    ESSA_HIP(essa_k::forward_group(ctx->stream, ks.data(), 1, x_dtype, y_dtype, flags, e0, e1));
     return ESSA_OK;
 }
 

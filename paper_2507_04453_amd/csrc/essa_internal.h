@@ -30,6 +30,9 @@ struct essa_ctx {
     hipStream_t stream = nullptr;
     void* ws = nullptr;        // scratch, grown on demand
     size_t ws_bytes = 0;
+    bool profiling = false;    // bracket GEMM launches with events
+    std::vector<hipEvent_t> ev;   // pairs (start, stop)
+    size_t ev_used = 0;
 };
 essa_status essa_ws_reserve(essa_ctx* ctx, size_t bytes);
 
@@ -126,7 +129,7 @@ struct fwd_item {              // one projection of a grouped forward, device po
     float* xscale;             // [R]      (W8A8)
 };
 hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int x_dtype, int y_dtype,
-                         unsigned flags);
+                         unsigned flags, hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t w8a8_accumulators(hipStream_t st, const fwd_item& it, int x_dtype, int32_t* acc_out);
 hipError_t reward_accumulate(hipStream_t st, const void* Y, int y_dtype, int R, int d_out, const float* v,
                              const int32_t* row2cand, int K, float* rowdot /*[R] scratch*/, float* F);

@@ -507,7 +507,8 @@ static void launch_mfma(hipStream_t st, fwd_args& a, int n_items, int mode, int 
 #undef ESSA_LAUNCH
 }
 
-hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int x_dtype, int y_dtype, unsigned flags) {
+hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int x_dtype, int y_dtype, unsigned flags,
+                         hipEvent_t ev_start, hipEvent_t ev_stop) {
     // items are grouped by the kernel family that takes them; within a family they share one launch
     fwd_args a{};
     a.flags = flags;
@@ -552,10 +553,12 @@ hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int
         } else ag.it[ag.n_items++] = items[g];
     }
     if (am.n_items) {
+        if (ev_start) (void)hipEventRecord(ev_start, st);
         long long tiles128 = 0;
         for (int g = 0; g < am.n_items; ++g) tiles128 += (long long)((am.it[g].R + 127) / 128) * ((am.it[g].d_out + 127) / 128);
         if (tiles128 >= 512) launch_mfma<128, 128>(st, am, am.n_items, mode, y_dtype);
         else launch_mfma<64, 64>(st, am, am.n_items, mode, y_dtype);
+        if (ev_stop) (void)hipEventRecord(ev_stop, st);
     }
     if (ag.n_items) {
         int total = 0;

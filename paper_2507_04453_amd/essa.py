@@ -25,6 +25,7 @@ MAX_GROUP = 8
 
 EXPORTED_SYMBOLS = [
     "essa_create", "essa_destroy", "essa_last_error", "essa_version", "essa_synchronize",
+    "essa_profile_enable", "essa_profile_read",
     "essa_proj_create", "essa_proj_destroy", "essa_proj_spectrum",
     "essa_cma_create", "essa_cma_destroy", "essa_cma_set_basis", "essa_cma_export", "essa_cma_import",
     "essa_sample_candidates", "essa_philox_words", "essa_theta_to_sigma",
@@ -63,6 +64,8 @@ def _load():
         "essa_last_error": (C.c_char_p, []),
         "essa_version": (C.c_char_p, []),
         "essa_synchronize": (i32, [vp]),
+        "essa_profile_enable": (i32, [vp, i32]),
+        "essa_profile_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(i32)]),
         "essa_proj_create": (i32, [vp, C.POINTER(_ProjDesc), C.POINTER(vp)]),
         "essa_proj_destroy": (None, [vp]),
         "essa_proj_spectrum": (i32, [vp, vp, vp]),
@@ -138,6 +141,15 @@ class Context:
 
     def synchronize(self):
         _check(lib.essa_synchronize(self._h))
+
+    def profile_enable(self, on: bool):
+        _check(lib.essa_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self):
+        """(summed GEMM-kernel milliseconds, launches) since the last read."""
+        ms, cnt = C.c_double(0), C.c_int(0)
+        _check(lib.essa_profile_read(self._h, C.byref(ms), C.byref(cnt)))
+        return ms.value, cnt.value
 
     def close(self):
         if self._h:
