@@ -51,6 +51,7 @@ typedef enum {
 #define ESSA_COMPUTE_W8A8 0x1u /* int8 x int8 -> int32 MFMA on per-row quantised activations (int8 weights only) */
 #define ESSA_LORA_ONLY 0x2u    /* test hook: Y = B_k A_k x only                                       */
 #define ESSA_BASE_ONLY 0x4u    /* test hook: Y = W_deq x only                                         */
+#define ESSA_COMPUTE_BF16 0x8u /* exact bf16 products on the bf16 MFMA instead of the default int8-limb path   */
 
 /* ---------------------------------------------------------------------------------------------
  * Context
@@ -160,9 +161,12 @@ essa_status essa_theta_to_sigma(essa_ctx* ctx, int P, int r, int n_top, const fl
  *   sigmaA/B   DEVICE float, candidate k's r values at sigmaX + k * sigma_stride (absolute singular
  *              values, not offsets)
  *   Y          DEVICE [R, d_out], y_dtype, written in full
- * Arithmetic: bf16 X -> bf16 MFMA with fp32 accumulation, weights exact; fp32 X -> fp32 throughout.
- * With ESSA_COMPUTE_W8A8 the base term uses x quantised per row (amax/127, round to nearest even)
- * in an int8 MFMA with exact int32 accumulation; the LoRA term still sees the unquantised x.
+ * Arithmetic: fp32 X -> fp32 throughout.  bf16 X with int8 weights (default): each row of x is put in
+ * 15-bit fixed point relative to its largest entry (x ~ delta_i (128 hi + lo), two int8 limbs, error at most
+ * amax_i / 32766 per entry) and the base term runs on the int8 MFMA with exact int32 accumulation, one pass per
+ * limb; ESSA_COMPUTE_BF16 selects exact bf16 products on the bf16 MFMA (fp32 accumulation) instead, which is
+ * also what 4-bit weights use.  With ESSA_COMPUTE_W8A8 the base term uses x quantised per row to one int8
+ * (amax/127, round to nearest even).  The LoRA term always sees the unquantised x.
  * R = 0 is a no-op.
  * ------------------------------------------------------------------------------------------- */
 essa_status essa_svdlora_forward(essa_ctx* ctx, const essa_proj* proj, const void* X, int x_dtype, int R,

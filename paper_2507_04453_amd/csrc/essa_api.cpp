@@ -153,7 +153,7 @@ extern "C" void essa_proj_destroy(essa_proj* p) {
     if (!p) return;
     (void)hipSetDevice(p->device);
     (void)hipDeviceSynchronize();
-    void* ptrs[] = {p->Wq, p->scale, p->zero, p->VA32, p->VA16, p->UB32, p->UB16, p->M};
+    void* ptrs[] = {p->Wq, p->scale, p->zero, p->VA32, p->VA16, p->UB32, p->UB16, p->M, p->Wt, p->VAp};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
     delete p;
@@ -227,11 +227,41 @@ extern "C" essa_status essa_proj_create(essa_ctx* ctx, const essa_proj_desc* d, 
     ESSA_TRY(upload(&p->UB32, UB32.data(), UB32.size()));
     ESSA_TRY(upload(&p->UB16, UB16.data(), UB16.size()));
 
+    {   // V_A^T as bf16 heads and tails, for the MFMA down-projection
+        std::vector<uint16_t> VAp((size_t)2 * rp * din, 0);
+        for (int i = 0; i < din; ++i)
+            for (int j = 0; j < r; ++j) {
+                const float v = (float)VA[(size_t)i * r + j];
+                const uint16_t hi = f32_to_bf16_rne(v);
+                uint32_t hb = (uint32_t)hi << 16;
+                float hf;
+                std::memcpy(&hf, &hb, 4);
+                VAp[(size_t)j * din + i] = hi;
+                VAp[(size_t)(rp + j) * din + i] = f32_to_bf16_rne(v - hf);
+            }
+        ESSA_TRY(upload(&p->VAp, VAp.data(), VAp.size()));
+    }
     if (d->quant == ESSA_QUANT_INT8_PERCH) {
         int8_t* w = nullptr;
         ESSA_TRY(upload(&w, (const int8_t*)d->Wq, (size_t)dout * din));
         p->Wq = w;
         ESSA_TRY(upload(&p->scale, (const float*)d->scales, (size_t)dout));
+        // tiled copy: 1 KB blocks of 32 channels x 32 k, laid out as the int8 MFMA wants its operand
+        p->d_in_pad = (din + 511) / 512 * 512;   // four K tiles of 128: the GEMM's unrolled pipeline
+        p->n_blocks = (dout + 31) / 32;
+        const int kch = p->d_in_pad / 32;
+        std::vector<int8_t> Wt((size_t)p->n_blocks * kch * 1024, 0);
+        const int8_t* src = (const int8_t*)d->Wq;
+        for (int nb = 0; nb < p->n_blocks; ++nb)
+            for (int n = 0; n < 32; ++n) {
+                const int o = nb * 32 + n;
+                if (o >= dout) continue;
+                for (int k = 0; k < din; ++k) {
+                    const int kc = k >> 5, hh = (k >> 4) & 1, j = k & 15;
+                    Wt[((size_t)kc * p->n_blocks + nb) * 1024 + (size_t)(hh * 32 + n) * 16 + j] = src[(size_t)o * din + k];
+                }
+            }
+        ESSA_TRY(upload(&p->Wt, Wt.data(), Wt.size()));
     } else {
         p->groups = din / 128;
         uint8_t* w = nullptr;
@@ -398,7 +428,7 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
                               unsigned flags, std::vector<essa_k::fwd_item>& out, const char* who) {
     if (x_dtype != ESSA_F32 && x_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: x_dtype %d", who, x_dtype);
     if (y_dtype != ESSA_F32 && y_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: y_dtype %d", who, y_dtype);
-    if (flags & ~(ESSA_COMPUTE_W8A8 | ESSA_LORA_ONLY | ESSA_BASE_ONLY)) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: unknown flag bits 0x%x", who, flags);
+    if (flags & ~(ESSA_COMPUTE_W8A8 | ESSA_LORA_ONLY | ESSA_BASE_ONLY | ESSA_COMPUTE_BF16)) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: unknown flag bits 0x%x", who, flags);
     if ((flags & ESSA_LORA_ONLY) && (flags & ESSA_BASE_ONLY)) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: LORA_ONLY and BASE_ONLY exclude each other", who);
     size_t total = 0;
     out.clear();
@@ -423,10 +453,12 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
         k.d_in = p->d_in; k.d_out = p->d_out; k.r = p->r; k.rp = p->rp; k.quant = p->quant; k.groups = p->groups;
         k.Wq = p->Wq; k.scale = p->scale; k.zero = p->zero; k.VA32 = p->VA32; k.VA16 = p->VA16;
         k.UB32 = p->UB32; k.UB16 = p->UB16; k.M = p->M;
+        k.Wt = p->Wt; k.VAp = p->VAp; k.d_in_pad = p->d_in_pad; k.n_blocks = p->n_blocks;
         out.push_back(k);
         const size_t R = it.R;
         total += align256(R * p->rp * 4) + align256(R * p->rp * 4) + align256(R * (p->groups > 0 ? p->groups : 1) * 4);
         if (flags & ESSA_COMPUTE_W8A8) total += align256(R * (size_t)p->d_in) + align256(R * 4);
+        if (p->Wt) total += 2 * align256((R + 255) / 256 * 256 * (size_t)p->d_in_pad) + align256(R * 4);
     }
     ESSA_TRY(essa_ws_reserve(ctx, total));
     char* w = (char*)ctx->ws;
@@ -439,7 +471,50 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
             k.Xq = (int8_t*)w; w += align256(R * (size_t)k.d_in);
             k.xscale = (float*)w; w += align256(R * 4);
         }
+        if (k.Wt) {
+            // items reading the same X share one set of limbs; the first of them quantises
+            const essa_k::fwd_item* first = nullptr;
+            for (auto& o : out) {
+                if (&o == &k) break;
+                if (o.Wt && o.X == k.X && o.R == k.R && o.d_in == k.d_in) { first = &o; break; }
+            }
+            if (first) {
+                k.Xh = first->Xh; k.Xl = first->Xl; k.xdelta = first->xdelta; k.x_owner = 0;
+            } else {
+                const size_t limb = align256((R + 255) / 256 * 256 * (size_t)k.d_in_pad);
+                k.Xh = (int8_t*)w; w += limb;
+                k.Xl = (int8_t*)w; w += limb;
+                k.xdelta = (float*)w; w += align256(R * 4);
+                k.x_owner = 1;
+            }
+        }
     }
+    return ESSA_OK;
+}
+
+// int8 weights, bf16 activations, 16-byte rows: the int8-limb kernels take the item
+static bool takes_stream(const essa_k::fwd_item& k, int x_dtype, unsigned flags) {
+    return k.Wt && x_dtype == ESSA_BF16 && k.d_in % 16 == 0 && !(flags & ESSA_COMPUTE_BF16) &&
+           ((uintptr_t)k.X & 15) == 0;
+}
+
+static essa_status run_items(essa_ctx* ctx, std::vector<essa_k::fwd_item>& ks, int x_dtype, int y_dtype, unsigned flags) {
+    std::vector<essa_k::fwd_item> fast, rest;
+    for (auto& k : ks) (takes_stream(k, x_dtype, flags) ? fast : rest).push_back(k);
+    // an item whose limbs were to be produced by an item that went the other way quantises for itself
+    for (size_t i = 0; i < fast.size(); ++i) {
+        if (fast[i].x_owner) continue;
+        bool found = false;
+        for (size_t j = 0; j < i; ++j) found = found || (fast[j].x_owner && fast[j].Xh == fast[i].Xh);
+        if (!found) fast[i].x_owner = 1;
+    }
+    hipEvent_t e0, e1;
+    ESSA_TRY(next_events(ctx, &e0, &e1));
+    const unsigned kflags = flags & ~ESSA_COMPUTE_BF16;
+    if (!fast.empty()) ESSA_HIP(essa_k::forward_stream(ctx->stream, fast.data(), (int)fast.size(), y_dtype, kflags, e0, e1));
+    if (!rest.empty())
+        ESSA_HIP(essa_k::forward_group(ctx->stream, rest.data(), (int)rest.size(), x_dtype, y_dtype, kflags,
+                                       fast.empty() ? e0 : nullptr, fast.empty() ? e1 : nullptr));
     return ESSA_OK;
 }
 
@@ -451,10 +526,7 @@ extern "C" essa_status essa_svdlora_forward_group(essa_ctx* ctx, const essa_fwd_
     std::vector<essa_k::fwd_item> ks;
     ESSA_TRY(plan_items(ctx, items, n_items, x_dtype, y_dtype, flags, ks, "essa_svdlora_forward_group"));
     if (ks.empty()) return ESSA_OK;
-    hipEvent_t e0, e1;
-    ESSA_TRY(next_events(ctx, &e0, &e1));
-    ESSA_HIP(essa_k::forward_group(ctx->stream, ks.data(), (int)ks.size(), x_dtype, y_dtype, flags, e0, e1));
-    return ESSA_OK;
+    return run_items(ctx, ks, x_dtype, y_dtype, flags);
 }
 
 extern "C" essa_status essa_svdlora_forward(essa_ctx* ctx, const essa_proj* proj, const void* X, int x_dtype, int R,
@@ -466,10 +538,7 @@ extern "C" essa_status essa_svdlora_forward(essa_ctx* ctx, const essa_proj* proj
     ESSA_HIP(hipSetDevice(ctx->device));
     ESSA_TRY(plan_items(ctx, &it, 1, x_dtype, y_dtype, flags, ks, "essa_svdlora_forward"));
     if (ks.empty()) return ESSA_OK;
-    hipEvent_t e0, e1;
-    ESSA_TRY(next_events(ctx, &e0, &e1));
-    ESSA_HIP(essa_k::forward_group(ctx->stream, ks.data(), 1, x_dtype, y_dtype, flags, e0, e1));
-    return ESSA_OK;
+    return run_items(ctx, ks, x_dtype, y_dtype, flags);
 }
 
 extern "C" essa_status essa_w8a8_accumulators(essa_ctx* ctx, const essa_proj* proj, const void* X, int x_dtype, int R,
@@ -483,6 +552,19 @@ extern "C" essa_status essa_w8a8_accumulators(essa_ctx* ctx, const essa_proj* pr
     k.X = X; k.R = R; k.K = 1;
     k.d_in = proj->d_in; k.d_out = proj->d_out; k.r = proj->r; k.rp = proj->rp; k.quant = proj->quant;
     k.Wq = proj->Wq; k.scale = proj->scale;
+    if (proj->d_in % 16 == 0 && ((uintptr_t)X & 15) == 0) {
+        // the production int8 kernel, one limb, dumping its accumulators
+        k.Wt = proj->Wt; k.d_in_pad = proj->d_in_pad; k.n_blocks = proj->n_blocks;
+        const size_t limb = align256((size_t)(R + 255) / 256 * 256 * (size_t)k.d_in_pad);
+        ESSA_TRY(essa_ws_reserve(ctx, 2 * limb));
+        k.Xh = (int8_t*)ctx->ws;
+        k.Xl = k.Xh + limb;
+        k.xdelta = xscale_out;
+        ESSA_HIP(essa_k::w8a8_accumulators_stream(ctx->stream, k, acc_out));
+        ESSA_HIP(hipMemcpy2DAsync(xq_out, (size_t)k.d_in, k.Xh, (size_t)k.d_in_pad, (size_t)k.d_in, (size_t)R,
+                                  hipMemcpyDeviceToDevice, ctx->stream));
+        return ESSA_OK;
+    }
     k.Xq = xq_out; k.xscale = xscale_out;
     ESSA_HIP(essa_k::w8a8_accumulators(ctx->stream, k, x_dtype, acc_out));
     return ESSA_OK;

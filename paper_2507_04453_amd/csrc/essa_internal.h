@@ -52,6 +52,11 @@ struct essa_proj {
     float* UB32 = nullptr;     // [d_out, rp]
     uint16_t* UB16 = nullptr;  // [d_out, 2, rp]  bf16 head and tail of U_B
     float* M = nullptr;        // [rp, rp]     V_B^T U_A, zero padded
+    // fast path (int8 weights): weights tiled for direct-to-register MFMA operand loads, and V_A^T as bf16
+    int8_t* Wt = nullptr;      // [d_in_pad/32][n_blocks][2][32][16]: block (kc,nb), half h, channel n, 16 consecutive k
+    int d_in_pad = 0;          // d_in rounded up to 512 (zero weights beyond d_in)
+    int n_blocks = 0;          // ceil(d_out / 32)
+    uint16_t* VAp = nullptr;   // [2*rp, d_in] bf16: rows 0..rp-1 heads of V_A's columns, rows rp..2rp-1 their tails
     std::vector<float> sA, sB; // own singular values, host copies
 };
 
@@ -127,10 +132,22 @@ struct fwd_item {              // one projection of a grouped forward, device po
     float* xsum;               // [R, max(groups,1)] group sums of x (int4) / unused
     int8_t* Xq;                // [R, d_in] (W8A8)
     float* xscale;             // [R]      (W8A8)
+    // fast path
+    const int8_t* Wt;
+    const uint16_t* VAp;
+    int d_in_pad, n_blocks;
+    int8_t* Xh;                // [R rounded up to 256, d_in_pad] high limb (or the single int8 code)
+    int8_t* Xl;                // same, low limb
+    float* xdelta;             // [R] value of one unit of the fixed-point row
+    int x_owner;               // 1: this item's rows are quantised by the prep kernel (first user of that X)
 };
 hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int x_dtype, int y_dtype,
                          unsigned flags, hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t w8a8_accumulators(hipStream_t st, const fwd_item& it, int x_dtype, int32_t* acc_out);
+// fast path for int8 weights x bf16 activations (kernels_stream.hip)
+hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, int y_dtype, unsigned flags,
+                          hipEvent_t ev_start, hipEvent_t ev_stop);
+hipError_t w8a8_accumulators_stream(hipStream_t st, const fwd_item& it, int32_t* acc_out);
 hipError_t reward_accumulate(hipStream_t st, const void* Y, int y_dtype, int R, int d_out, const float* v,
                              const int32_t* row2cand, int K, float* rowdot /*[R] scratch*/, float* F);
 }  // namespace essa_k

@@ -1,0 +1,604 @@
+// Fast path of the population-batched forward for int8 base weights and bf16 activations
+// (paper: Algorithm 1, reconstruction step + inference pass; see kernels_forward.hip for the algebra).
+//
+// Idea: the int8 weights never leave the integer domain.  Each activation row is re-expressed in
+// 15-bit fixed point relative to its own largest entry, x ~ delta_i * (128 * hi + lo) with two int8
+// limbs, and the base product runs on the int8 MFMA (exact int32 accumulation, one pass per limb):
+//     W_deq x_i = delta_i * s_o * (128 * <hi_i, q_o> + <lo_i, q_o>).
+// There is no weight conversion at all; every weight byte is loaded from HBM straight into the MFMA
+// operand registers of the one wave that owns its 32 output channels (pre-tiled layout, 1 KB
+// contiguous per load instruction, k-chunk major), while the activation limbs of all the rows of the tile are staged
+// through LDS and shared by the four waves.  With one limb (ESSA_COMPUTE_W8A8) the same kernel is the
+// plain W8A8 mode.  The rank-r term is added by bf16 head+tail MFMA steps in the epilogue.
+#include "essa_internal.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(16))) int i32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+#ifdef EXP_TIMING
+__device__ unsigned long long essa_dbg[8 * 1024];
+extern "C" void essa_dbg_read(unsigned long long* out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(essa_dbg), sizeof(essa_dbg)); }
+#define TSTAMP(i) if (lane == 0 && wave == 0) essa_dbg[blockIdx.x * 8 + (i)] = __builtin_amdgcn_s_memtime();
+#else
+#define TSTAMP(i)
+#endif
+
+namespace {
+
+using essa_k::fwd_item;
+
+struct stream_args {
+    fwd_item it[ESSA_MAX_GROUP];
+    int tile_start[ESSA_MAX_GROUP + 1];    // GEMM tiles per item (prefix sums)
+    int quant_start[ESSA_MAX_GROUP + 1];   // prep kernel: rows to quantise per item (0 for items sharing an X)
+    int lora_start[ESSA_MAX_GROUP + 1];    // prep kernel: 32-row blocks per item
+    int n_items;
+    unsigned flags;
+    int limbs;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ------------------------------------------------------------------------------------------------
+// prep kernel (1024 threads): two kinds of workgroups in one launch.
+//  (a) quantise four activation rows into limbs, one row per 256 threads (once per distinct X of the group);
+//  (b) for one item and 32 rows: t = V_A^T x by bf16 MFMA against the head+tail copy of V_A -- the 16 waves
+//      split K and their partial tiles are summed through LDS in a fixed order -- then
+//      u = sB_c * (M (sA_c * t)), stored as bf16 head+tail for the GEMM epilogue.
+// ------------------------------------------------------------------------------------------------
+constexpr int PREP_NT = 1024;
+
+__global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
+    __shared__ __attribute__((aligned(16))) float part[8][2][16][64];   // lora role: partial tiles of 8 waves (64 KB)
+    __shared__ float tvec[32][33];
+    __shared__ float wred[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.x;
+    const int n_qblocks = a.quant_start[a.n_items];
+    if (b < n_qblocks) {
+        // ---- (a) row quantisation: this 256-thread group takes row 4*b' + grp of its item ---------------
+        int g = 0;
+        while (b >= a.quant_start[g + 1]) ++g;
+        const fwd_item& it = a.it[g];
+        const int grp = tid >> 8, t256 = tid & 255;
+        const int i = (b - a.quant_start[g]) * 4 + grp;
+        const bool live = i < it.R;
+        const int din = it.d_in, dpad = it.d_in_pad;
+        const u32x4* xrow = reinterpret_cast<const u32x4*>((const uint16_t*)it.X + (size_t)(live ? i : 0) * din);
+        const int nch = din / 8;                          // 16-byte chunks of 8 bf16
+        float m = 0.f;
+        for (int c = t256; c < nch; c += 256) {
+            const u32x4 v = xrow[c];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                m = fmaxf(m, fabsf(__uint_as_float(v[e] << 16)));
+                m = fmaxf(m, fabsf(__uint_as_float(v[e] & 0xffff0000u)));
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+        if (lane == 0) wred[wave] = m;
+        __syncthreads();
+        const float amax = fmaxf(fmaxf(wred[4 * grp], wred[4 * grp + 1]), fmaxf(wred[4 * grp + 2], wred[4 * grp + 3]));
+        const float top = a.limbs == 2 ? 16383.0f : 127.0f;
+        const float inv = amax > 0.f ? top / amax : 0.f;
+        if (!live) return;
+        uint2* hrow = reinterpret_cast<uint2*>(it.Xh + (size_t)i * dpad);
+        uint2* lrow = reinterpret_cast<uint2*>(it.Xl + (size_t)i * dpad);
+        for (int c = t256; c < dpad / 8; c += 256) {
+            uint32_t hi[2] = {0, 0}, lo[2] = {0, 0};
+            if (c < nch) {
+                const u32x4 v = xrow[c];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = (e & 1) ? __uint_as_float(v[e >> 1] & 0xffff0000u) : __uint_as_float(v[e >> 1] << 16);
+                    float q = rintf(x * inv);
+                    q = fminf(fmaxf(q, -top), top);
+                    const int qi = (int)q;
+                    if (a.limbs == 2) {
+                        hi[e >> 2] |= (uint32_t)((qi >> 7) & 0xff) << (8 * (e & 3));   // arithmetic shift: hi in [-128,127]
+                        lo[e >> 2] |= (uint32_t)(qi & 127) << (8 * (e & 3));           // lo in [0,127]
+                    } else {
+                        hi[e >> 2] |= (uint32_t)(qi & 0xff) << (8 * (e & 3));
+                    }
+                }
+            }
+            hrow[c] = make_uint2(hi[0], hi[1]);
+            if (a.limbs == 2) lrow[c] = make_uint2(lo[0], lo[1]);
+        }
+        if (t256 == 0) it.xdelta[i] = amax > 0.f ? amax / top : 0.f;
+        return;
+    }
+    // ---- (b) rank-space vector u for 32 rows of one item ------------------------------------------
+    const int lb = b - n_qblocks;
+    int g = 0;
+    while (lb >= a.lora_start[g + 1]) ++g;
+    const fwd_item& it = a.it[g];
+    const int r0 = (lb - a.lora_start[g]) * 32;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int din = it.d_in, rp = it.rp, nbv = rp / 16, R = it.R;
+    const int arow = min(r0 + l32, R - 1);
+    const uint16_t* xp = (const uint16_t*)it.X + (size_t)arow * din + 8 * h;
+    const uint16_t* vp0 = it.VAp + (size_t)l32 * din + 8 * h;
+    const uint16_t* vp1 = it.VAp + (size_t)(32 + l32) * din + 8 * h;
+    f32x16 acc0 = {0}, acc1 = {0};
+    const int ksteps = din / 16;
+    if (!(a.flags & ESSA_BASE_ONLY)) {
+        // wave w takes k steps w, w+16, ...; four steps' loads are issued before their MFMAs
+        for (int ks0 = wave; ks0 < ksteps; ks0 += 64) {
+            u32x4 xa[4], v0[4], v1[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int ks = ks0 + 16 * u;
+                xa[u] = v0[u] = v1[u] = (u32x4){0, 0, 0, 0};
+                if (ks < ksteps) {
+                    xa[u] = *reinterpret_cast<const u32x4*>(xp + ks * 16);
+                    v0[u] = *reinterpret_cast<const u32x4*>(vp0 + ks * 16);
+                    if (nbv == 2) v1[u] = *reinterpret_cast<const u32x4*>(vp1 + ks * 16);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v0[u]), acc0, 0, 0, 0);
+                if (nbv == 2)
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v1[u]), acc1, 0, 0, 0);
+            }
+        }
+    }
+    // 16 partial tiles -> 8 -> t, always in the same order
+    if (wave >= 8) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            part[wave - 8][0][q][lane] = acc0[q];
+            part[wave - 8][1][q][lane] = acc1[q];
+        }
+    }
+    __syncthreads();
+    if (wave < 8) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            acc0[q] += part[wave][0][q][lane];
+            acc1[q] += part[wave][1][q][lane];
+        }
+    }
+    __syncthreads();
+    if (wave < 8) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            part[wave][0][q][lane] = acc0[q];
+            part[wave][1][q][lane] = acc1[q];
+        }
+    }
+    __syncthreads();
+    // t[row][j] = head part + tail part
+    for (int idx = tid; idx < 32 * rp; idx += PREP_NT) {
+        const int row = idx / rp, j = idx % rp;
+        const int q = 4 * (row >> 3) + (row & 3), lnb = 32 * ((row >> 2) & 1);
+        float t = 0.f;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int v = half * rp + j;              // row of the head+tail copy of V_A
+            const int nb = v >> 5, ln = lnb + (v & 31);
+            t += ((part[0][nb][q][ln] + part[1][nb][q][ln]) + (part[2][nb][q][ln] + part[3][nb][q][ln])) +
+                 ((part[4][nb][q][ln] + part[5][nb][q][ln]) + (part[6][nb][q][ln] + part[7][nb][q][ln]));
+        }
+        const int c = it.row2cand[min(r0 + row, R - 1)];
+        tvec[row][j] = (j < it.r ? it.sigmaA[(size_t)c * it.sigma_stride + j] : 0.f) * t;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < 32 * rp; idx += PREP_NT) {
+        const int row = idx / rp, j = idx % rp;
+        if (r0 + row >= R) continue;
+        float u = 0.f;
+        if (j < it.r && !(a.flags & ESSA_BASE_ONLY)) {
+            const int c = it.row2cand[r0 + row];
+            for (int l = 0; l < it.r; ++l) u = fmaf(it.M[j * rp + l], tvec[row][l], u);
+            u *= it.sigmaB[(size_t)c * it.sigma_stride + j];
+        }
+        const uint16_t hi = f32_to_bf16_bits(u);
+        it.U16[(size_t)(r0 + row) * 2 * rp + j] = hi;
+        it.U16[(size_t)(r0 + row) * 2 * rp + rp + j] = f32_to_bf16_bits(u - bf16_bits_to_f32(hi));
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// int8-MFMA GEMM.  512 threads = 8 waves; tile = (32*MB rows) x 128 channels.  Wave (n, kh): n = 0..3
+// owns channels 32n..32n+31 of the tile for all its rows, kh = 0..1 takes the even / odd pair of 32-wide
+// K chunks of every K tile (two waves per SIMD hide each other's LDS and memory latency; int32 partial
+// sums are exact, so the split costs nothing numerically).  K advances in tiles of 128:
+//   weights      global -> registers, two 16-byte loads per lane and tile, PD tiles ahead;
+//   activations  global -> registers -> LDS (two stages), issued three tiles ahead.
+// Epilogue: the two K halves swap half of their accumulators through LDS, scale, add the rank-r term
+// (operands fetched before the main loop), and the tile leaves through an LDS transpose as full rows.
+// ------------------------------------------------------------------------------------------------
+constexpr int KT = 128;            // K per tile (bytes per limb row)
+constexpr int LROW = KT + 16;      // padded LDS row of an activation tile
+constexpr int PD = 4;              // weight prefetch distance in K tiles; d_in_pad is a multiple of KT * PD
+constexpr int NT = 512;            // threads per workgroup
+constexpr int UROW = 144;          // LDS row of the u tile: 2 * rp bf16 (at most 128 B) + pad
+
+template <int LIMBS, int BM, int XV>
+__device__ __forceinline__ void load_x(u32x4 (&xr)[XV], const int8_t* __restrict__ Xh, const int8_t* __restrict__ Xl, int m0, int dpad,
+                                       int kt, int tid) {
+#pragma unroll
+    for (int e = 0; e < XV; ++e) {
+        const int idx = tid + NT * e;
+        if ((LIMBS * BM * 8) % NT != 0 && idx >= LIMBS * BM * 8) continue;
+        const int limb = idx / (BM * 8), rem = idx % (BM * 8), row = rem >> 3, part = rem & 7;
+        const int8_t* src = (limb == 0 ? Xh : Xl) + (size_t)(m0 + row) * dpad + kt * KT + part * 16;
+        xr[e] = *reinterpret_cast<const u32x4*>(src);
+    }
+}
+
+template <int LIMBS, int BM, int XV>
+__device__ __forceinline__ void store_x(const u32x4 (&xr)[XV], unsigned char* smem, int stage, int tid) {
+#pragma unroll
+    for (int e = 0; e < XV; ++e) {
+        const int idx = tid + NT * e;
+        if ((LIMBS * BM * 8) % NT != 0 && idx >= LIMBS * BM * 8) continue;
+        const int limb = idx / (BM * 8), rem = idx % (BM * 8), row = rem >> 3, part = rem & 7;
+        *reinterpret_cast<u32x4*>(smem + ((size_t)((stage * LIMBS + limb) * BM + row)) * LROW + part * 16) = xr[e];
+    }
+}
+
+// the wave's two K chunks of one tile
+template <int LIMBS, int MB>
+__device__ __forceinline__ void compute_tile(i32x16 (&acc)[LIMBS][MB], const u32x4 (&w)[2], const unsigned char* smem, int stage, int kh,
+                                             int l32, int h) {
+    constexpr int BM = 32 * MB;
+    i32x4 fr[2][LIMBS][MB];
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+        for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                fr[cc][l][mb] = *reinterpret_cast<const i32x4*>(smem + ((size_t)((stage * LIMBS + l) * BM + mb * 32 + l32)) * LROW +
+                                                                (2 * kh + cc) * 32 + 16 * h);
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) {
+        const i32x4 wv = (i32x4)w[cc];
+#pragma unroll
+        for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) acc[l][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[cc][l][mb], wv, acc[l][mb], 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void load_w(u32x4 (&w)[2], const u32x4* __restrict__ wp, size_t wstride, int kt, int kh) {
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc) w[cc] = wp[(size_t)(kt * 4 + 2 * kh + cc) * wstride];
+}
+
+template <int MB, int LIMBS, bool YBF16>
+constexpr size_t gemm_smem_bytes() {
+    constexpr size_t BM = 32 * MB;
+    constexpr size_t stages = 2 * LIMBS * BM * LROW;
+    constexpr size_t exch = (size_t)4 * 2 * LIMBS * (MB >= 2 ? MB / 2 : 1) * 4096;
+    constexpr size_t ctile = BM * (128 * (YBF16 ? 2 : 4) + 16);
+    constexpr size_t big = stages > exch ? (stages > ctile ? stages : ctile) : (exch > ctile ? exch : ctile);
+    return big + BM * 4 + BM * UROW;
+}
+
+template <int MB, int LIMBS, bool YBF16, bool DUMP>
+__global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __restrict__ acc_out) {
+    constexpr int BM = 32 * MB;
+    constexpr int XTOT = LIMBS * BM * 8;               // 16-byte vectors of X per K tile
+    constexpr int XV = (XTOT + NT - 1) / NT;
+    constexpr int MBO = MB >= 2 ? MB / 2 : 1;          // row blocks a wave finishes in the epilogue
+    constexpr size_t BIG = gemm_smem_bytes<MB, LIMBS, YBF16>() - BM * 4 - BM * UROW;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float* xd = reinterpret_cast<float*>(smem + BIG);                  // [BM] value of one fixed-point unit per row
+    unsigned char* utile = smem + BIG + BM * 4;                        // [BM][UROW] bf16 head+tail of u_i
+
+    int g = 0;
+    while (g + 1 < a.n_items && (int)blockIdx.x >= a.tile_start[g + 1]) ++g;
+    const fwd_item& it = a.it[g];
+    // blocks go round-robin over the 8 XCDs; give each XCD a contiguous range of tiles so that the row
+    // tiles sharing a weight tile sit behind the same L2
+    const int ntile = a.tile_start[g + 1] - a.tile_start[g];
+    int tile = blockIdx.x - a.tile_start[g];
+    if ((ntile & 7) == 0 && (a.tile_start[g] & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);
+    const int tiles_m = (it.R + BM - 1) / BM;
+    const int m0 = (tile % tiles_m) * BM, nb0 = (tile / tiles_m) * 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nw = wave & 3, kh = wave >> 2;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int R = it.R, dout = it.d_out, dpad = it.d_in_pad, rp = it.rp;
+    int nk = dpad / KT;                                    // a multiple of PD
+#ifdef EXP_NK
+    nk = EXP_NK;
+#endif
+    const int nbw = min(nb0 + nw, it.n_blocks - 1);        // a wave past the last n-block repeats it; nothing of it is stored
+    // weights are stored k-chunk major, [kc][n-block][1 KB]: at any moment the waves of the whole grid read one
+    // contiguous stretch of memory, which spreads over all HBM channels
+    const size_t wstride = (size_t)it.n_blocks * 64;       // 16-byte vectors per k chunk
+    const u32x4* wp = reinterpret_cast<const u32x4*>(it.Wt) + (size_t)nbw * 64 + lane;
+    const int8_t* Xh = it.Xh;
+    const int8_t* Xl = it.Xl;
+
+    TSTAMP(0)
+    u32x4 w0[2], w1[2], w2[2], w3[2];
+    load_w(w0, wp, wstride, 0, kh);
+    load_w(w1, wp, wstride, 1, kh);
+    load_w(w2, wp, wstride, 2, kh);
+    load_w(w3, wp, wstride, 3, kh);
+    u32x4 xa[XV], xb[XV];
+    load_x<LIMBS, BM, XV>(xa, Xh, Xl, m0, dpad, 0, tid);
+
+    // epilogue operands, fetched now so that their latency hides behind the main loop
+    const int oc = min(nbw * 32 + l32, dout - 1);
+    float wscale = 0.f;
+    u32x4 ubf[2][2];                                       // [ks][head, tail] fragments of U_B for this lane's channel
+    if (!DUMP) {
+        wscale = it.scale[oc];
+        const uint16_t* bp = it.UB16 + (size_t)oc * 2 * rp + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            ubf[ks][0] = ubf[ks][1] = (u32x4){0, 0, 0, 0};
+            if (ks * 16 < rp) {
+                ubf[ks][0] = *reinterpret_cast<const u32x4*>(bp + ks * 16);
+                ubf[ks][1] = *reinterpret_cast<const u32x4*>(bp + rp + ks * 16);
+            }
+        }
+        if (tid < BM) xd[tid] = it.xdelta[min(m0 + tid, R - 1)];
+        // u tile: BM rows x (2 rp bf16) bytes, 16 bytes per thread
+        const int upr = rp / 4;                            // 16-byte pieces per row (2*rp*2 / 16)
+        for (int p = tid; p < BM * upr; p += NT) {
+            const int row = p / upr, piece = p % upr;
+            *reinterpret_cast<u32x4*>(utile + (size_t)row * UROW + piece * 16) =
+                *reinterpret_cast<const u32x4*>(it.U16 + (size_t)min(m0 + row, R - 1) * 2 * rp + piece * 8);
+        }
+    }
+
+    i32x16 acc[LIMBS][MB];
+#pragma unroll
+    for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[l][mb][q] = 0;
+
+    store_x<LIMBS, BM, XV>(xa, smem, 0, tid);
+    load_x<LIMBS, BM, XV>(xa, Xh, Xl, m0, dpad, 1, tid);
+    load_x<LIMBS, BM, XV>(xb, Xh, Xl, m0, dpad, min(2, nk - 1), tid);
+    __syncthreads();
+    TSTAMP(1)
+    // One step: multiply K tile kt (weights in W), refill W with tile kt+PD, move activation tile kt+1 (in XS)
+    // into the other LDS stage and refill XS with tile kt+3.  Tile indices past the end are clamped: that data
+    // is fetched again and never used.
+#define ESSA_STEP(W, XS, KTI)                                                        \
+    {                                                                                \
+        const int kt_ = (KTI);                                                       \
+        compute_tile<LIMBS, MB>(acc, W, smem, kt_ & 1, kh, l32, h);                  \
+        load_w(W, wp, wstride, min(kt_ + PD, nk - 1), kh);                           \
+        store_x<LIMBS, BM, XV>(XS, smem, (kt_ + 1) & 1, tid);                        \
+        __syncthreads();                                                             \
+        load_x<LIMBS, BM, XV>(XS, Xh, Xl, m0, dpad, min(kt_ + 3, nk - 1), tid);      \
+    }
+    for (int kt0 = 0; kt0 < nk; kt0 += PD) {
+        ESSA_STEP(w0, xa, kt0)
+        ESSA_STEP(w1, xb, kt0 + 1)
+        ESSA_STEP(w2, xa, kt0 + 2)
+        ESSA_STEP(w3, xb, kt0 + 3)
+    }
+#undef ESSA_STEP
+    TSTAMP(2)
+
+    // ---- epilogue 1: the two K halves exchange accumulators.  Half kh keeps row blocks with (mb & 1) == kh
+    // (all of them when there is only one) and hands the others to its partner.
+    // exchange slot (n, writer kh, limb, j): 16 x 64 ints, written as [q/4][lane] 16-byte vectors
+    auto slot = [&](int n_, int kh_, int l_, int j_) { return smem + ((size_t)((n_ * 2 + kh_) * LIMBS + l_) * MBO + j_) * 4096; };
+#pragma unroll
+    for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const bool mine = MB >= 2 ? ((mb & 1) == kh) : (kh == 0);
+            if (!mine) {
+                unsigned char* dst = slot(nw, kh, l, MB >= 2 ? mb / 2 : 0);
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *reinterpret_cast<i32x4*>(dst + (q4 * 64 + lane) * 16) =
+                        (i32x4){acc[l][mb][4 * q4], acc[l][mb][4 * q4 + 1], acc[l][mb][4 * q4 + 2], acc[l][mb][4 * q4 + 3]};
+            }
+        }
+    __syncthreads();
+#pragma unroll
+    for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const bool mine = MB >= 2 ? ((mb & 1) == kh) : (kh == 0);
+            if (mine) {
+                const unsigned char* src = slot(nw, kh ^ 1, l, MB >= 2 ? mb / 2 : 0);
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const i32x4 o4 = *reinterpret_cast<const i32x4*>(src + (q4 * 64 + lane) * 16);
+                    acc[l][mb][4 * q4] += o4[0];
+                    acc[l][mb][4 * q4 + 1] += o4[1];
+                    acc[l][mb][4 * q4 + 2] += o4[2];
+                    acc[l][mb][4 * q4 + 3] += o4[3];
+                }
+            }
+        }
+    if (DUMP) {
+        const int o = (nb0 + nw) * 32 + l32;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const bool mine = MB >= 2 ? ((mb & 1) == kh) : (kh == 0);
+            if (!mine) continue;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int i = m0 + mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+                if (i < R && o < dout) acc_out[(size_t)i * dout + o] = acc[0][mb][q];
+            }
+        }
+        return;
+    }
+    __syncthreads();   // exchange slots are read; the same memory now becomes the output tile
+    TSTAMP(3)
+
+    // ---- epilogue 2: scale, rank-r term, into the LDS output tile [BM][128 channels]
+    constexpr int CROW = 128 * (YBF16 ? 2 : 4) + 16;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const bool mine = MB >= 2 ? ((mb & 1) == kh) : (kh == 0);
+        if (!mine) continue;
+        f32x16 v;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int rl = mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+            const float sc = xd[rl] * wscale;
+            if (LIMBS == 2) v[q] = fmaf(128.0f, (float)acc[0][mb][q], (float)acc[LIMBS - 1][mb][q]) * sc;
+            else v[q] = (float)acc[0][mb][q] * sc;
+            if (a.flags & ESSA_LORA_ONLY) v[q] = 0.f;
+        }
+        if (!(a.flags & ESSA_BASE_ONLY)) {
+            // rank-r term U_B u_i: bf16 head+tail operands, lo*hi + hi*lo + hi*hi per 16 rank columns
+            const unsigned char* up = utile + (size_t)(mb * 32 + l32) * UROW + 16 * h;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                if (ks * 16 < rp) {
+                    const bf16x8 ua_hi = *reinterpret_cast<const bf16x8*>(up + ks * 32);
+                    const bf16x8 ua_lo = *reinterpret_cast<const bf16x8*>(up + 2 * rp + ks * 32);
+                    const bf16x8 ub_hi = __builtin_bit_cast(bf16x8, ubf[ks][0]);
+                    const bf16x8 ub_lo = __builtin_bit_cast(bf16x8, ubf[ks][1]);
+                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_lo, ub_hi, v, 0, 0, 0);
+                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_hi, ub_lo, v, 0, 0, 0);
+                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_hi, ub_hi, v, 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int rl = mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+            unsigned char* dst = smem + (size_t)rl * CROW + (nw * 32 + l32) * (YBF16 ? 2 : 4);
+            if (YBF16) *reinterpret_cast<uint16_t*>(dst) = f32_to_bf16_bits(v[q]);
+            else *reinterpret_cast<float*>(dst) = v[q];
+        }
+    }
+    __syncthreads();
+    TSTAMP(4)
+
+    // ---- epilogue 3: the tile leaves as full rows, 16 bytes per thread where the output allows it
+    constexpr int ESZ = YBF16 ? 2 : 4, EPV = 16 / ESZ, PPR = 128 / EPV;     // elements per vector, vectors per row
+    unsigned char* Yb = reinterpret_cast<unsigned char*>(it.Y);
+    const int n0 = nb0 * 32;
+    const bool vec_ok = (dout % EPV == 0) && ((reinterpret_cast<uintptr_t>(it.Y) & 15) == 0);
+    for (int p = tid; p < BM * PPR; p += NT) {
+        const int row = p / PPR, piece = p % PPR;
+        const int i = m0 + row, o = n0 + piece * EPV;
+        if (i >= R || o >= dout) continue;
+        const unsigned char* src = smem + (size_t)row * CROW + piece * 16;
+        if (vec_ok && o + EPV <= dout) {
+            *reinterpret_cast<u32x4*>(Yb + ((size_t)i * dout + o) * ESZ) = *reinterpret_cast<const u32x4*>(src);
+        } else {
+            for (int e = 0; e < EPV && o + e < dout; ++e) {
+                if (YBF16) reinterpret_cast<uint16_t*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const uint16_t*>(src)[e];
+                else reinterpret_cast<float*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const float*>(src)[e];
+            }
+        }
+    }
+    TSTAMP(5)
+}
+
+template <int MB, int LIMBS, bool YBF16, bool DUMP>
+hipError_t launch_gemm(hipStream_t st, stream_args& a, int32_t* acc_out) {
+    int total = 0;
+    for (int g = 0; g < a.n_items; ++g) {
+        a.tile_start[g] = total;
+        total += ((a.it[g].R + 32 * MB - 1) / (32 * MB)) * ((a.it[g].n_blocks + 3) / 4);
+    }
+    a.tile_start[a.n_items] = total;
+    constexpr size_t smem = gemm_smem_bytes<MB, LIMBS, YBF16>();
+    static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
+    auto kern = gemm_i8_kernel<MB, LIMBS, YBF16, DUMP>;
+    static bool attr_done = false;   // one flag per instantiation
+    if (!attr_done && smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a, acc_out);
+    return hipGetLastError();
+}
+
+template <int LIMBS, bool YBF16>
+hipError_t launch_gemm_mb(hipStream_t st, stream_args& a, int mb) {
+    switch (mb) {
+        case 1: return launch_gemm<1, LIMBS, YBF16, false>(st, a, nullptr);
+        case 2: return launch_gemm<2, LIMBS, YBF16, false>(st, a, nullptr);
+        default: return launch_gemm<4, LIMBS, YBF16, false>(st, a, nullptr);
+    }
+}
+
+// rows per tile: the largest of 128/64/32 that still leaves every CU a tile
+int pick_mb(const stream_args& a) {
+    int maxR = 0;
+    for (int g = 0; g < a.n_items; ++g) maxR = a.it[g].R > maxR ? a.it[g].R : maxR;
+    for (int mb : {4, 2}) {
+        if (maxR <= 16 * mb) continue;     // tile would be more than half empty
+        long long tiles = 0;
+        for (int g = 0; g < a.n_items; ++g) tiles += (long long)((a.it[g].R + 32 * mb - 1) / (32 * mb)) * ((a.it[g].n_blocks + 3) / 4);
+        if (tiles >= 256) return mb;
+    }
+    return maxR <= 32 ? 1 : 2;
+}
+
+void fill_prep_tables(stream_args& a) {
+    int q = 0, l = 0;
+    for (int g = 0; g < a.n_items; ++g) {
+        a.quant_start[g] = q;
+        a.lora_start[g] = l;
+        if (a.it[g].x_owner) q += (a.it[g].R + 3) / 4;
+        l += (a.it[g].R + 31) / 32;
+    }
+    a.quant_start[a.n_items] = q;
+    a.lora_start[a.n_items] = l;
+}
+
+}  // namespace
+
+namespace essa_k {
+
+hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, int y_dtype, unsigned flags,
+                          hipEvent_t ev_start, hipEvent_t ev_stop) {
+    stream_args a{};
+    for (int g = 0; g < n_items; ++g) a.it[g] = items[g];
+    a.n_items = n_items;
+    a.flags = flags;
+    a.limbs = (flags & ESSA_COMPUTE_W8A8) ? 1 : 2;
+    fill_prep_tables(a);
+    hipLaunchKernelGGL(prep_kernel, dim3(a.quant_start[n_items] + a.lora_start[n_items]), dim3(PREP_NT), 0, st, a);
+    const int mb = pick_mb(a);
+    if (ev_start) (void)hipEventRecord(ev_start, st);
+    hipError_t e;
+    if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true>(st, a, mb) : launch_gemm_mb<2, false>(st, a, mb);
+    else e = y_dtype == ESSA_BF16 ? launch_gemm_mb<1, true>(st, a, mb) : launch_gemm_mb<1, false>(st, a, mb);
+    if (ev_stop) (void)hipEventRecord(ev_stop, st);
+    return e != hipSuccess ? e : hipGetLastError();
+}
+
+hipError_t w8a8_accumulators_stream(hipStream_t st, const fwd_item& it, int32_t* acc_out) {
+    stream_args a{};
+    a.it[0] = it;
+    a.it[0].x_owner = 1;
+    a.n_items = 1;
+    a.flags = ESSA_BASE_ONLY | ESSA_COMPUTE_W8A8;
+    a.limbs = 1;
+    a.quant_start[0] = 0;
+    a.quant_start[1] = (it.R + 3) / 4;      // quantise only: no rank-space work for the accumulator dump
+    a.lora_start[0] = a.lora_start[1] = 0;
+    hipLaunchKernelGGL(prep_kernel, dim3(a.quant_start[1]), dim3(PREP_NT), 0, st, a);
+    return launch_gemm<2, 1, false, true>(st, a, acc_out);
+}
+
+}  // namespace essa_k

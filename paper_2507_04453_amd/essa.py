@@ -10,7 +10,7 @@ import torch
 
 __all__ = [
     "EssaError", "lib", "LIB_PATH", "Context", "Projection", "CmaState",
-    "F32", "BF16", "QUANT_INT8_PERCH", "QUANT_INT4_G128", "COMPUTE_W8A8", "LORA_ONLY", "BASE_ONLY",
+    "F32", "BF16", "QUANT_INT8_PERCH", "QUANT_INT4_G128", "COMPUTE_W8A8", "LORA_ONLY", "BASE_ONLY", "COMPUTE_BF16",
     "essa_create", "essa_proj_create", "essa_cma_create", "essa_sample_candidates", "essa_philox_words",
     "essa_theta_to_sigma", "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
     "essa_reward_accumulate", "essa_cmaes_update", "essa_rank_rewards", "essa_version", "EXPORTED_SYMBOLS",
@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libessa.so"
 
 F32, BF16 = 0, 1
 QUANT_INT8_PERCH, QUANT_INT4_G128 = 0, 1
-COMPUTE_W8A8, LORA_ONLY, BASE_ONLY = 1, 2, 4
+COMPUTE_W8A8, LORA_ONLY, BASE_ONLY, COMPUTE_BF16 = 1, 2, 4, 8
 MAX_GROUP = 8
 
 EXPORTED_SYMBOLS = [

@@ -3,9 +3,12 @@
 Tolerances (relative to the whole reference tensor: max|d|/max|ref| and ||d||/||ref||):
   bit-exact      Philox words, int8 activation codes, int32 accumulators, ranking
   fp32 paths     rms 1e-5, max 1e-4   (tiny config, sampler, update)
-  bf16 inputs    rms 1e-3, max 2e-2   (the stated bar); the fp32-output variants are held to rms 2e-5,
-                 max 2e-4: inputs are exact there and every accumulation is fp32 (the rank-r term uses
-                 bf16 head+tail operands).
+  bf16 inputs    rms 1e-3, max 2e-2   (the stated bar) for bf16 outputs.  With fp32 outputs the same kernels are
+                 held to tighter bars that follow from their arithmetic:
+                   exact-product paths (ESSA_COMPUTE_BF16, 4-bit weights): rms 2e-5, max 2e-4 (fp32 accumulation,
+                   bf16 head+tail operands in the rank-r term);
+                   default int8-limb path: rms 2e-4, max 2e-3 -- each activation is rounded to a grid of
+                   amax_row/16383, a uniform error of rms amax/56752, i.e. about 7e-5 of the output for N(0,1) rows.
 """
 import math
 
@@ -21,6 +24,8 @@ pytestmark = pytest.mark.gpu
 
 FP32_RMS, FP32_MAX = 1e-5, 1e-4
 BF16_RMS, BF16_MAX = 1e-3, 2e-2
+EXACT_RMS, EXACT_MAX = 2e-5, 2e-4
+LIMB_RMS, LIMB_MAX = 2e-4, 2e-3
 
 
 @pytest.fixture(scope="module")
@@ -157,35 +162,38 @@ def test_forward_small_shapes_bf16(essa, ctx, quant, d_in, d_out, r, K, R):
     ref = orc.svdlora_forward(W, f, xv, r2c, sA, sB)
     Xd, rd, sAd, sBd = bf16_dev(xb), to_dev(r2c), to_dev(sA), to_dev(sB)
     Y32 = torch.empty(R, d_out, device="cuda")
-    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32)
-    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref)
-    _say("  fp32 out: max %.3g rms %.3g" % (e_max, e_rms))
-    assert e_rms <= 2e-5 and e_max <= 2e-4
-    Y16 = torch.empty(R, d_out, device="cuda", dtype=torch.bfloat16)
-    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y16)
-    e_max, e_rms = orc.rel_errors(bf16_host(Y16), orc.round_to_bf16(ref))
-    _say("  bf16 out: max %.3g rms %.3g" % (e_max, e_rms))
-    assert e_rms <= BF16_RMS and e_max <= BF16_MAX
-    # the rank-r term alone and the base alone
-    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, essa.LORA_ONLY)
+    base = xv.astype(np.float64) @ W.T
     ref_l = orc.svdlora_forward(W, f, xv, r2c, sA, sB, lora_only=True)
-    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref_l)
-    _say("  lora only: max %.3g rms %.3g" % (e_max, e_rms))
-    assert e_rms <= 1e-4 and e_max <= 1e-3
-    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, essa.BASE_ONLY)
-    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), xv.astype(np.float64) @ W.T)
-    assert e_rms <= 1e-5 and e_max <= 1e-4
-    # sigma = 0 reproduces the base layer; own spectrum reproduces W + BA of the unfactored factors
-    z = torch.zeros(K, r, device="cuda")
-    essa.essa_svdlora_forward(ctx, gp, Xd, rd, z, sBd, Y32)
-    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), xv.astype(np.float64) @ W.T)
-    assert e_rms <= 1e-5
     own_A = to_dev(np.tile(f["S_A"].astype(np.float32), (K, 1)))
     own_B = to_dev(np.tile(f["S_B"].astype(np.float32), (K, 1)))
-    essa.essa_svdlora_forward(ctx, gp, Xd, rd, own_A, own_B, Y32)
-    ref_own = xv.astype(np.float64) @ W.T + (xv.astype(np.float64) @ p.A.astype(np.float64).T) @ p.B.astype(np.float64).T
-    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref_own)
-    assert e_rms <= 2e-5
+    ref_own = base + (xv.astype(np.float64) @ p.A.astype(np.float64).T) @ p.B.astype(np.float64).T
+    # the default path of int8 weights rounds activations to 15-bit fixed point; the others are exact in the products
+    variants = [(0, LIMB_RMS, LIMB_MAX), (essa.COMPUTE_BF16, EXACT_RMS, EXACT_MAX)] if quant == "int8" and d_in % 16 == 0 \
+        else [(0, EXACT_RMS, EXACT_MAX)]
+    for fl, t_rms, t_max in variants:
+        essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, fl)
+        e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref)
+        _say("  flags %d fp32 out: max %.3g rms %.3g" % (fl, e_max, e_rms))
+        assert e_rms <= t_rms and e_max <= t_max
+        Y16 = torch.empty(R, d_out, device="cuda", dtype=torch.bfloat16)
+        essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y16, fl)
+        e_max, e_rms = orc.rel_errors(bf16_host(Y16), orc.round_to_bf16(ref))
+        _say("  flags %d bf16 out: max %.3g rms %.3g" % (fl, e_max, e_rms))
+        assert e_rms <= BF16_RMS and e_max <= BF16_MAX
+        # the rank-r term alone (never touched by the activation rounding) and the base alone
+        essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, fl | essa.LORA_ONLY)
+        e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref_l)
+        _say("  flags %d lora only: max %.3g rms %.3g" % (fl, e_max, e_rms))
+        assert e_rms <= 1e-4 and e_max <= 1e-3
+        essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, fl | essa.BASE_ONLY)
+        e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), base)
+        assert e_rms <= t_rms and e_max <= t_max
+        # sigma = 0 reproduces the base layer; own spectrum reproduces W + BA of the unfactored factors
+        z = torch.zeros(K, r, device="cuda")
+        essa.essa_svdlora_forward(ctx, gp, Xd, rd, z, sBd, Y32, fl)
+        assert orc.rel_errors(Y32.cpu().numpy(), base)[1] <= t_rms
+        essa.essa_svdlora_forward(ctx, gp, Xd, rd, own_A, own_B, Y32, fl)
+        assert orc.rel_errors(Y32.cpu().numpy(), ref_own)[1] <= t_rms
     gp.close()
 
 
@@ -199,7 +207,7 @@ def test_forward_edge_cases(essa, ctx):
     Y = torch.empty(1, 128, device="cuda")
     essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb), to_dev(np.zeros(1, np.int32)), to_dev(sA), to_dev(sB), Y)
     e_max, e_rms = orc.rel_errors(Y.cpu().numpy(), orc.svdlora_forward(W, f, xv, np.zeros(1, np.int32), sA, sB))
-    assert e_rms <= 2e-5
+    assert e_rms <= LIMB_RMS
     # R = 0 is a no-op
     essa.essa_svdlora_forward(ctx, gp, torch.empty(0, 256, device="cuda", dtype=torch.bfloat16), torch.empty(0, dtype=torch.int32, device="cuda"),
                               to_dev(sA), to_dev(sB), torch.empty(0, 128, device="cuda"))
@@ -220,7 +228,7 @@ def test_forward_edge_cases(essa, ctx):
         Y = torch.empty(K, 64, device="cuda")
         essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb), to_dev(r2c), to_dev(sA), to_dev(sB), Y)
         e_max, e_rms = orc.rel_errors(Y.cpu().numpy(), orc.svdlora_forward(W, f, xv, r2c, sA, sB))
-        assert e_rms <= 2e-5, (K, r, e_rms)
+        assert e_rms <= LIMB_RMS, (K, r, e_rms)
         gp.close()
 
 
@@ -244,7 +252,7 @@ def test_forward_row_permutation_and_strided_sigma(essa, ctx):
     essa.essa_svdlora_forward(ctx, gp, bf16_dev(xb[perm]), to_dev(r2c[perm]), to_dev(sA), to_dev(sB), Y2)
     assert torch.equal(Y1[torch.from_numpy(perm).cuda()], Y2)      # a row's result does not depend on where it sits
     e_max, e_rms = orc.rel_errors(Y1.cpu().numpy(), orc.svdlora_forward(W, f, xv, r2c, sA, sB))
-    assert e_rms <= 2e-5
+    assert e_rms <= LIMB_RMS
     gp.close()
 
 
