@@ -33,7 +33,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--mode", choices=["w8a16", "w8a8"], default="w8a16", help="bf16 MFMA on bf16 activations, or int8 MFMA on per-row quantised ones")
+    ap.add_argument("--mode", choices=["w8a16", "w8a8"], default="w8a16", help="w8a16: bf16 activations as two int8 limbs on the int8 MFMA (default path); w8a8: one int8 limb")
     ap.add_argument("--layers", type=int, default=28)
     ap.add_argument("--rows-per-cand", type=int, default=8)
     ap.add_argument("--forward-only", action="store_true", help="time only the projections (no sampler / reward / update)")
@@ -107,8 +107,7 @@ def main():
         for l in range(layers):
             essa.essa_svdlora_forward_group(ctx, items[l], flags)
             if with_reward:
-                for pi in range(4):
-                    essa.essa_reward_accumulate(ctx, Ys[pi], vecs[l * 4 + pi], r2c, F)
+                essa.essa_reward_accumulate_group(ctx, Ys, vecs[l * 4:l * 4 + 4], r2c, F)
 
     def step():
         if args.forward_only:
@@ -126,12 +125,19 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ctx.profile_enable(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # the same K steps once more with the library's HIP events around every GEMM launch (on its own stream):
+    # the events cost a few percent of a step, so they stay out of the region that `value` is taken from
+    ctx.profile_enable(True)
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed_profiled = time.perf_counter() - t1
     gemm_ms, gemm_launches = ctx.profile_read()
     ctx.profile_enable(False)
     ms_per_step = 1e3 * elapsed / args.steps
@@ -171,7 +177,7 @@ def main():
     else:
         ach = bytes_per_launch / avg_s / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
-    roof.update({"kernel": "gemm_mfma_kernel", "avg_launch_us": avg_s * 1e6, "launches": gemm_launches,
+    roof.update({"kernel": "gemm_i8_kernel", "avg_launch_us": avg_s * 1e6, "launches": gemm_launches,
                  "flops_per_launch": flops_per_launch, "bytes_per_launch": bytes_per_launch,
                  "achieved_GBs": bytes_per_launch / avg_s / 1e9, "achieved_TFLOPs": flops_per_launch / avg_s / 1e12})
 
@@ -187,6 +193,7 @@ def main():
                    "rows": R, "weights": "int8 per-channel", "activations": "bf16", "mode": args.mode,
                    "step": "forward only" if args.forward_only else "sample + sigma + %d layers x (q,k,v,o) + reward + update" % layers},
         "roofline": roof, "cpu_baseline": cpu, "breakdown_ms": breakdown,
+        "ms_per_step_with_events": 1e3 * elapsed_profiled / args.steps,
     }
     print(json.dumps(out), flush=True)
 
@@ -203,26 +210,30 @@ def cpu_baseline(cfg, R, rows_per, mode):
     except Exception:
         threads = 1
     K = cfg.K
-    projs = wl.make_layer(cfg.hidden, cfg.kv, cfg.r, cfg.quant, 0)
     xv1 = wl.make_x_bf16(R, cfg.hidden, 0)[1]
     xv2 = wl.make_x_bf16(R, cfg.hidden, 1)[1]
     r2c = wl.row2cand_contiguous(K, rows_per)
-    prepared = []
-    for pi, p in enumerate(projs):      # set-up (SVD, dequantisation) is not timed, as on the GPU side
-        W = orc.dequant_int8(p.Wq, p.scales)
-        f = orc.thin_svd_factors(p.A, p.B)
-        dA, dB = wl.sigma_perturbation(K, 1, cfg.r, cfg.sigma_step, pi)
-        prepared.append((p, W, f, (f["S_A"][None] + dA[:, 0]), (f["S_B"][None] + dB[:, 0])))
-    t0 = time.perf_counter()
-    for p, W, f, sA, sB in prepared:
-        xv = xv2 if p.name == "o" else xv1
-        if mode == "w8a8":
-            orc.svdlora_forward_w8a8(p.Wq, p.scales, f, xv, r2c, sA, sB)
-        else:
-            orc.svdlora_forward(W, f, xv, r2c, sA, sB)
-    dt = time.perf_counter() - t0
-    return {"value": R / dt, "unit": "candidate-tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "one layer (q,k,v,o) of c2_7b_decode, all %d rows, candidate weights W + B_k A_k formed explicitly in fp64; %.2f s" % (R, dt)}
+    n_layers, dt = 0, 0.0
+    while dt < 12.0 and n_layers < cfg.layers:      # about 10-30 s of oracle work
+        prepared = []
+        for pi, p in enumerate(wl.make_layer(cfg.hidden, cfg.kv, cfg.r, cfg.quant, n_layers)):
+            # set-up (SVD, dequantisation) is not timed, as on the GPU side
+            W = orc.dequant_int8(p.Wq, p.scales)
+            f = orc.thin_svd_factors(p.A, p.B)
+            dA, dB = wl.sigma_perturbation(K, 1, cfg.r, cfg.sigma_step, n_layers * 4 + pi)
+            prepared.append((p, W, f, (f["S_A"][None] + dA[:, 0]), (f["S_B"][None] + dB[:, 0])))
+        t0 = time.perf_counter()
+        for p, W, f, sA, sB in prepared:
+            xv = xv2 if p.name == "o" else xv1
+            if mode == "w8a8":
+                orc.svdlora_forward_w8a8(p.Wq, p.scales, f, xv, r2c, sA, sB)
+            else:
+                orc.svdlora_forward(W, f, xv, r2c, sA, sB)
+        dt += time.perf_counter() - t0
+        n_layers += 1
+    return {"value": n_layers * R / dt, "unit": "candidate-tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "the first %d layers (q,k,v,o each) of c2_7b_decode, all %d rows, candidate weights W + B_k A_k formed "
+                      "explicitly in fp64, forward only; %.1f s" % (n_layers, R, dt)}
 
 
 if __name__ == "__main__":

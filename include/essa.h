@@ -202,6 +202,12 @@ essa_status essa_w8a8_accumulators(essa_ctx* ctx, const essa_proj* proj, const v
  * ------------------------------------------------------------------------------------------- */
 essa_status essa_reward_accumulate(essa_ctx* ctx, const void* Y, int y_dtype, int R, int d_out, const float* v,
                                    const int32_t* row2cand, int K, float* F);
+/* The same over several outputs that share the rows (the projections of one layer) in one launch sequence:
+ * F[k] += mean over the rows of k of  sum_g < Y_g[i,:], v_g >.  Y, d_out, v are HOST arrays of n_items entries
+ * (1..ESSA_MAX_GROUP) holding DEVICE pointers / widths. */
+essa_status essa_reward_accumulate_group(essa_ctx* ctx, int n_items, const void* const* Y, const int* d_out,
+                                         const float* const* v, int y_dtype, int R, const int32_t* row2cand, int K,
+                                         float* F);
 
 /* ---------------------------------------------------------------------------------------------
  * Hot path 5: rank-weighted update  (paper: Algorithm 1, "each worker reconstructs the same

@@ -458,7 +458,8 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
         const size_t R = it.R;
         total += align256(R * p->rp * 4) + align256(R * p->rp * 4) + align256(R * (p->groups > 0 ? p->groups : 1) * 4);
         if (flags & ESSA_COMPUTE_W8A8) total += align256(R * (size_t)p->d_in) + align256(R * 4);
-        if (p->Wt) total += 2 * align256((R + 255) / 256 * 256 * (size_t)p->d_in_pad) + align256(R * 4);
+        if (p->Wt) total += 2 * align256((R + 255) / 256 * 256 * (size_t)p->d_in_pad) + align256(R * 4) +
+                            align256((size_t)((p->d_in / 16 + 63) / 64) * ((R + 31) / 32 * 32) * 2 * p->rp * 4);
     }
     ESSA_TRY(essa_ws_reserve(ctx, total));
     char* w = (char*)ctx->ws;
@@ -472,6 +473,8 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
             k.xscale = (float*)w; w += align256(R * 4);
         }
         if (k.Wt) {
+            k.tslices = (k.d_in / 16 + 63) / 64;
+            k.Tpart = (float*)w; w += align256((size_t)k.tslices * ((R + 31) / 32 * 32) * 2 * k.rp * 4);
             // items reading the same X share one set of limbs; the first of them quantises
             const essa_k::fwd_item* first = nullptr;
             for (auto& o : out) {
@@ -570,15 +573,26 @@ extern "C" essa_status essa_w8a8_accumulators(essa_ctx* ctx, const essa_proj* pr
     return ESSA_OK;
 }
 
-extern "C" essa_status essa_reward_accumulate(essa_ctx* ctx, const void* Y, int y_dtype, int R, int d_out, const float* v,
-                                              const int32_t* row2cand, int K, float* F) {
-    if (!ctx || !Y || !v || !row2cand || !F) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_reward_accumulate: NULL argument");
-    if (y_dtype != ESSA_F32 && y_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_reward_accumulate: y_dtype %d", y_dtype);
-    if (R < 1 || d_out < 1 || K < 1) return essa_fail(ESSA_ERR_SHAPE, "essa_reward_accumulate: R=%d d_out=%d K=%d", R, d_out, K);
+extern "C" essa_status essa_reward_accumulate_group(essa_ctx* ctx, int n_items, const void* const* Y, const int* d_out,
+                                                    const float* const* v, int y_dtype, int R, const int32_t* row2cand, int K,
+                                                    float* F) {
+    if (!ctx || !Y || !d_out || !v || !row2cand || !F) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_reward_accumulate_group: NULL argument");
+    if (n_items < 1 || n_items > ESSA_MAX_GROUP) return essa_fail(ESSA_ERR_SHAPE, "essa_reward_accumulate_group: %d items, at most %d", n_items, ESSA_MAX_GROUP);
+    if (y_dtype != ESSA_F32 && y_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_reward_accumulate_group: y_dtype %d", y_dtype);
+    if (R < 1 || K < 1) return essa_fail(ESSA_ERR_SHAPE, "essa_reward_accumulate_group: R=%d K=%d", R, K);
+    for (int g = 0; g < n_items; ++g) {
+        if (!Y[g] || !v[g]) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_reward_accumulate_group: item %d has a NULL tensor", g);
+        if (d_out[g] < 1) return essa_fail(ESSA_ERR_SHAPE, "essa_reward_accumulate_group: item %d has d_out=%d", g, d_out[g]);
+    }
     ESSA_HIP(hipSetDevice(ctx->device));
     ESSA_TRY(essa_ws_reserve(ctx, align256((size_t)R * 4)));
-    ESSA_HIP(essa_k::reward_accumulate(ctx->stream, Y, y_dtype, R, d_out, v, row2cand, K, (float*)ctx->ws, F));
+    ESSA_HIP(essa_k::reward_accumulate(ctx->stream, n_items, Y, d_out, v, y_dtype, R, row2cand, K, (float*)ctx->ws, F));
     return ESSA_OK;
+}
+
+extern "C" essa_status essa_reward_accumulate(essa_ctx* ctx, const void* Y, int y_dtype, int R, int d_out, const float* v,
+                                              const int32_t* row2cand, int K, float* F) {
+    return essa_reward_accumulate_group(ctx, 1, &Y, &d_out, &v, y_dtype, R, row2cand, K, F);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -140,6 +140,8 @@ struct fwd_item {              // one projection of a grouped forward, device po
     int8_t* Xl;                // same, low limb
     float* xdelta;             // [R] value of one unit of the fixed-point row
     int x_owner;               // 1: this item's rows are quantised by the prep kernel (first user of that X)
+    float* Tpart;              // [tslices][R rounded up to 32][2*rp] partial sums of V_A^T x over K slices (head and tail columns)
+    int tslices;               // K slices of 64 steps of 16
 };
 hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int x_dtype, int y_dtype,
                          unsigned flags, hipEvent_t ev_start, hipEvent_t ev_stop);
@@ -148,6 +150,6 @@ hipError_t w8a8_accumulators(hipStream_t st, const fwd_item& it, int x_dtype, in
 hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, int y_dtype, unsigned flags,
                           hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t w8a8_accumulators_stream(hipStream_t st, const fwd_item& it, int32_t* acc_out);
-hipError_t reward_accumulate(hipStream_t st, const void* Y, int y_dtype, int R, int d_out, const float* v,
-                             const int32_t* row2cand, int K, float* rowdot /*[R] scratch*/, float* F);
+hipError_t reward_accumulate(hipStream_t st, int n_items, const void* const* Y, const int* d_out, const float* const* v,
+                             int y_dtype, int R, const int32_t* row2cand, int K, float* rowdot /*[R] scratch*/, float* F);
 }  // namespace essa_k

@@ -448,19 +448,57 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(fwd_args a, int32_t* __r
 // ------------------------------------------------------------------------------------------------
 // synthetic reward
 // ------------------------------------------------------------------------------------------------
-template <bool YBF16>
-__global__ __launch_bounds__(256) void rowdot_kernel(const void* __restrict__ Y, int R, int d_out, const float* __restrict__ v,
-                                                    float* __restrict__ rowdot) {
+struct reward_args {
+    const void* Y[ESSA_MAX_GROUP];
+    const float* v[ESSA_MAX_GROUP];
+    int d_out[ESSA_MAX_GROUP];
+    int n_items, R;
+};
+
+// rowdot[i] = sum over the items (in order) of <Y_item[i, :], v_item>; one wave per row, 16-byte loads when VEC
+template <bool YBF16, bool VEC>
+__global__ __launch_bounds__(256) void rowdot_kernel(reward_args a, float* __restrict__ rowdot) {
     const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= R) return;
-    float s = 0.f;
-    for (int o = lane; o < d_out; o += 64) {
-        const float y = YBF16 ? bf16_bits_to_f32(((const uint16_t*)Y)[(size_t)row * d_out + o]) : ((const float*)Y)[(size_t)row * d_out + o];
-        s = fmaf(y, v[o], s);
-    }
+    if (row >= a.R) return;
+    float total = 0.f;
+    for (int g = 0; g < a.n_items; ++g) {
+        const int d = a.d_out[g];
+        const float* __restrict__ v = a.v[g];
+        float s = 0.f;
+        if (VEC && YBF16) {
+            const uint4* y = reinterpret_cast<const uint4*>((const uint16_t*)a.Y[g] + (size_t)row * d);
+            for (int c = lane; c < d / 8; c += 64) {
+                const uint4 w = y[c];
+                const float4 v0 = *reinterpret_cast<const float4*>(v + c * 8), v1 = *reinterpret_cast<const float4*>(v + c * 8 + 4);
+                s = fmaf(__uint_as_float(w.x << 16), v0.x, s);
+                s = fmaf(__uint_as_float(w.x & 0xffff0000u), v0.y, s);
+                s = fmaf(__uint_as_float(w.y << 16), v0.z, s);
+                s = fmaf(__uint_as_float(w.y & 0xffff0000u), v0.w, s);
+                s = fmaf(__uint_as_float(w.z << 16), v1.x, s);
+                s = fmaf(__uint_as_float(w.z & 0xffff0000u), v1.y, s);
+                s = fmaf(__uint_as_float(w.w << 16), v1.z, s);
+                s = fmaf(__uint_as_float(w.w & 0xffff0000u), v1.w, s);
+            }
+        } else if (VEC) {
+            const float4* y = reinterpret_cast<const float4*>((const float*)a.Y[g] + (size_t)row * d);
+            for (int c = lane; c < d / 4; c += 64) {
+                const float4 w = y[c], vv = *reinterpret_cast<const float4*>(v + c * 4);
+                s = fmaf(w.x, vv.x, s);
+                s = fmaf(w.y, vv.y, s);
+                s = fmaf(w.z, vv.z, s);
+                s = fmaf(w.w, vv.w, s);
+            }
+        } else {
+            for (int o = lane; o < d; o += 64) {
+                const float y = YBF16 ? bf16_bits_to_f32(((const uint16_t*)a.Y[g])[(size_t)row * d + o]) : ((const float*)a.Y[g])[(size_t)row * d + o];
+                s = fmaf(y, v[o], s);
+            }
+        }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    if (lane == 0) rowdot[row] = s;
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        total += s;
+    }
+    if (lane == 0) rowdot[row] = total;
 }
 
 // F[k] += (sum of rowdot over the rows of candidate k) / (their number); fixed-order tree, 0/0 = NaN.
@@ -589,10 +627,27 @@ hipError_t w8a8_accumulators(hipStream_t st, const fwd_item& it, int x_dtype, in
     return hipGetLastError();
 }
 
-hipError_t reward_accumulate(hipStream_t st, const void* Y, int y_dtype, int R, int d_out, const float* v,
-                             const int32_t* row2cand, int K, float* rowdot, float* F) {
-    if (y_dtype == ESSA_BF16) hipLaunchKernelGGL((rowdot_kernel<true>), dim3((R + 3) / 4), dim3(256), 0, st, Y, R, d_out, v, rowdot);
-    else hipLaunchKernelGGL((rowdot_kernel<false>), dim3((R + 3) / 4), dim3(256), 0, st, Y, R, d_out, v, rowdot);
+hipError_t reward_accumulate(hipStream_t st, int n_items, const void* const* Y, const int* d_out, const float* const* v, int y_dtype,
+                             int R, const int32_t* row2cand, int K, float* rowdot, float* F) {
+    reward_args a{};
+    a.n_items = n_items;
+    a.R = R;
+    bool vec = true;
+    const int epv = y_dtype == ESSA_BF16 ? 8 : 4;
+    for (int g = 0; g < n_items; ++g) {
+        a.Y[g] = Y[g];
+        a.v[g] = v[g];
+        a.d_out[g] = d_out[g];
+        vec = vec && d_out[g] % epv == 0 && ((uintptr_t)Y[g] & 15) == 0 && ((uintptr_t)v[g] & 15) == 0;
+    }
+    const dim3 grid((R + 3) / 4);
+    if (y_dtype == ESSA_BF16) {
+        if (vec) hipLaunchKernelGGL((rowdot_kernel<true, true>), grid, dim3(256), 0, st, a, rowdot);
+        else hipLaunchKernelGGL((rowdot_kernel<true, false>), grid, dim3(256), 0, st, a, rowdot);
+    } else {
+        if (vec) hipLaunchKernelGGL((rowdot_kernel<false, true>), grid, dim3(256), 0, st, a, rowdot);
+        else hipLaunchKernelGGL((rowdot_kernel<false, false>), grid, dim3(256), 0, st, a, rowdot);
+    }
     hipLaunchKernelGGL(cand_mean_kernel, dim3(K), dim3(256), 0, st, rowdot, row2cand, R, F);
     return hipGetLastError();
 }

@@ -14,6 +14,7 @@
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) int i32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
@@ -51,15 +52,14 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
 // ------------------------------------------------------------------------------------------------
 // prep kernel (1024 threads): two kinds of workgroups in one launch.
 //  (a) quantise four activation rows into limbs, one row per 256 threads (once per distinct X of the group);
-//  (b) for one item and 32 rows: t = V_A^T x by bf16 MFMA against the head+tail copy of V_A -- the 16 waves
-//      split K and their partial tiles are summed through LDS in a fixed order -- then
-//      u = sB_c * (M (sA_c * t)), stored as bf16 head+tail for the GEMM epilogue.
+//  (b) for one item, 32 rows and one K slice of 1024: the partial t = V_A^T x by bf16 MFMA against the head+tail
+//      copy of V_A; the 16 waves split the slice and their tiles are summed through LDS in a fixed order.  The
+//      GEMM kernel adds the slices up and turns t into u = sB_c * (M (sA_c * t)).
 // ------------------------------------------------------------------------------------------------
 constexpr int PREP_NT = 1024;
 
 __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     __shared__ __attribute__((aligned(16))) float part[8][2][16][64];   // lora role: partial tiles of 8 waves (64 KB)
-    __shared__ float tvec[32][33];
     __shared__ float wred[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
@@ -118,12 +118,13 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         if (t256 == 0) it.xdelta[i] = amax > 0.f ? amax / top : 0.f;
         return;
     }
-    // ---- (b) rank-space vector u for 32 rows of one item ------------------------------------------
+    // ---- (b) partial t = V_A^T x for 32 rows of one item over one K slice --------------------------------
     const int lb = b - n_qblocks;
     int g = 0;
     while (lb >= a.lora_start[g + 1]) ++g;
     const fwd_item& it = a.it[g];
-    const int r0 = (lb - a.lora_start[g]) * 32;
+    const int S = it.tslices;
+    const int r0 = ((lb - a.lora_start[g]) / S) * 32, slice = (lb - a.lora_start[g]) % S;
     const int l32 = lane & 31, h = lane >> 5;
     const int din = it.d_in, rp = it.rp, nbv = rp / 16, R = it.R;
     const int arow = min(r0 + l32, R - 1);
@@ -133,28 +134,26 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     f32x16 acc0 = {0}, acc1 = {0};
     const int ksteps = din / 16;
     if (!(a.flags & ESSA_BASE_ONLY)) {
-        // wave w takes k steps w, w+16, ...; four steps' loads are issued before their MFMAs
-        for (int ks0 = wave; ks0 < ksteps; ks0 += 64) {
-            u32x4 xa[4], v0[4], v1[4];
+        // wave w takes steps slice*64 + w + 16u, u = 0..3; all loads are issued before the MFMAs
+        u32x4 xa[4], v0[4], v1[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int ks = ks0 + 16 * u;
-                xa[u] = v0[u] = v1[u] = (u32x4){0, 0, 0, 0};
-                if (ks < ksteps) {
-                    xa[u] = *reinterpret_cast<const u32x4*>(xp + ks * 16);
-                    v0[u] = *reinterpret_cast<const u32x4*>(vp0 + ks * 16);
-                    if (nbv == 2) v1[u] = *reinterpret_cast<const u32x4*>(vp1 + ks * 16);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v0[u]), acc0, 0, 0, 0);
-                if (nbv == 2)
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v1[u]), acc1, 0, 0, 0);
+        for (int u = 0; u < 4; ++u) {
+            const int ks = slice * 64 + wave + 16 * u;
+            xa[u] = v0[u] = v1[u] = (u32x4){0, 0, 0, 0};
+            if (ks < ksteps) {
+                xa[u] = *reinterpret_cast<const u32x4*>(xp + ks * 16);
+                v0[u] = *reinterpret_cast<const u32x4*>(vp0 + ks * 16);
+                if (nbv == 2) v1[u] = *reinterpret_cast<const u32x4*>(vp1 + ks * 16);
             }
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v0[u]), acc0, 0, 0, 0);
+            if (nbv == 2)
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v1[u]), acc1, 0, 0, 0);
+        }
     }
-    // 16 partial tiles -> 8 -> t, always in the same order
+    // 16 partial tiles -> 8 -> 1, always in the same order
     if (wave >= 8) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
@@ -179,34 +178,14 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         }
     }
     __syncthreads();
-    // t[row][j] = head part + tail part
-    for (int idx = tid; idx < 32 * rp; idx += PREP_NT) {
-        const int row = idx / rp, j = idx % rp;
-        const int q = 4 * (row >> 3) + (row & 3), lnb = 32 * ((row >> 2) & 1);
-        float t = 0.f;
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int v = half * rp + j;              // row of the head+tail copy of V_A
-            const int nb = v >> 5, ln = lnb + (v & 31);
-            t += ((part[0][nb][q][ln] + part[1][nb][q][ln]) + (part[2][nb][q][ln] + part[3][nb][q][ln])) +
-                 ((part[4][nb][q][ln] + part[5][nb][q][ln]) + (part[6][nb][q][ln] + part[7][nb][q][ln]));
-        }
-        const int c = it.row2cand[min(r0 + row, R - 1)];
-        tvec[row][j] = (j < it.r ? it.sigmaA[(size_t)c * it.sigma_stride + j] : 0.f) * t;
-    }
-    __syncthreads();
-    for (int idx = tid; idx < 32 * rp; idx += PREP_NT) {
-        const int row = idx / rp, j = idx % rp;
-        if (r0 + row >= R) continue;
-        float u = 0.f;
-        if (j < it.r && !(a.flags & ESSA_BASE_ONLY)) {
-            const int c = it.row2cand[r0 + row];
-            for (int l = 0; l < it.r; ++l) u = fmaf(it.M[j * rp + l], tvec[row][l], u);
-            u *= it.sigmaB[(size_t)c * it.sigma_stride + j];
-        }
-        const uint16_t hi = f32_to_bf16_bits(u);
-        it.U16[(size_t)(r0 + row) * 2 * rp + j] = hi;
-        it.U16[(size_t)(r0 + row) * 2 * rp + rp + j] = f32_to_bf16_bits(u - bf16_bits_to_f32(hi));
+    // element (row, v): v indexes the rows of the head+tail copy of V_A (v < rp heads, v >= rp tails)
+    const int rpad = (R + 31) / 32 * 32;
+    for (int idx = tid; idx < 32 * 2 * rp; idx += PREP_NT) {
+        const int row = idx / (2 * rp), v = idx % (2 * rp);
+        const int q = 4 * (row >> 3) + (row & 3), nb = v >> 5, ln = 32 * ((row >> 2) & 1) + (v & 31);
+        const float t = ((part[0][nb][q][ln] + part[1][nb][q][ln]) + (part[2][nb][q][ln] + part[3][nb][q][ln])) +
+                        ((part[4][nb][q][ln] + part[5][nb][q][ln]) + (part[6][nb][q][ln] + part[7][nb][q][ln]));
+        it.Tpart[((size_t)slice * rpad + r0 + row) * 2 * rp + v] = t;
     }
 }
 
@@ -285,7 +264,9 @@ constexpr size_t gemm_smem_bytes() {
     constexpr size_t stages = 2 * LIMBS * BM * LROW;
     constexpr size_t exch = (size_t)4 * 2 * LIMBS * (MB >= 2 ? MB / 2 : 1) * 4096;
     constexpr size_t ctile = BM * (128 * (YBF16 ? 2 : 4) + 16);
-    constexpr size_t big = stages > exch ? (stages > ctile ? stages : ctile) : (exch > ctile ? exch : ctile);
+    constexpr size_t pre = stages + BM * 64 * 4 + BM * 33 * 4 + 32 * 33 * 4;   // + t sums, sA*t, core matrix (before the main loop)
+    constexpr size_t m1 = pre > exch ? pre : exch;
+    constexpr size_t big = m1 > ctile ? m1 : ctile;
     return big + BM * 4 + BM * UROW;
 }
 
@@ -351,12 +332,80 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
             }
         }
         if (tid < BM) xd[tid] = it.xdelta[min(m0 + tid, R - 1)];
-        // u tile: BM rows x (2 rp bf16) bytes, 16 bytes per thread
-        const int upr = rp / 4;                            // 16-byte pieces per row (2*rp*2 / 16)
-        for (int p = tid; p < BM * upr; p += NT) {
-            const int row = p / upr, piece = p % upr;
-            *reinterpret_cast<u32x4*>(utile + (size_t)row * UROW + piece * 16) =
-                *reinterpret_cast<const u32x4*>(it.U16 + (size_t)min(m0 + row, R - 1) * 2 * rp + piece * 8);
+    }
+    if (!DUMP) {
+        // u tile: add up the K slices of t = V_A^T x, then u = sB_c * (M (sA_c * t)), kept as bf16 head+tail.
+        // These loads fly together with the first weight and activation tiles.
+        constexpr size_t STG = (size_t)2 * LIMBS * BM * LROW;
+        float* tsum = reinterpret_cast<float*>(smem + STG);                        // [BM][2 rp]
+        float* tvec = tsum + BM * 64;                                              // [BM][33]
+        float* Ms = tvec + BM * 33;                                                // [rp][33]
+        const int rpad = (R + 31) / 32 * 32, S = it.tslices, tw = 2 * rp;
+        const int rsh = rp == 16 ? 4 : 5, tsh = rsh + 1;   // rp is 16 or 32: divisions become shifts
+        // every global load of this block is independent of the others' results except sigma on the candidate
+        // index; they are all issued before the first use
+        constexpr int EV = (BM * 64 / 4 + NT - 1) / NT;   // 4-column pieces of the (row, column) sums per thread at the widest rank
+        constexpr int EU = (BM * 32 + NT - 1) / NT;       // (row, j) entries of u per thread
+        int cand[EU];
+#pragma unroll
+        for (int i = 0; i < EU; ++i) {
+            const int e = tid + NT * i;
+            cand[i] = e < BM * rp ? it.row2cand[min(m0 + (e >> rsh), R - 1)] : 0;
+        }
+        f32x4 tp[EV][8];
+#pragma unroll
+        for (int i = 0; i < EV; ++i) {
+            const int e = (tid + NT * i) * 4;                   // four consecutive columns of one row
+            const int row = e >> tsh, v = e & (tw - 1);
+            const float* src = it.Tpart + (size_t)min(m0 + row, rpad - 1) * tw + v;
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl)
+                tp[i][sl] = (e < BM * tw && sl < S) ? *reinterpret_cast<const f32x4*>(src + (size_t)sl * rpad * tw) : (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+        for (int e = tid; e < rp * rp; e += NT) Ms[(e >> rsh) * 33 + (e & (rp - 1))] = it.M[e];
+        float sa[EU], sb[EU];
+#pragma unroll
+        for (int i = 0; i < EU; ++i) {
+            const int e = tid + NT * i, j = e & (rp - 1);
+            const bool ok = e < BM * rp && j < it.r;
+            sa[i] = ok ? it.sigmaA[(size_t)cand[i] * it.sigma_stride + j] : 0.f;
+            sb[i] = ok ? it.sigmaB[(size_t)cand[i] * it.sigma_stride + j] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < EV; ++i) {
+            const int e = (tid + NT * i) * 4;
+            if (e < BM * tw) {
+                f32x4 t = tp[i][0];
+#pragma unroll
+                for (int sl = 1; sl < 8; ++sl) t += tp[i][sl];       // slices beyond S hold zeros
+                *reinterpret_cast<f32x4*>(tsum + e) = t;            // e = row * tw + v
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < EU; ++i) {
+            const int e = tid + NT * i;
+            if (e < BM * rp) {
+                const int row = e >> rsh, j = e & (rp - 1);
+                tvec[row * 33 + j] = sa[i] * (tsum[row * tw + j] + tsum[row * tw + rp + j]);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < EU; ++i) {
+            const int e = tid + NT * i;
+            if (e < BM * rp) {
+                const int row = e >> rsh, j = e & (rp - 1);
+                float u = 0.f;
+                if (!(a.flags & ESSA_BASE_ONLY)) {
+                    for (int l = 0; l < it.r; ++l) u = fmaf(Ms[j * 33 + l], tvec[row * 33 + l], u);
+                    u *= sb[i];
+                }
+                const uint16_t hi = f32_to_bf16_bits(u);
+                uint16_t* urow = reinterpret_cast<uint16_t*>(utile + (size_t)row * UROW);
+                urow[j] = hi;
+                urow[rp + j] = f32_to_bf16_bits(u - bf16_bits_to_f32(hi));
+            }
         }
     }
 
@@ -559,7 +608,7 @@ void fill_prep_tables(stream_args& a) {
         a.quant_start[g] = q;
         a.lora_start[g] = l;
         if (a.it[g].x_owner) q += (a.it[g].R + 3) / 4;
-        l += (a.it[g].R + 31) / 32;
+        l += ((a.it[g].R + 31) / 32) * a.it[g].tslices;
     }
     a.quant_start[a.n_items] = q;
     a.lora_start[a.n_items] = l;

@@ -13,7 +13,7 @@ __all__ = [
     "F32", "BF16", "QUANT_INT8_PERCH", "QUANT_INT4_G128", "COMPUTE_W8A8", "LORA_ONLY", "BASE_ONLY", "COMPUTE_BF16",
     "essa_create", "essa_proj_create", "essa_cma_create", "essa_sample_candidates", "essa_philox_words",
     "essa_theta_to_sigma", "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
-    "essa_reward_accumulate", "essa_cmaes_update", "essa_rank_rewards", "essa_version", "EXPORTED_SYMBOLS",
+    "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards", "essa_version", "EXPORTED_SYMBOLS",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libessa.so")
@@ -30,7 +30,7 @@ EXPORTED_SYMBOLS = [
     "essa_cma_create", "essa_cma_destroy", "essa_cma_set_basis", "essa_cma_export", "essa_cma_import",
     "essa_sample_candidates", "essa_philox_words", "essa_theta_to_sigma",
     "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
-    "essa_reward_accumulate", "essa_cmaes_update", "essa_rank_rewards",
+    "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards",
 ]
 
 
@@ -81,6 +81,7 @@ def _load():
         "essa_svdlora_forward_group": (i32, [vp, C.POINTER(_FwdItem), i32, i32, i32, u32]),
         "essa_w8a8_accumulators": (i32, [vp, vp, vp, i32, i32, vp, vp, vp]),
         "essa_reward_accumulate": (i32, [vp, vp, i32, i32, i32, vp, vp, i32, vp]),
+        "essa_reward_accumulate_group": (i32, [vp, i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), i32, i32, vp, i32, vp]),
         "essa_cmaes_update": (i32, [vp, vp, vp, vp, i32, vp]),
         "essa_rank_rewards": (i32, [vp, vp, i32, vp]),
     }
@@ -381,6 +382,22 @@ def essa_reward_accumulate(ctx: Context, Y: torch.Tensor, v: torch.Tensor, row2c
     R, d_out = Y.shape
     _check(lib.essa_reward_accumulate(ctx._h, _dev(Y, None, "Y"), _ydtype(Y), R, d_out, _dev(v, torch.float32, "v"),
                                       _dev(row2cand, torch.int32, "row2cand"), F.numel(), _dev(F, torch.float32, "F")))
+
+
+def essa_reward_accumulate_group(ctx: Context, Ys, vs, row2cand: torch.Tensor, F: torch.Tensor):
+    """Ys, vs: lists of outputs [R, d_out_g] (one dtype) and reward vectors [d_out_g]."""
+    n = len(Ys)
+    if not 1 <= n <= MAX_GROUP or len(vs) != n:
+        raise ValueError("1..%d outputs with one vector each" % MAX_GROUP)
+    R = Ys[0].shape[0]
+    yd = _ydtype(Ys[0])
+    yp, vp_, dd = (C.c_void_p * n)(), (C.c_void_p * n)(), (C.c_int * n)()
+    for g, (Y, v) in enumerate(zip(Ys, vs)):
+        if Y.shape[0] != R or _ydtype(Y) != yd or v.numel() != Y.shape[1]:
+            raise ValueError("outputs share rows and dtype; v_g has d_out_g entries")
+        yp[g], vp_[g], dd[g] = _dev(Y, None, "Y").value, _dev(v, torch.float32, "v").value, Y.shape[1]
+    _check(lib.essa_reward_accumulate_group(ctx._h, n, yp, dd, vp_, yd, R, _dev(row2cand, torch.int32, "row2cand"), F.numel(),
+                                            _dev(F, torch.float32, "F")))
 
 
 def essa_cmaes_update(ctx: Context, cma: CmaState, seeds: torch.Tensor, rewards: torch.Tensor, order_out: torch.Tensor | None = None):

@@ -365,6 +365,13 @@ def test_reward_accumulate(essa, ctx):
     got = F.cpu().numpy()
     assert math.isnan(got[K - 1]) and math.isnan(ref[K - 1])
     np.testing.assert_allclose(got[:K - 1], ref[:K - 1], rtol=1e-5, atol=1e-6)
+    # several outputs in one call: same sum as one call per output, whatever their widths
+    Y2 = wl.f32_to_bf16_bits(g.standard_normal((R, 41)).astype(np.float32))
+    v2 = g.standard_normal(41).astype(np.float32)
+    F = torch.zeros(K, device="cuda")
+    essa.essa_reward_accumulate_group(ctx, [bf16_dev(Yb), bf16_dev(Y2)], [to_dev(v), to_dev(v2)], to_dev(r2c), F)
+    ref2 = orc.reward_accumulate(orc.reward_accumulate(np.zeros(K), wl.bf16_bits_to_f32(Yb), v, r2c, K), wl.bf16_bits_to_f32(Y2), v2, r2c, K)
+    np.testing.assert_allclose(F.cpu().numpy()[:K - 1], ref2[:K - 1], rtol=1e-5, atol=1e-6)
     Y32 = g.standard_normal((R, d)).astype(np.float32)
     F = torch.zeros(K, device="cuda")
     essa.essa_reward_accumulate(ctx, to_dev(Y32), to_dev(v), to_dev(r2c), F)
