@@ -38,6 +38,7 @@ def main():
     ap.add_argument("--rows-per-cand", type=int, default=8)
     ap.add_argument("--forward-only", action="store_true", help="time only the projections (no sampler / reward / update)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy (a reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported" % args.gpus)
@@ -119,6 +120,12 @@ def main():
         forward_all(True)
         essa.essa_cmaes_update(ctx, cma, seeds, F, None)
 
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)           # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     if args.forward_only:   # sigma must exist
         essa.essa_sample_candidates(ctx, cma, seeds, theta, None)
         essa.essa_theta_to_sigma(ctx, r, sft_A, sft_B, theta, sA, sB)
