@@ -455,13 +455,13 @@ struct reward_args {
     int n_items, R;
 };
 
-// rowdot[i] = sum over the items (in order) of <Y_item[i, :], v_item>; one wave per row, 16-byte loads when VEC
+// rowdot[i] = sum over the items (in order) of <Y_item[i, :], v_item>.  One workgroup per row; wave w takes the
+// items g = w, w+4, ...; 16-byte loads when VEC.  The per-item sums meet in LDS and are added in item order.
 template <bool YBF16, bool VEC>
 __global__ __launch_bounds__(256) void rowdot_kernel(reward_args a, float* __restrict__ rowdot) {
-    const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= a.R) return;
-    float total = 0.f;
-    for (int g = 0; g < a.n_items; ++g) {
+    __shared__ float dots[ESSA_MAX_GROUP];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, row = blockIdx.x;
+    for (int g = wave; g < a.n_items; g += 4) {
         const int d = a.d_out[g];
         const float* __restrict__ v = a.v[g];
         float s = 0.f;
@@ -496,9 +496,14 @@ __global__ __launch_bounds__(256) void rowdot_kernel(reward_args a, float* __res
         }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-        total += s;
+        if (lane == 0) dots[g] = s;
     }
-    if (lane == 0) rowdot[row] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float total = 0.f;
+        for (int g = 0; g < a.n_items; ++g) total += dots[g];
+        rowdot[row] = total;
+    }
 }
 
 // F[k] += (sum of rowdot over the rows of candidate k) / (their number); fixed-order tree, 0/0 = NaN.
@@ -640,7 +645,7 @@ hipError_t reward_accumulate(hipStream_t st, int n_items, const void* const* Y, 
         a.d_out[g] = d_out[g];
         vec = vec && d_out[g] % epv == 0 && ((uintptr_t)Y[g] & 15) == 0 && ((uintptr_t)v[g] & 15) == 0;
     }
-    const dim3 grid((R + 3) / 4);
+    const dim3 grid(R);
     if (y_dtype == ESSA_BF16) {
         if (vec) hipLaunchKernelGGL((rowdot_kernel<true, true>), grid, dim3(256), 0, st, a, rowdot);
         else hipLaunchKernelGGL((rowdot_kernel<true, false>), grid, dim3(256), 0, st, a, rowdot);
