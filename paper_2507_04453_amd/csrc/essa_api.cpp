@@ -645,8 +645,8 @@ extern "C" essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uin
         ESSA_TRY(upload(&cma->weights, w.data(), w.size()));
         cma->weights_K = K;
     }
-    // scratch: order[K] | S[(mu+1), n] | BY[(mu+1), n] | Z[mu, n]
-    const size_t rows = (size_t)c.mu + 1;
+    // scratch: order[K] | S[(mu+2), n] | BY[(mu+2), n] | Z[mu, n];  S rows: D*z_i (i < mu), z_w, D*z_w
+    const size_t rows = (size_t)c.mu + 2;
     const size_t off_S = align256((size_t)K * 4), off_BY = off_S + align256(rows * n * 4);
     const size_t off_Z = off_BY + align256(rows * n * 4);
     ESSA_TRY(essa_ws_reserve(ctx, off_Z + align256(rows * n * 4)));

@@ -26,13 +26,16 @@ __global__ __launch_bounds__(1024) void rank_kernel(const float* __restrict__ F,
     }
 }
 
-// S[mu, l] = sum_i w[i] Z[i, l], summed for i = 0..mu-1 in fp64.
-__global__ void weighted_rowsum_kernel(const float* __restrict__ Z, const float* __restrict__ w, int mu, int n, float* __restrict__ out) {
+// z_w[l] = sum_i w[i] Z[i, l], summed for i = 0..mu-1 in fp64;  out_z = z_w,  out_dz = D * z_w.
+__global__ void weighted_rowsum_kernel(const float* __restrict__ Z, const float* __restrict__ w, const float* __restrict__ D, int mu,
+                                       int n, float* __restrict__ out_z, float* __restrict__ out_dz) {
     const int l = blockIdx.x * blockDim.x + threadIdx.x;
     if (l >= n) return;
     double acc = 0.0;
     for (int i = 0; i < mu; ++i) acc += (double)w[i] * (double)Z[(size_t)i * n + l];
-    out[l] = (float)acc;
+    const float zw = (float)acc;
+    out_z[l] = zw;
+    out_dz[l] = D[l] * zw;
 }
 
 __device__ __forceinline__ double block_sum_1024(double v, double* sh) {
@@ -48,7 +51,8 @@ __device__ __forceinline__ double block_sum_1024(double v, double* sh) {
     return r;
 }
 
-// One workgroup.  BY rows 0..mu-1 are y_{i:lambda} = B D z_{i:lambda}, row mu is B z_w.
+// One workgroup.  BY rows 0..mu-1 are y_{i:lambda} = B D z_{i:lambda}, row mu is B z_w, row mu+1 is y_w = B D z_w
+// (the weighted mean of the y_i, taken before the product with B because that product is linear).
 __global__ __launch_bounds__(1024) void cma_vectors_kernel(essa_k::cma_consts c, const float* __restrict__ w, const float* __restrict__ BY,
                                                           float* __restrict__ m, float* __restrict__ p_sigma, float* __restrict__ p_c,
                                                           essa_cma_scalars* __restrict__ sc) {
@@ -69,8 +73,7 @@ __global__ __launch_bounds__(1024) void cma_vectors_kernel(essa_k::cma_consts c,
     const float h_sigma = (ps_norm / denom < (1.4 + 2.0 / ((double)n + 1.0)) * (double)c.chi_n) ? 1.0f : 0.0f;
     const float pc_coef = h_sigma * (float)sqrt(cc * (2.0 - cc) * mueff);
     for (int l = threadIdx.x; l < n; l += 1024) {
-        float yw = 0.f;
-        for (int i = 0; i < mu; ++i) yw += w[i] * BY[(size_t)i * n + l];
+        const float yw = BY[(size_t)(mu + 1) * n + l];
         m[l] += sigma * yw;
         p_c[l] = (1.0f - c.c_c) * p_c[l] + pc_coef * yw;
     }
@@ -89,7 +92,8 @@ constexpr int CV_T = 64, CV_CH = 32;
 __global__ __launch_bounds__(256) void cma_cov_kernel(essa_k::cma_consts c, const float* __restrict__ w, const float* __restrict__ BY,
                                                      const float* __restrict__ p_c, const essa_cma_scalars* __restrict__ sc,
                                                      float* __restrict__ C) {
-    __shared__ float Vi[CV_CH][CV_T], Vj[CV_CH][CV_T];
+    __shared__ __attribute__((aligned(16))) float Vi[CV_CH][CV_T], Vj[CV_CH][CV_T];
+    __shared__ float coef[CV_CH];
     const int n = c.n, mu = c.mu;
     const int i0 = blockIdx.y * CV_T, j0 = blockIdx.x * CV_T;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -97,21 +101,25 @@ __global__ __launch_bounds__(256) void cma_cov_kernel(essa_k::cma_consts c, cons
     const int nvec = mu + 1;   // vector mu is p_c with coefficient c_1
     for (int v0 = 0; v0 < nvec; v0 += CV_CH) {
         __syncthreads();
+        if (threadIdx.x < CV_CH) {
+            const int v = v0 + threadIdx.x;
+            coef[threadIdx.x] = v < mu ? sqrtf(c.c_mu * w[v]) : (v == mu ? sqrtf(c.c_1) : 0.f);
+        }
+        __syncthreads();
         for (int idx = threadIdx.x; idx < CV_CH * CV_T; idx += 256) {
             const int vv = idx / CV_T, e = idx % CV_T, v = v0 + vv;
             float a = 0.f, b = 0.f;
             if (v < nvec) {
-                const float coef = sqrtf(v < mu ? c.c_mu * w[v] : c.c_1);
                 const float* src = v < mu ? BY + (size_t)v * n : p_c;
-                if (i0 + e < n) a = coef * src[i0 + e];
-                if (j0 + e < n) b = coef * src[j0 + e];
+                if (i0 + e < n) a = coef[vv] * src[i0 + e];
+                if (j0 + e < n) b = coef[vv] * src[j0 + e];
             }
             Vi[vv][e] = a;
             Vj[vv][e] = b;
         }
         __syncthreads();
-#pragma unroll 4
-        for (int vv = 0; vv < CV_CH; ++vv) {
+        const int lim = min(CV_CH, nvec - v0);
+        for (int vv = 0; vv < lim; ++vv) {
             const float4 a = *reinterpret_cast<const float4*>(&Vi[vv][ty * 4]);
             const float4 b = *reinterpret_cast<const float4*>(&Vj[vv][tx * 4]);
             const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
@@ -123,14 +131,24 @@ __global__ __launch_bounds__(256) void cma_cov_kernel(essa_k::cma_consts c, cons
     }
     const float hs = sc->h_sigma;
     const float decay = 1.0f - c.c_1 - c.c_mu + (1.0f - hs) * c.c_1 * c.c_c * (2.0f - c.c_c);
+    const int j = j0 + tx * 4;
+    const bool vec = (n % 4 == 0) && j + 3 < n;
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
         const int i = i0 + ty * 4 + x;
         if (i >= n) continue;
+        if (vec) {
+            float4* p = reinterpret_cast<float4*>(C + (size_t)i * n + j);
+            float4 cv = *p;
+            cv.x = decay * cv.x + acc[x][0];
+            cv.y = decay * cv.y + acc[x][1];
+            cv.z = decay * cv.z + acc[x][2];
+            cv.w = decay * cv.w + acc[x][3];
+            *p = cv;
+        } else {
 #pragma unroll
-        for (int y = 0; y < 4; ++y) {
-            const int j = j0 + tx * 4 + y;
-            if (j < n) C[(size_t)i * n + j] = decay * C[(size_t)i * n + j] + acc[x][y];
+            for (int y = 0; y < 4; ++y)
+                if (j + y < n) C[(size_t)i * n + j + y] = decay * C[(size_t)i * n + j + y] + acc[x][y];
         }
     }
 }
@@ -148,7 +166,8 @@ hipError_t cma_build_rhs(hipStream_t st, const uint32_t* seeds, const int32_t* o
                          const float* D, float* S, float* Z) {
     hipError_t e = normals_scaled(st, seeds, order, c.mu, c.n, D, S, Z);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(weighted_rowsum_kernel, dim3((c.n + 255) / 256), dim3(256), 0, st, Z, w, c.mu, c.n, S + (size_t)c.mu * c.n);
+    hipLaunchKernelGGL(weighted_rowsum_kernel, dim3((c.n + 255) / 256), dim3(256), 0, st, Z, w, D, c.mu, c.n, S + (size_t)c.mu * c.n,
+                       S + (size_t)(c.mu + 1) * c.n);
     return hipGetLastError();
 }
 

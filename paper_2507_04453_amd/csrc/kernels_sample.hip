@@ -79,63 +79,70 @@ __global__ void theta_to_sigma_kernel(int P, int r, int n_top, const float* __re
     sB[idx] = b;
 }
 
-// Out[j, i] = bias[i] + scale * sum_l S[j,l] * B[i,l]        (fp32 MFMA 32x32x2)
-// One workgroup = 32 rows of B x 64 rows of S; its 8 waves interleave over chunks of 8 columns and
-// their partial tiles are summed through LDS in a fixed order (bit-reproducible).
+// Out[j, i] = bias[i] + scale * sum_l S[j,l] * B[i,l]        (fp32 MFMA 16x16x4)
+// One workgroup = 16 rows of B x (16 * JB) rows of S.  Its 8 waves interleave over chunks of 16 columns (a lane
+// loads four consecutive floats of its row, which feed four MFMA steps) and their partial tiles are summed
+// through LDS in a fixed order (bit-reproducible).  B is read exactly once when J <= 16 * JB.
 constexpr int SG_WAVES = 8;
-template <bool ALIGNED>
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+template <bool ALIGNED, int JB>
 __global__ __launch_bounds__(SG_WAVES * 64) void skinny_gemm_nt_kernel(const float* __restrict__ S, int J, const float* __restrict__ B,
                                                                       int n, const float* __restrict__ bias,
                                                                       const essa_cma_scalars* __restrict__ sc, int use_sigma,
                                                                       float* __restrict__ Out) {
-    __shared__ float red[SG_WAVES][2][16][64];
+    __shared__ __attribute__((aligned(16))) float red[SG_WAVES][JB][4][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int i0 = blockIdx.x * 32, j0 = blockIdx.y * 64;
-    const int li = lane & 31, h = lane >> 5;
-    const int i = i0 + li;
-    const int ja = j0 + li, jb = j0 + 32 + li;
-    f32x16 acc0 = {0}, acc1 = {0};
-    const int nchunks = (n + 7) / 8;
-    for (int ch = wave; ch < nchunks; ch += SG_WAVES) {
-        const int l = ch * 8 + 4 * h;
-        float a[4] = {0, 0, 0, 0}, s0[4] = {0, 0, 0, 0}, s1[4] = {0, 0, 0, 0};
-        if (ALIGNED) {
-            if (l < n) {
-                if (i < n) *reinterpret_cast<float4*>(a) = *reinterpret_cast<const float4*>(B + (size_t)i * n + l);
-                if (ja < J) *reinterpret_cast<float4*>(s0) = *reinterpret_cast<const float4*>(S + (size_t)ja * n + l);
-                if (jb < J) *reinterpret_cast<float4*>(s1) = *reinterpret_cast<const float4*>(S + (size_t)jb * n + l);
+    const int i0 = blockIdx.x * 16, j0 = blockIdx.y * 16 * JB;
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int i = i0 + l16;
+    f32x4 acc[JB];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) acc[jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const int nchunks = (n + 15) / 16;
+    auto load4 = [&](const float* base, int row, int rows, int l) {
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (row < rows) {
+            if (ALIGNED) {
+                if (l < n) v = *reinterpret_cast<const f32x4*>(base + (size_t)row * n + l);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (l + e < n) v[e] = base[(size_t)row * n + l + e];
             }
-        } else {
+        }
+        return v;
+    };
+    for (int ch0 = wave; ch0 < nchunks; ch0 += 2 * SG_WAVES) {
+        // two chunks per trip: all their loads are issued before the first MFMA
+        f32x4 a[2], sv[2][JB];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int l = (ch0 + u * SG_WAVES) * 16 + 4 * kq;      // past the end: l >= n, everything loads as zero
+            a[u] = load4(B, i, n, l);
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) sv[u][jb] = load4(S, j0 + 16 * jb + l16, J, l);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                if (l + e < n) {
-                    if (i < n) a[e] = B[(size_t)i * n + l + e];
-                    if (ja < J) s0[e] = S[(size_t)ja * n + l + e];
-                    if (jb < J) s1[e] = S[(size_t)jb * n + l + e];
-                }
-        }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], s0[e], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], s1[e], acc1, 0, 0, 0);
-        }
+                for (int jb = 0; jb < JB; ++jb) acc[jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][e], sv[u][jb][e], acc[jb], 0, 0, 0);
     }
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-        red[wave][0][q][lane] = acc0[q];
-        red[wave][1][q][lane] = acc1[q];
-    }
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) red[wave][jb][q][lane] = acc[jb][q];
     __syncthreads();
     const float scale = use_sigma ? sc->sigma : 1.0f;
-    // 2 x 16 x 64 results, 512 threads: 4 each
-    for (int idx = threadIdx.x; idx < 2 * 16 * 64; idx += SG_WAVES * 64) {
-        const int ln = idx & 63, q = (idx >> 6) & 15, blk = idx >> 10;
+    for (int idx = threadIdx.x; idx < JB * 4 * 64; idx += SG_WAVES * 64) {
+        const int ln = idx & 63, q = (idx >> 6) & 3, jb = idx >> 8;
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < SG_WAVES; ++w) sum += red[w][blk][q][ln];
-        // accumulator element q of lane ln: row (of B) 8*(q/4) + 4*(ln/32) + q%4, column (of S) ln%32
-        const int ii = i0 + 8 * (q >> 2) + 4 * (ln >> 5) + (q & 3);
-        const int jj = j0 + 32 * blk + (ln & 31);
+        for (int w = 0; w < SG_WAVES; ++w) sum += red[w][jb][q][ln];
+        // accumulator element q of lane ln: row (of B) 4*(ln/16) + q, column (of S) ln%16
+        const int ii = i0 + 4 * (ln >> 4) + q;
+        const int jj = j0 + 16 * jb + (ln & 15);
         if (ii < n && jj < J) Out[(size_t)jj * n + ii] = (bias ? bias[ii] : 0.f) + scale * sum;
     }
 }
@@ -157,13 +164,21 @@ hipError_t normals_scaled(hipStream_t st, const uint32_t* seeds, const int32_t* 
     return hipGetLastError();
 }
 
+template <int JB>
+static void launch_skinny(hipStream_t st, const float* S, int J, const float* B, int n, const float* bias, const essa_cma_scalars* sc,
+                          int use_sigma, float* Out) {
+    dim3 grid((n + 15) / 16, (J + 16 * JB - 1) / (16 * JB));
+    if (n % 4 == 0)
+        hipLaunchKernelGGL((skinny_gemm_nt_kernel<true, JB>), grid, dim3(SG_WAVES * 64), 0, st, S, J, B, n, bias, sc, use_sigma, Out);
+    else
+        hipLaunchKernelGGL((skinny_gemm_nt_kernel<false, JB>), grid, dim3(SG_WAVES * 64), 0, st, S, J, B, n, bias, sc, use_sigma, Out);
+}
+
 hipError_t skinny_gemm_nt(hipStream_t st, const float* S, int J, const float* B, int n, const float* bias,
                           const essa_cma_scalars* sc, int use_sigma, float* Out) {
-    dim3 grid((n + 31) / 32, (J + 63) / 64);
-    if (n % 4 == 0)
-        hipLaunchKernelGGL(skinny_gemm_nt_kernel<true>, grid, dim3(SG_WAVES * 64), 0, st, S, J, B, n, bias, sc, use_sigma, Out);
-    else
-        hipLaunchKernelGGL(skinny_gemm_nt_kernel<false>, grid, dim3(SG_WAVES * 64), 0, st, S, J, B, n, bias, sc, use_sigma, Out);
+    if (J <= 16) launch_skinny<1>(st, S, J, B, n, bias, sc, use_sigma, Out);
+    else if (J <= 32) launch_skinny<2>(st, S, J, B, n, bias, sc, use_sigma, Out);
+    else launch_skinny<4>(st, S, J, B, n, bias, sc, use_sigma, Out);
     return hipGetLastError();
 }
 
