@@ -34,8 +34,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--mode", choices=["w8a16", "w8a8"], default="w8a16", help="w8a16: bf16 activations as two int8 limbs on the int8 MFMA (default path); w8a8: one int8 limb")
-    ap.add_argument("--layers", type=int, default=28)
-    ap.add_argument("--rows-per-cand", type=int, default=8)
+    ap.add_argument("--workload", choices=["c2_7b_decode", "c3_32b_prefill", "c4_72b_decode", "c5_7b_es_iter"], default="c2_7b_decode",
+                    help="c2 is the configuration the headline metric is quoted on; the others are side measurements")
+    ap.add_argument("--layers", type=int, default=0, help="distinct layers cycled through (default: 28 for c2/c5, 1 for c3, 8 for c4)")
+    ap.add_argument("--rows-per-cand", type=int, default=0)
     ap.add_argument("--forward-only", action="store_true", help="time only the projections (no sampler / reward / update)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy (a reference for HBM byte counters)")
@@ -53,9 +55,15 @@ def main():
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(2)
-    cfg = wl.CONFIGS["c2_7b_decode"]
+    cfg = wl.CONFIGS[args.workload]
     hidden, kv, r, K = cfg.hidden, cfg.kv, cfg.r, cfg.K
-    layers, rows_per = args.layers, args.rows_per_cand
+    layers = args.layers or {"c2_7b_decode": 28, "c3_32b_prefill": 1, "c4_72b_decode": 8, "c5_7b_es_iter": 28}[args.workload]
+    rows_per = args.rows_per_cand or cfg.rows_per_cand
+    if args.workload in ("c3_32b_prefill", "c4_72b_decode"):
+        args.forward_only = True        # these configurations name the projections only
+    if args.workload != "c2_7b_decode":
+        args.no_cpu_baseline = True
+    quant = essa.QUANT_INT8_PERCH if cfg.quant == "int8" else essa.QUANT_INT4_G128
     R = K * rows_per
     P = layers * 4
     n = P * 2 * r
@@ -67,7 +75,7 @@ def main():
     projs, sft_A, sft_B, vecs = [], [], [], []
     for l in range(layers):
         for pi, p in enumerate(wl.make_layer(hidden, kv, r, cfg.quant, l)):
-            gp = essa.Projection(ctx, p.Wq, p.scales, None, p.A, p.B, essa.QUANT_INT8_PERCH)
+            gp = essa.Projection(ctx, p.Wq, p.scales, p.zeros, p.A, p.B, quant)
             a, b = gp.spectrum()
             projs.append(gp)
             sft_A.append(a)
@@ -82,7 +90,7 @@ def main():
 
     X1 = bf16(wl.make_x_bf16(R, hidden, 0)[0])
     X2 = bf16(wl.make_x_bf16(R, hidden, 1)[0])
-    r2c = torch.from_numpy(wl.row2cand_contiguous(K, rows_per)).cuda()
+    r2c = torch.from_numpy(wl.row2cand_interleaved(K, rows_per) if cfg.interleaved else wl.row2cand_contiguous(K, rows_per)).cuda()
     Q, d = wl.random_covariance_basis(n, 0)
     d = (d * 0.05).astype(np.float32)           # offsets of the order of 1% of a singular value
     cma = essa.CmaState(ctx, n, 0.32, None)
@@ -173,8 +181,10 @@ def main():
     # roofline of the dominant kernel (the fused-dequant MFMA GEMM, one launch per layer)
     dsum = sum(p.d_out for p in projs[:4])
     flops_per_launch = 2.0 * R * sum(p.d_out * (p.d_in + r) for p in projs[:4])
-    bytes_per_launch = sum(p.d_out * p.d_in + 4 * p.d_out + 2 * 2 * 16 * p.d_out for p in projs[:4]) \
-        + 2 * R * hidden * (1 if args.mode == "w8a8" else 2) + 2 * R * dsum + 4 * R * 2 * 16 * 2
+    wbytes = (lambda p: p.d_out * p.d_in + 4 * p.d_out) if cfg.quant == "int8" else (lambda p: p.d_out * p.d_in // 2 + 4 * p.d_out * (p.d_in // 128))
+    # weights once + scales + U_B, two distinct X in, four Y out, rank-space vectors
+    bytes_per_launch = sum(wbytes(p) + 2 * 2 * r * p.d_out for p in projs[:4]) \
+        + 2 * R * hidden * (1 if args.mode == "w8a8" else 2) + 2 * R * dsum + 4 * R * 2 * r * 2
     avg_s = (gemm_ms / max(gemm_launches, 1)) * 1e-3
     t_mfma = flops_per_launch / (MFMA_PEAK_TFLOPS[args.mode] * 1e12)
     t_hbm = bytes_per_launch / (HBM_PEAK_GBS * 1e9)
@@ -184,7 +194,7 @@ def main():
     else:
         ach = bytes_per_launch / avg_s / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
-    roof.update({"kernel": "gemm_i8_kernel", "avg_launch_us": avg_s * 1e6, "launches": gemm_launches,
+    roof.update({"kernel": "gemm_i8_kernel" if cfg.quant == "int8" else "gemm_mfma_kernel", "avg_launch_us": avg_s * 1e6, "launches": gemm_launches,
                  "flops_per_launch": flops_per_launch, "bytes_per_launch": bytes_per_launch,
                  "achieved_GBs": bytes_per_launch / avg_s / 1e9, "achieved_TFLOPs": flops_per_launch / avg_s / 1e12})
 
@@ -196,8 +206,9 @@ def main():
         "metric": "candidate-tokens/s through batched SVD-LoRA projections", "value": value, "unit": "candidate-tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if args.mode == "w8a16" else "int8", "data": "synthetic",
-        "config": {"workload": "c2_7b_decode", "layers": layers, "hidden": hidden, "kv": kv, "rank": r, "population": K,
-                   "rows": R, "weights": "int8 per-channel", "activations": "bf16", "mode": args.mode,
+        "config": {"workload": args.workload, "layers": layers, "hidden": hidden, "kv": kv, "rank": r, "population": K,
+                   "rows": R, "weights": "int8 per-channel" if cfg.quant == "int8" else "int4 g128 asymmetric", "activations": "bf16",
+                   "mode": args.mode,
                    "step": "forward only" if args.forward_only else "sample + sigma + %d layers x (q,k,v,o) + reward + update" % layers},
         "roofline": roof, "cpu_baseline": cpu, "breakdown_ms": breakdown,
         "ms_per_step_with_events": 1e3 * elapsed_profiled / args.steps,
