@@ -153,7 +153,7 @@ extern "C" void essa_proj_destroy(essa_proj* p) {
     if (!p) return;
     (void)hipSetDevice(p->device);
     (void)hipDeviceSynchronize();
-    void* ptrs[] = {p->Wq, p->scale, p->zero, p->VA32, p->VA16, p->UB32, p->UB16, p->M, p->Wt, p->VAp};
+    void* ptrs[] = {p->Wq, p->scale, p->zero, p->VA32, p->VA16, p->UB32, p->UB16, p->M, p->Wt, p->VAp, p->St, p->SZ16};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
     delete p;
@@ -274,6 +274,44 @@ extern "C" essa_status essa_proj_create(essa_ctx* ctx, const essa_proj_desc* d, 
         for (size_t i = 0; i < ng; ++i) { s[i] = f16_to_f32(sh[i]); z[i] = f16_to_f32(zh[i]); }
         ESSA_TRY(upload(&p->scale, s.data(), ng));
         ESSA_TRY(upload(&p->zero, z.data(), ng));
+        // fast-path copies: nibbles tiled for the int8 MFMA operand, scales group major, -scale*zero as bf16 head+tail
+        p->d_in_pad = (din + 511) / 512 * 512;
+        p->n_blocks = (dout + 31) / 32;
+        p->Gp = (p->groups + 15) / 16 * 16;
+        const int pairs = p->d_in_pad / 64, nbs = p->n_blocks;
+        const uint8_t* src = (const uint8_t*)d->Wq;
+        auto nib = [&](int o, int k) -> uint8_t {
+            if (o >= dout || k >= din) return 0;
+            const uint8_t b = src[((size_t)o * din + k) >> 1];
+            return (k & 1) ? (uint8_t)(b >> 4) : (uint8_t)(b & 15);
+        };
+        std::vector<int8_t> Wt((size_t)pairs * nbs * 1024, 0);
+        for (int pr = 0; pr < pairs; ++pr)
+            for (int nb = 0; nb < nbs; ++nb)
+                for (int hh = 0; hh < 2; ++hh)
+                    for (int n = 0; n < 32; ++n)
+                        for (int j = 0; j < 16; ++j) {
+                            const int o = nb * 32 + n, k0 = pr * 64 + 16 * hh + j;
+                            Wt[((size_t)pr * nbs + nb) * 1024 + (size_t)(hh * 32 + n) * 16 + j] = (int8_t)(nib(o, k0) | (nib(o, k0 + 32) << 4));
+                        }
+        ESSA_TRY(upload(&p->Wt, Wt.data(), Wt.size()));
+        const int gpad = p->d_in_pad / 128;
+        std::vector<float> St((size_t)gpad * nbs * 32, 0.f);
+        std::vector<uint16_t> SZ((size_t)nbs * 32 * 2 * p->Gp, 0);
+        for (int o = 0; o < dout; ++o)
+            for (int g = 0; g < p->groups; ++g) {
+                const float sv = s[(size_t)o * p->groups + g], zv = z[(size_t)o * p->groups + g];
+                St[(size_t)g * nbs * 32 + o] = sv;
+                const float m = -(sv * zv);
+                const uint16_t hi = f32_to_bf16_rne(m);
+                uint32_t hb = (uint32_t)hi << 16;
+                float hf;
+                std::memcpy(&hf, &hb, 4);
+                SZ[((size_t)o * 2 + 0) * p->Gp + g] = hi;
+                SZ[((size_t)o * 2 + 1) * p->Gp + g] = f32_to_bf16_rne(m - hf);
+            }
+        ESSA_TRY(upload(&p->St, St.data(), St.size()));
+        ESSA_TRY(upload(&p->SZ16, SZ.data(), SZ.size()));
     }
     *out = p.release();
     return ESSA_OK;
@@ -454,11 +492,12 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
         k.Wq = p->Wq; k.scale = p->scale; k.zero = p->zero; k.VA32 = p->VA32; k.VA16 = p->VA16;
         k.UB32 = p->UB32; k.UB16 = p->UB16; k.M = p->M;
         k.Wt = p->Wt; k.VAp = p->VAp; k.d_in_pad = p->d_in_pad; k.n_blocks = p->n_blocks;
+        k.St = p->St; k.SZ16 = p->SZ16; k.Gp = p->Gp;
         out.push_back(k);
         const size_t R = it.R;
         total += align256(R * p->rp * 4) + align256(R * p->rp * 4) + align256(R * (p->groups > 0 ? p->groups : 1) * 4);
         if (flags & ESSA_COMPUTE_W8A8) total += align256(R * (size_t)p->d_in) + align256(R * 4);
-        if (p->Wt) total += 2 * align256((R + 255) / 256 * 256 * (size_t)p->d_in_pad) + align256(R * 4) +
+        if (p->Wt) total += 2 * align256((R + 255) / 256 * 256 * (size_t)p->d_in_pad) + align256(R * 4) + align256(R * 2 * (size_t)(p->Gp + 16) * 2) +
                             align256((size_t)((p->d_in / 16 + 63) / 64) * ((R + 31) / 32 * 32) * 2 * p->rp * 4);
     }
     ESSA_TRY(essa_ws_reserve(ctx, total));
@@ -479,15 +518,16 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
             const essa_k::fwd_item* first = nullptr;
             for (auto& o : out) {
                 if (&o == &k) break;
-                if (o.Wt && o.X == k.X && o.R == k.R && o.d_in == k.d_in) { first = &o; break; }
+                if (o.Wt && o.X == k.X && o.R == k.R && o.d_in == k.d_in && o.quant == k.quant) { first = &o; break; }
             }
             if (first) {
-                k.Xh = first->Xh; k.Xl = first->Xl; k.xdelta = first->xdelta; k.x_owner = 0;
+                k.Xh = first->Xh; k.Xl = first->Xl; k.xdelta = first->xdelta; k.XS16 = first->XS16; k.x_owner = 0;
             } else {
                 const size_t limb = align256((R + 255) / 256 * 256 * (size_t)k.d_in_pad);
                 k.Xh = (int8_t*)w; w += limb;
                 k.Xl = (int8_t*)w; w += limb;
                 k.xdelta = (float*)w; w += align256(R * 4);
+                k.XS16 = (uint16_t*)w; w += align256(R * 2 * (size_t)(k.Gp + 16) * 2);
                 k.x_owner = 1;
             }
         }
@@ -497,8 +537,8 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
 
 // int8 weights, bf16 activations, 16-byte rows: the int8-limb kernels take the item
 static bool takes_stream(const essa_k::fwd_item& k, int x_dtype, unsigned flags) {
-    return k.Wt && x_dtype == ESSA_BF16 && k.d_in % 16 == 0 && !(flags & ESSA_COMPUTE_BF16) &&
-           ((uintptr_t)k.X & 15) == 0;
+    return k.Wt && x_dtype == ESSA_BF16 && k.d_in % 16 == 0 && !(flags & ESSA_COMPUTE_BF16) && ((uintptr_t)k.X & 15) == 0 &&
+           !(k.quant == ESSA_QUANT_INT4_G128 && (flags & ESSA_COMPUTE_W8A8));
 }
 
 static essa_status run_items(essa_ctx* ctx, std::vector<essa_k::fwd_item>& ks, int x_dtype, int y_dtype, unsigned flags) {
@@ -514,7 +554,20 @@ static essa_status run_items(essa_ctx* ctx, std::vector<essa_k::fwd_item>& ks, i
     hipEvent_t e0, e1;
     ESSA_TRY(next_events(ctx, &e0, &e1));
     const unsigned kflags = flags & ~ESSA_COMPUTE_BF16;
-    if (!fast.empty()) ESSA_HIP(essa_k::forward_stream(ctx->stream, fast.data(), (int)fast.size(), y_dtype, kflags, e0, e1));
+    // int8 and 4-bit items of one group go to different instantiations of the GEMM
+    std::vector<essa_k::fwd_item> f8, f4;
+    for (auto& k : fast) (k.quant == ESSA_QUANT_INT8_PERCH ? f8 : f4).push_back(k);
+    for (auto* grp : {&f8, &f4}) {
+        for (size_t i = 0; i < grp->size(); ++i) {          // every set of limbs needs exactly one producer in its launch
+            bool found = false;
+            for (size_t j = 0; j < i; ++j) found = found || ((*grp)[j].x_owner && (*grp)[j].Xh == (*grp)[i].Xh);
+            (*grp)[i].x_owner = found ? 0 : 1;
+        }
+        if (!grp->empty()) {
+            ESSA_HIP(essa_k::forward_stream(ctx->stream, grp->data(), (int)grp->size(), y_dtype, kflags, e0, e1));
+            e0 = e1 = nullptr;
+        }
+    }
     if (!rest.empty())
         ESSA_HIP(essa_k::forward_group(ctx->stream, rest.data(), (int)rest.size(), x_dtype, y_dtype, kflags,
                                        fast.empty() ? e0 : nullptr, fast.empty() ? e1 : nullptr));

@@ -57,6 +57,11 @@ struct essa_proj {
     int d_in_pad = 0;          // d_in rounded up to 512 (zero weights beyond d_in)
     int n_blocks = 0;          // ceil(d_out / 32)
     uint16_t* VAp = nullptr;   // [2*rp, d_in] bf16: rows 0..rp-1 heads of V_A's columns, rows rp..2rp-1 their tails
+    // 4-bit weights on the fast path: Wt holds nibbles ([d_in_pad/64][n_blocks][2][32][16] bytes: byte j of lane
+    // (h, n) = columns 64p+16h+j (low nibble) and 64p+32+16h+j (high nibble) of channel n)
+    float* St = nullptr;       // [d_in_pad/128][n_blocks*32] group scales, group major
+    uint16_t* SZ16 = nullptr;  // [n_blocks*32][2][Gp] bf16 head and tail of -scale*zero
+    int Gp = 0;                // groups rounded up to 16
     std::vector<float> sA, sB; // own singular values, host copies
 };
 
@@ -140,6 +145,10 @@ struct fwd_item {              // one projection of a grouped forward, device po
     int8_t* Xl;                // same, low limb
     float* xdelta;             // [R] value of one unit of the fixed-point row
     int x_owner;               // 1: this item's rows are quantised by the prep kernel (first user of that X)
+    const float* St;
+    const uint16_t* SZ16;
+    int Gp;
+    uint16_t* XS16;            // [R][2][Gp] bf16 head and tail of delta_i * (sum of the row's fixed-point activations over a group)
     float* Tpart;              // [tslices][R rounded up to 32][2*rp] partial sums of V_A^T x over K slices (head and tail columns)
     int tslices;               // K slices of 64 steps of 16
 };

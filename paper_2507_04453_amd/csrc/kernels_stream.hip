@@ -96,6 +96,7 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         uint2* lrow = reinterpret_cast<uint2*>(it.Xl + (size_t)i * dpad);
         for (int c = t256; c < dpad / 8; c += 256) {
             uint32_t hi[2] = {0, 0}, lo[2] = {0, 0};
+            int qsum = 0;
             if (c < nch) {
                 const u32x4 v = xrow[c];
 #pragma unroll
@@ -104,6 +105,7 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
                     float q = rintf(x * inv);
                     q = fminf(fmaxf(q, -top), top);
                     const int qi = (int)q;
+                    qsum += qi;
                     if (a.limbs == 2) {
                         hi[e >> 2] |= (uint32_t)((qi >> 7) & 0xff) << (8 * (e & 3));   // arithmetic shift: hi in [-128,127]
                         lo[e >> 2] |= (uint32_t)(qi & 127) << (8 * (e & 3));           // lo in [0,127]
@@ -114,7 +116,26 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
             }
             hrow[c] = make_uint2(hi[0], hi[1]);
             if (a.limbs == 2) lrow[c] = make_uint2(lo[0], lo[1]);
+            if (it.quant == ESSA_QUANT_INT4_G128) {
+                // sum of the row's fixed-point activations over each group of 128 columns (16 consecutive lanes),
+                // times delta: what the zero-points of the 4-bit format multiply.  Kept as bf16 head + tail.
+                int gs = qsum;
+#pragma unroll
+                for (int off = 8; off > 0; off >>= 1) gs += __shfl_xor(gs, off, 64);
+                const int grp16 = c >> 4;
+                if ((lane & 15) == 0 && grp16 < it.Gp) {
+                    const float xs = (amax > 0.f ? amax / top : 0.f) * (float)gs;
+                    const uint16_t xh = f32_to_bf16_bits(xs);
+                    it.XS16[(size_t)i * 2 * it.Gp + grp16] = xh;
+                    it.XS16[(size_t)i * 2 * it.Gp + it.Gp + grp16] = f32_to_bf16_bits(xs - bf16_bits_to_f32(xh));
+                }
+            }
         }
+        if (it.quant == ESSA_QUANT_INT4_G128)
+            for (int gq = dpad / 128 + t256; gq < it.Gp; gq += 256) {
+                it.XS16[(size_t)i * 2 * it.Gp + gq] = 0;
+                it.XS16[(size_t)i * 2 * it.Gp + it.Gp + gq] = 0;
+            }
         if (t256 == 0) it.xdelta[i] = amax > 0.f ? amax / top : 0.f;
         return;
     }
@@ -253,6 +274,48 @@ __device__ __forceinline__ void compute_tile(i32x16 (&acc)[LIMBS][MB], const u32
     }
 }
 
+// 4-bit weights: one 16-byte load holds the wave's two chunks of the tile (low / high nibbles); the group's scale
+// rides along in w[1].x.  The tile's integer sums are complete for the group (a K tile is one group of 128), so they
+// are scaled and added to the fp32 totals right away: tot += s_g * (128 * <hi, q> + <lo, q>).
+template <int LIMBS, int MB>
+__device__ __forceinline__ void compute_tile_q4(f32x16 (&tot)[MB], const u32x4 (&w)[2], const unsigned char* smem, int stage, int kh, int l32,
+                                                int h) {
+    constexpr int BM = 32 * MB;
+    i32x4 fr[2][LIMBS][MB];
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+        for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                fr[cc][l][mb] = *reinterpret_cast<const i32x4*>(smem + ((size_t)((stage * LIMBS + l) * BM + mb * 32 + l32)) * LROW +
+                                                                (2 * kh + cc) * 32 + 16 * h);
+    const u32x4 m4 = {0x0f0f0f0fu, 0x0f0f0f0fu, 0x0f0f0f0fu, 0x0f0f0f0fu};
+    const i32x4 wlo = (i32x4)(w[0] & m4), whi = (i32x4)((w[0] >> 4) & m4);
+    const float sg = __uint_as_float(w[1][0]);
+    const i32x16 zero = {0};
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        i32x16 t[LIMBS];
+#pragma unroll
+        for (int l = 0; l < LIMBS; ++l) {
+            t[l] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[0][l][mb], wlo, zero, 0, 0, 0);
+            t[l] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[1][l][mb], whi, t[l], 0, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int comb = LIMBS == 2 ? (t[0][q] << 7) + t[LIMBS - 1][q] : t[0][q];   // |t| < 2^17 per tile: no overflow
+            tot[mb][q] = fmaf(sg, (float)comb, tot[mb][q]);
+        }
+    }
+}
+
+__device__ __forceinline__ void load_w_q4(u32x4 (&w)[2], const u32x4* __restrict__ wp, size_t wstride, const float* __restrict__ sp, size_t sstride,
+                                          int kt, int kh) {
+    w[0] = wp[(size_t)(kt * 2 + kh) * wstride];
+    w[1][0] = __float_as_uint(sp[(size_t)kt * sstride]);
+}
+
 __device__ __forceinline__ void load_w(u32x4 (&w)[2], const u32x4* __restrict__ wp, size_t wstride, int kt, int kh) {
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc) w[cc] = wp[(size_t)(kt * 4 + 2 * kh + cc) * wstride];
@@ -270,7 +333,7 @@ constexpr size_t gemm_smem_bytes() {
     return big + BM * 4 + BM * UROW;
 }
 
-template <int MB, int LIMBS, bool YBF16, bool DUMP>
+template <int MB, int LIMBS, bool YBF16, bool DUMP, bool Q4>
 __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __restrict__ acc_out) {
     constexpr int BM = 32 * MB;
     constexpr int XTOT = LIMBS * BM * 8;               // 16-byte vectors of X per K tile
@@ -308,11 +371,18 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     const int8_t* Xl = it.Xl;
 
     TSTAMP(0)
+    // 4-bit: the group scale of this lane's channel, [group][channel]
+    const float* sp = Q4 ? it.St + (size_t)nbw * 32 + l32 : nullptr;
+    const size_t sstride = (size_t)it.n_blocks * 32;
+    auto fetch_w = [&](u32x4 (&w)[2], int kt) {
+        if (Q4) load_w_q4(w, wp, wstride, sp, sstride, kt, kh);
+        else load_w(w, wp, wstride, kt, kh);
+    };
     u32x4 w0[2], w1[2], w2[2], w3[2];
-    load_w(w0, wp, wstride, 0, kh);
-    load_w(w1, wp, wstride, 1, kh);
-    load_w(w2, wp, wstride, 2, kh);
-    load_w(w3, wp, wstride, 3, kh);
+    fetch_w(w0, 0);
+    fetch_w(w1, 1);
+    fetch_w(w2, 2);
+    fetch_w(w3, 3);
     u32x4 xa[XV], xb[XV];
     load_x<LIMBS, BM, XV>(xa, Xh, Xl, m0, dpad, 0, tid);
 
@@ -321,7 +391,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     float wscale = 0.f;
     u32x4 ubf[2][2];                                       // [ks][head, tail] fragments of U_B for this lane's channel
     if (!DUMP) {
-        wscale = it.scale[oc];
+        if (!Q4) wscale = it.scale[oc];
         const uint16_t* bp = it.UB16 + (size_t)oc * 2 * rp + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
@@ -410,12 +480,16 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     }
 
     i32x16 acc[LIMBS][MB];
+    f32x16 tot[MB];                                          // 4-bit only: group-scaled running totals
 #pragma unroll
-    for (int l = 0; l < LIMBS; ++l)
+    for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
+        for (int l = 0; l < LIMBS; ++l)
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[l][mb][q] = 0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) tot[mb][q] = 0.f;
+    }
 
     store_x<LIMBS, BM, XV>(xa, smem, 0, tid);
     load_x<LIMBS, BM, XV>(xa, Xh, Xl, m0, dpad, 1, tid);
@@ -428,8 +502,9 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
 #define ESSA_STEP(W, XS, KTI)                                                        \
     {                                                                                \
         const int kt_ = (KTI);                                                       \
-        compute_tile<LIMBS, MB>(acc, W, smem, kt_ & 1, kh, l32, h);                  \
-        load_w(W, wp, wstride, min(kt_ + PD, nk - 1), kh);                           \
+        if (Q4) compute_tile_q4<LIMBS, MB>(tot, W, smem, kt_ & 1, kh, l32, h);       \
+        else compute_tile<LIMBS, MB>(acc, W, smem, kt_ & 1, kh, l32, h);             \
+        fetch_w(W, min(kt_ + PD, nk - 1));                                           \
         store_x<LIMBS, BM, XV>(XS, smem, (kt_ + 1) & 1, tid);                        \
         __syncthreads();                                                             \
         load_x<LIMBS, BM, XV>(XS, Xh, Xl, m0, dpad, min(kt_ + 3, nk - 1), tid);      \
@@ -447,8 +522,14 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     // (all of them when there is only one) and hands the others to its partner.
     // exchange slot (n, writer kh, limb, j): 16 x 64 ints, written as [q/4][lane] 16-byte vectors
     auto slot = [&](int n_, int kh_, int l_, int j_) { return smem + ((size_t)((n_ * 2 + kh_) * LIMBS + l_) * MBO + j_) * 4096; };
+    if (Q4) {   // the running totals travel as bit patterns in the accumulator of limb 0
 #pragma unroll
-    for (int l = 0; l < LIMBS; ++l)
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[0][mb][q] = (int)__float_as_uint(tot[mb][q]);
+    }
+#pragma unroll
+    for (int l = 0; l < (Q4 ? 1 : LIMBS); ++l)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const bool mine = MB >= 2 ? ((mb & 1) == kh) : (kh == 0);
@@ -462,7 +543,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         }
     __syncthreads();
 #pragma unroll
-    for (int l = 0; l < LIMBS; ++l)
+    for (int l = 0; l < (Q4 ? 1 : LIMBS); ++l)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const bool mine = MB >= 2 ? ((mb & 1) == kh) : (kh == 0);
@@ -471,10 +552,13 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
                     const i32x4 o4 = *reinterpret_cast<const i32x4*>(src + (q4 * 64 + lane) * 16);
-                    acc[l][mb][4 * q4] += o4[0];
-                    acc[l][mb][4 * q4 + 1] += o4[1];
-                    acc[l][mb][4 * q4 + 2] += o4[2];
-                    acc[l][mb][4 * q4 + 3] += o4[3];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        // 4-bit: fp32 totals, always (K half 0) + (K half 1)
+                        if (Q4) tot[mb][4 * q4 + e] = kh == 0 ? tot[mb][4 * q4 + e] + __uint_as_float((uint32_t)o4[e])
+                                                              : __uint_as_float((uint32_t)o4[e]) + tot[mb][4 * q4 + e];
+                        else acc[l][mb][4 * q4 + e] += o4[e];
+                    }
                 }
             }
         }
@@ -506,9 +590,26 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         for (int q = 0; q < 16; ++q) {
             const int rl = mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
             const float sc = xd[rl] * wscale;
-            if (LIMBS == 2) v[q] = fmaf(128.0f, (float)acc[0][mb][q], (float)acc[LIMBS - 1][mb][q]) * sc;
+            if (Q4) v[q] = tot[mb][q] * xd[rl];
+            else if (LIMBS == 2) v[q] = fmaf(128.0f, (float)acc[0][mb][q], (float)acc[LIMBS - 1][mb][q]) * sc;
             else v[q] = (float)acc[0][mb][q] * sc;
             if (a.flags & ESSA_LORA_ONLY) v[q] = 0.f;
+        }
+        if (Q4 && !(a.flags & ESSA_LORA_ONLY)) {
+            // zero-point term of the asymmetric format, - sum_g (s z)[o,g] * (delta_i * sum_{k in g} x^[i,k]): one more
+            // low-rank product over the groups, bf16 head+tail operands straight from memory
+            const int Gp = it.Gp;
+            const uint16_t* xs = it.XS16 + (size_t)min(m0 + mb * 32 + l32, R - 1) * 2 * Gp + 8 * h;
+            const uint16_t* sz = it.SZ16 + (size_t)(nbw * 32 + l32) * 2 * Gp + 8 * h;
+            for (int ks = 0; ks < Gp / 16; ++ks) {
+                const bf16x8 xa_hi = *reinterpret_cast<const bf16x8*>(xs + ks * 16);
+                const bf16x8 xa_lo = *reinterpret_cast<const bf16x8*>(xs + Gp + ks * 16);
+                const bf16x8 zb_hi = *reinterpret_cast<const bf16x8*>(sz + ks * 16);
+                const bf16x8 zb_lo = *reinterpret_cast<const bf16x8*>(sz + Gp + ks * 16);
+                v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa_lo, zb_hi, v, 0, 0, 0);
+                v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa_hi, zb_lo, v, 0, 0, 0);
+                v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa_hi, zb_hi, v, 0, 0, 0);
+            }
         }
         if (!(a.flags & ESSA_BASE_ONLY)) {
             // rank-r term U_B u_i: bf16 head+tail operands, lo*hi + hi*lo + hi*hi per 16 rank columns
@@ -559,7 +660,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     TSTAMP(5)
 }
 
-template <int MB, int LIMBS, bool YBF16, bool DUMP>
+template <int MB, int LIMBS, bool YBF16, bool DUMP, bool Q4 = false>
 hipError_t launch_gemm(hipStream_t st, stream_args& a, int32_t* acc_out) {
     int total = 0;
     for (int g = 0; g < a.n_items; ++g) {
@@ -569,7 +670,7 @@ hipError_t launch_gemm(hipStream_t st, stream_args& a, int32_t* acc_out) {
     a.tile_start[a.n_items] = total;
     constexpr size_t smem = gemm_smem_bytes<MB, LIMBS, YBF16>();
     static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
-    auto kern = gemm_i8_kernel<MB, LIMBS, YBF16, DUMP>;
+    auto kern = gemm_i8_kernel<MB, LIMBS, YBF16, DUMP, Q4>;
     static bool attr_done = false;   // one flag per instantiation
     if (!attr_done && smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -580,12 +681,12 @@ hipError_t launch_gemm(hipStream_t st, stream_args& a, int32_t* acc_out) {
     return hipGetLastError();
 }
 
-template <int LIMBS, bool YBF16>
+template <int LIMBS, bool YBF16, bool Q4>
 hipError_t launch_gemm_mb(hipStream_t st, stream_args& a, int mb) {
     switch (mb) {
-        case 1: return launch_gemm<1, LIMBS, YBF16, false>(st, a, nullptr);
-        case 2: return launch_gemm<2, LIMBS, YBF16, false>(st, a, nullptr);
-        default: return launch_gemm<4, LIMBS, YBF16, false>(st, a, nullptr);
+        case 1: return launch_gemm<1, LIMBS, YBF16, false, Q4>(st, a, nullptr);
+        case 2: return launch_gemm<2, LIMBS, YBF16, false, Q4>(st, a, nullptr);
+        default: return launch_gemm<4, LIMBS, YBF16, false, Q4>(st, a, nullptr);
     }
 }
 
@@ -630,8 +731,10 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
     const int mb = pick_mb(a);
     if (ev_start) (void)hipEventRecord(ev_start, st);
     hipError_t e;
-    if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true>(st, a, mb) : launch_gemm_mb<2, false>(st, a, mb);
-    else e = y_dtype == ESSA_BF16 ? launch_gemm_mb<1, true>(st, a, mb) : launch_gemm_mb<1, false>(st, a, mb);
+    if (items[0].quant == ESSA_QUANT_INT4_G128)   // all items of a call share the weight format
+        e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true, true>(st, a, mb) : launch_gemm_mb<2, false, true>(st, a, mb);
+    else if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true, false>(st, a, mb) : launch_gemm_mb<2, false, false>(st, a, mb);
+    else e = y_dtype == ESSA_BF16 ? launch_gemm_mb<1, true, false>(st, a, mb) : launch_gemm_mb<1, false, false>(st, a, mb);
     if (ev_stop) (void)hipEventRecord(ev_stop, st);
     return e != hipSuccess ? e : hipGetLastError();
 }
