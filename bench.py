@@ -194,6 +194,10 @@ def main():
     else:
         ach = bytes_per_launch / avg_s / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
+    # HBM-side bytes per GEMM launch from rocprofv3 --pmc (profiles/c2_7b_decode_gemm_i8_hbm_traffic.md: reads scaled by the
+    # factor a plain 256 MiB copy gives, 2.0; writes 1.0); measured for the default workload and mode only
+    if args.workload == "c2_7b_decode" and args.mode == "w8a16" and rows_per == cfg.rows_per_cand:
+        roof["traffic"] = 74.6e6
     roof.update({"kernel": "gemm_i8_kernel" if cfg.quant == "int8" else "gemm_mfma_kernel", "avg_launch_us": avg_s * 1e6, "launches": gemm_launches,
                  "flops_per_launch": flops_per_launch, "bytes_per_launch": bytes_per_launch,
                  "achieved_GBs": bytes_per_launch / avg_s / 1e9, "achieved_TFLOPs": flops_per_launch / avg_s / 1e12})
