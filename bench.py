@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--rows-per-cand", type=int, default=0)
     ap.add_argument("--forward-only", action="store_true", help="time only the projections (no sampler / reward / update)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-pass-reward", action="store_true", help="reward as a second pass over Y instead of in the GEMM's epilogue")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy (a reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -112,9 +113,19 @@ def main():
             it.append((projs[j], X2 if pi == 3 else X1, r2c, sA[:, j, :], sB[:, j, :], Ys[pi]))
         items.append(it)
 
+    # argument blocks marshalled once; the reward share of every output tile is added by the GEMM's epilogue
+    groups = [essa.ForwardGroup(items[l], vecs[l * 4:l * 4 + 4]) for l in range(layers)]
+    rowpart = torch.empty(sum(g.blocks for g in groups), R, device="cuda")
+
     def forward_all(with_reward):
+        if with_reward and not args.two_pass_reward:
+            b = 0
+            for l in range(layers):
+                b = essa.essa_svdlora_forward_reward_group(ctx, groups[l], None, rowpart, b, flags)
+            essa.essa_reward_finish(ctx, rowpart, b, r2c, F)
+            return
         for l in range(layers):
-            essa.essa_svdlora_forward_group(ctx, items[l], flags)
+            essa.essa_svdlora_forward_group(ctx, groups[l], flags)
             if with_reward:
                 essa.essa_reward_accumulate_group(ctx, Ys, vecs[l * 4:l * 4 + 4], r2c, F)
 
@@ -143,6 +154,7 @@ def main():
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
+    enqueue = time.perf_counter() - t0      # host time to issue the K steps (the GPU runs behind it)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     # the same K steps once more with the library's HIP events around every GEMM launch (on its own stream):
@@ -216,6 +228,7 @@ def main():
                    "step": "forward only" if args.forward_only else "sample + sigma + %d layers x (q,k,v,o) + reward + update" % layers},
         "roofline": roof, "cpu_baseline": cpu, "breakdown_ms": breakdown,
         "ms_per_step_with_events": 1e3 * elapsed_profiled / args.steps,
+        "host_enqueue_ms_per_step": 1e3 * enqueue / args.steps,
     }
     print(json.dumps(out), flush=True)
 

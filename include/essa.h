@@ -164,8 +164,9 @@ essa_status essa_theta_to_sigma(essa_ctx* ctx, int P, int r, int n_top, const fl
  * Arithmetic: fp32 X -> fp32 throughout.  bf16 X with int8 weights (default): each row of x is put in
  * 15-bit fixed point relative to its largest entry (x ~ delta_i (128 hi + lo), two int8 limbs, error at most
  * amax_i / 32766 per entry) and the base term runs on the int8 MFMA with exact int32 accumulation, one pass per
- * limb; ESSA_COMPUTE_BF16 selects exact bf16 products on the bf16 MFMA (fp32 accumulation) instead, which is
- * also what 4-bit weights use.  With ESSA_COMPUTE_W8A8 the base term uses x quantised per row to one int8
+ * limb (4-bit weights likewise, their nibbles unpacked in registers, each group of 128 rescaled in fp32 and the
+ * zero-point term added as a low-rank product); ESSA_COMPUTE_BF16 selects exact bf16 products on the bf16 MFMA
+ * (fp32 accumulation) instead.  With ESSA_COMPUTE_W8A8 the base term uses x quantised per row to one int8
  * (amax/127, round to nearest even).  The LoRA term always sees the unquantised x.
  * R = 0 is a no-op.
  * ------------------------------------------------------------------------------------------- */
@@ -208,6 +209,25 @@ essa_status essa_reward_accumulate(essa_ctx* ctx, const void* Y, int y_dtype, in
 essa_status essa_reward_accumulate_group(essa_ctx* ctx, int n_items, const void* const* Y, const int* d_out,
                                          const float* const* v, int y_dtype, int R, const int32_t* row2cand, int K,
                                          float* F);
+
+/* The reward fused into the forward (same definition, no second pass over Y): forward of the group as
+ * essa_svdlora_forward_group, and for every item g, every block b of ESSA_REWARD_BLOCK consecutive output channels
+ * and every row i
+ *     rowpart[block, i] = sum over o in the block of Y_g[i,o] v_g[o]     (Y as written, i.e. after rounding to y_dtype)
+ * with the blocks of the call numbered block0, block0 + 1, ... item after item (item g has
+ * ceil(d_out_g / ESSA_REWARD_BLOCK) of them).  Nothing is accumulated: successive calls of a generation (its layers)
+ * take successive block ranges of one buffer, and essa_reward_finish adds them up in ascending order, so the reward
+ * is bit-identical from run to run.  All items share R.
+ *   v        HOST array of n_items DEVICE float pointers, v[g] of length d_out_g
+ *   rowpart  DEVICE float [block_capacity, R]
+ * essa_reward_finish: F[k] += mean over candidate k's rows of sum_{b < n_blocks} rowpart[b, i] (sums in fp64, one
+ * rounding); a candidate without rows gets NaN. */
+#define ESSA_REWARD_BLOCK 128
+essa_status essa_svdlora_forward_reward_group(essa_ctx* ctx, const essa_fwd_item* items /* HOST */, int n_items,
+                                              int x_dtype, int y_dtype, uint32_t flags, const float* const* v,
+                                              float* rowpart, int64_t block_capacity, int64_t block0);
+essa_status essa_reward_finish(essa_ctx* ctx, const float* rowpart, int64_t n_blocks, int R, const int32_t* row2cand,
+                               int K, float* F);
 
 /* ---------------------------------------------------------------------------------------------
  * Hot path 5: rank-weighted update  (paper: Algorithm 1, "each worker reconstructs the same

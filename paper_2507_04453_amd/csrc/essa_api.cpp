@@ -463,12 +463,14 @@ extern "C" essa_status essa_theta_to_sigma(essa_ctx* ctx, int P, int r, int n_to
 // hot path: forward
 // ---------------------------------------------------------------------------------------------
 static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_items, int x_dtype, int y_dtype,
-                              unsigned flags, std::vector<essa_k::fwd_item>& out, const char* who) {
+                              unsigned flags, std::vector<essa_k::fwd_item>& out, const char* who,
+                              const float* const* rv = nullptr, float* rowpart = nullptr) {
     if (x_dtype != ESSA_F32 && x_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: x_dtype %d", who, x_dtype);
     if (y_dtype != ESSA_F32 && y_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: y_dtype %d", who, y_dtype);
     if (flags & ~(ESSA_COMPUTE_W8A8 | ESSA_LORA_ONLY | ESSA_BASE_ONLY | ESSA_COMPUTE_BF16)) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: unknown flag bits 0x%x", who, flags);
     if ((flags & ESSA_LORA_ONLY) && (flags & ESSA_BASE_ONLY)) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: LORA_ONLY and BASE_ONLY exclude each other", who);
     size_t total = 0;
+    size_t block0 = 0;       // fused reward: first 128-channel block of the item within the call's range
     out.clear();
     for (int i = 0; i < n_items; ++i) {
         const essa_fwd_item& it = items[i];
@@ -493,6 +495,11 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
         k.UB32 = p->UB32; k.UB16 = p->UB16; k.M = p->M;
         k.Wt = p->Wt; k.VAp = p->VAp; k.d_in_pad = p->d_in_pad; k.n_blocks = p->n_blocks;
         k.St = p->St; k.SZ16 = p->SZ16; k.Gp = p->Gp;
+        if (rv) {
+            k.rv = rv[i];
+            k.rowpart = rowpart + block0 * (size_t)it.R;
+            block0 += (size_t)(p->d_out + ESSA_REWARD_BLOCK - 1) / ESSA_REWARD_BLOCK;
+        }
         out.push_back(k);
         const size_t R = it.R;
         total += align256(R * p->rp * 4) + align256(R * p->rp * 4) + align256(R * (p->groups > 0 ? p->groups : 1) * 4);
@@ -568,9 +575,11 @@ static essa_status run_items(essa_ctx* ctx, std::vector<essa_k::fwd_item>& ks, i
             e0 = e1 = nullptr;
         }
     }
-    if (!rest.empty())
+    if (!rest.empty()) {
         ESSA_HIP(essa_k::forward_group(ctx->stream, rest.data(), (int)rest.size(), x_dtype, y_dtype, kflags,
                                        fast.empty() ? e0 : nullptr, fast.empty() ? e1 : nullptr));
+        ESSA_HIP(essa_k::rowdot_blocks(ctx->stream, rest.data(), (int)rest.size(), y_dtype));   // no-op without reward vectors
+    }
     return ESSA_OK;
 }
 
@@ -583,6 +592,37 @@ extern "C" essa_status essa_svdlora_forward_group(essa_ctx* ctx, const essa_fwd_
     ESSA_TRY(plan_items(ctx, items, n_items, x_dtype, y_dtype, flags, ks, "essa_svdlora_forward_group"));
     if (ks.empty()) return ESSA_OK;
     return run_items(ctx, ks, x_dtype, y_dtype, flags);
+}
+
+extern "C" essa_status essa_svdlora_forward_reward_group(essa_ctx* ctx, const essa_fwd_item* items, int n_items, int x_dtype,
+                                                         int y_dtype, uint32_t flags, const float* const* v, float* rowpart,
+                                                         int64_t block_capacity, int64_t block0) {
+    const char* who = "essa_svdlora_forward_reward_group";
+    if (!ctx || !items || !v || !rowpart) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: NULL argument", who);
+    if (n_items < 1 || n_items > ESSA_MAX_GROUP) return essa_fail(ESSA_ERR_SHAPE, "%s: %d items, at most %d", who, n_items, ESSA_MAX_GROUP);
+    int64_t blocks = 0;
+    for (int g = 0; g < n_items; ++g) {
+        if (!v[g] || !items[g].proj) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: item %d has no reward vector or no projection", who, g);
+        if (items[g].R != items[0].R) return essa_fail(ESSA_ERR_SHAPE, "%s: item %d has R=%d, item 0 has R=%d", who, g, items[g].R, items[0].R);
+        blocks += (items[g].proj->d_out + ESSA_REWARD_BLOCK - 1) / ESSA_REWARD_BLOCK;
+    }
+    if (block0 < 0 || block0 + blocks > block_capacity)
+        return essa_fail(ESSA_ERR_SHAPE, "%s: blocks %lld..%lld do not fit a buffer of %lld", who, (long long)block0, (long long)(block0 + blocks), (long long)block_capacity);
+    ESSA_HIP(hipSetDevice(ctx->device));
+    std::vector<essa_k::fwd_item> ks;
+    ESSA_TRY(plan_items(ctx, items, n_items, x_dtype, y_dtype, flags, ks, who, v, rowpart + (size_t)block0 * (size_t)items[0].R));
+    if (ks.empty()) return ESSA_OK;
+    return run_items(ctx, ks, x_dtype, y_dtype, flags);
+}
+
+extern "C" essa_status essa_reward_finish(essa_ctx* ctx, const float* rowpart, int64_t n_blocks, int R, const int32_t* row2cand, int K,
+                                          float* F) {
+    if (!ctx || !rowpart || !row2cand || !F) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_reward_finish: NULL argument");
+    if (R < 1 || K < 1 || n_blocks < 1 || n_blocks > INT32_MAX) return essa_fail(ESSA_ERR_SHAPE, "essa_reward_finish: R=%d K=%d blocks=%lld", R, K, (long long)n_blocks);
+    ESSA_HIP(hipSetDevice(ctx->device));
+    ESSA_TRY(essa_ws_reserve(ctx, (size_t)essa_k::reward_slices((int)n_blocks) * R * sizeof(double)));
+    ESSA_HIP(essa_k::reward_finish(ctx->stream, rowpart, (int)n_blocks, R, row2cand, K, (double*)ctx->ws, F));
+    return ESSA_OK;
 }
 
 extern "C" essa_status essa_svdlora_forward(essa_ctx* ctx, const essa_proj* proj, const void* X, int x_dtype, int R,

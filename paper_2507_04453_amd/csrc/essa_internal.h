@@ -151,6 +151,9 @@ struct fwd_item {              // one projection of a grouped forward, device po
     uint16_t* XS16;            // [R][2][Gp] bf16 head and tail of delta_i * (sum of the row's fixed-point activations over a group)
     float* Tpart;              // [tslices][R rounded up to 32][2*rp] partial sums of V_A^T x over K slices (head and tail columns)
     int tslices;               // K slices of 64 steps of 16
+    // fused reward (optional)
+    const float* rv;           // [d_out] reward vector, or null
+    float* rowpart;            // [ceil(d_out / 128)][R] partial <Y, v> over blocks of 128 output channels
 };
 hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int x_dtype, int y_dtype,
                          unsigned flags, hipEvent_t ev_start, hipEvent_t ev_stop);
@@ -159,6 +162,12 @@ hipError_t w8a8_accumulators(hipStream_t st, const fwd_item& it, int x_dtype, in
 hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, int y_dtype, unsigned flags,
                           hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t w8a8_accumulators_stream(hipStream_t st, const fwd_item& it, int32_t* acc_out);
+// rowpart[b][i] = <Y_g[i, 128 b ..], v_g[128 b ..]> for the items that carry a reward vector (any forward path)
+hipError_t rowdot_blocks(hipStream_t st, const fwd_item* items, int n_items, int y_dtype);
+// F[k] += mean over the rows of k of the sum over all blocks of rowpart[b][i]; rowsum: [reward_slices(n_blocks)][R] scratch
+int reward_slices(int n_blocks);
+hipError_t reward_finish(hipStream_t st, const float* rowpart, int n_blocks, int R, const int32_t* row2cand, int K,
+                         double* rowsum, float* F);
 hipError_t reward_accumulate(hipStream_t st, int n_items, const void* const* Y, const int* d_out, const float* const* v,
                              int y_dtype, int R, const int32_t* row2cand, int K, float* rowdot /*[R] scratch*/, float* F);
 }  // namespace essa_k

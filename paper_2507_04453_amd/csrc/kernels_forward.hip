@@ -526,6 +526,82 @@ __global__ __launch_bounds__(256) void cand_mean_kernel(const float* __restrict_
     if (tid == 0) F[k] += (float)(ssum[0] / (double)scnt[0]);
 }
 
+// The generic-path twin of the reward partials that the int8-limb GEMM writes in its epilogue: one workgroup per
+// row; for every item and every block b of 128 output channels, rowpart[b][row] = <Y[row, 128 b ..], v[128 b ..]>.
+struct rowblock_args {
+    const void* Y[ESSA_MAX_GROUP];
+    const float* v[ESSA_MAX_GROUP];
+    float* rowpart[ESSA_MAX_GROUP];
+    int d_out[ESSA_MAX_GROUP];
+    int n_items, R;
+};
+template <bool YBF16>
+__global__ __launch_bounds__(256) void rowdot_blocks_kernel(rowblock_args a) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, row = blockIdx.x;
+    for (int g = 0; g < a.n_items; ++g) {
+        const int d = a.d_out[g];
+        const float* __restrict__ v = a.v[g];
+        for (int b = wave; b * 128 < d; b += 4) {
+            float s = 0.f;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int o = b * 128 + 2 * lane + e;
+                if (o < d) {
+                    const float y = YBF16 ? bf16_bits_to_f32(((const uint16_t*)a.Y[g])[(size_t)row * d + o]) : ((const float*)a.Y[g])[(size_t)row * d + o];
+                    s = fmaf(y, v[o], s);
+                }
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+            if (lane == 0) a.rowpart[g][(size_t)b * a.R + row] = s;
+        }
+    }
+}
+
+// rowsum[g][i] = sum of rowpart[b][i] over the blocks b = 16 (g + G q) + sl, q = 0, 1, ..., first along q inside a
+// thread, then over the 16 interleaved slices sl in ascending order: a fixed order, whatever the launch timing
+__global__ __launch_bounds__(1024) void rowpart_sum_kernel(const float* __restrict__ rowpart, int n_blocks, int R, double* __restrict__ rowsum) {
+    __shared__ double part[16][64];
+    const int c = threadIdx.x & 63, sl = threadIdx.x >> 6, i = blockIdx.x * 64 + c;
+    const int g = blockIdx.y, G = gridDim.y;
+    double s = 0.0;
+    if (i < R)
+        for (int b = 16 * g + sl; b < n_blocks; b += 16 * G) s += (double)rowpart[(size_t)b * R + i];
+    part[sl][c] = s;
+    __syncthreads();
+    if (sl == 0 && i < R) {
+        double t = part[0][c];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) t += part[q][c];
+        rowsum[(size_t)g * R + i] = t;
+    }
+}
+
+// F[k] += (sum over the rows of candidate k, and over the G slices of each row in ascending order) / (number of rows)
+__global__ __launch_bounds__(256) void cand_mean_sliced_kernel(const double* __restrict__ rowsum, int G, const int32_t* __restrict__ row2cand, int R,
+                                                              float* __restrict__ F) {
+    __shared__ double ssum[256];
+    __shared__ int scnt[256];
+    const int k = blockIdx.x, tid = threadIdx.x;
+    double s = 0.0;
+    int cnt = 0;
+    for (int i = tid; i < R; i += 256)
+        if (row2cand[i] == k) {
+            double t = rowsum[i];
+            for (int g = 1; g < G; ++g) t += rowsum[(size_t)g * R + i];
+            s += t;
+            ++cnt;
+        }
+    ssum[tid] = s;
+    scnt[tid] = cnt;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if (tid < st) { ssum[tid] += ssum[tid + st]; scnt[tid] += scnt[tid + st]; }
+        __syncthreads();
+    }
+    if (tid == 0) F[k] += (float)(ssum[0] / (double)scnt[0]);
+}
+
 }  // namespace
 
 namespace essa_k {
@@ -654,6 +730,33 @@ hipError_t reward_accumulate(hipStream_t st, int n_items, const void* const* Y, 
         else hipLaunchKernelGGL((rowdot_kernel<false, false>), grid, dim3(256), 0, st, a, rowdot);
     }
     hipLaunchKernelGGL(cand_mean_kernel, dim3(K), dim3(256), 0, st, rowdot, row2cand, R, F);
+    return hipGetLastError();
+}
+
+hipError_t rowdot_blocks(hipStream_t st, const fwd_item* items, int n_items, int y_dtype) {
+    rowblock_args a{};
+    for (int g = 0; g < n_items; ++g) {
+        if (!items[g].rv) continue;
+        a.Y[a.n_items] = items[g].Y;
+        a.v[a.n_items] = items[g].rv;
+        a.rowpart[a.n_items] = items[g].rowpart;
+        a.d_out[a.n_items] = items[g].d_out;
+        a.R = items[g].R;
+        ++a.n_items;
+    }
+    if (a.n_items == 0) return hipSuccess;
+    if (y_dtype == ESSA_BF16) hipLaunchKernelGGL((rowdot_blocks_kernel<true>), dim3(a.R), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((rowdot_blocks_kernel<false>), dim3(a.R), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+int reward_slices(int n_blocks) { return n_blocks >= 256 ? 16 : (n_blocks + 15) / 16; }
+
+hipError_t reward_finish(hipStream_t st, const float* rowpart, int n_blocks, int R, const int32_t* row2cand, int K,
+                         double* rowsum, float* F) {
+    const int G = reward_slices(n_blocks);
+    hipLaunchKernelGGL(rowpart_sum_kernel, dim3((R + 63) / 64, G), dim3(1024), 0, st, rowpart, n_blocks, R, rowsum);
+    hipLaunchKernelGGL(cand_mean_sliced_kernel, dim3(K), dim3(256), 0, st, rowsum, G, row2cand, R, F);
     return hipGetLastError();
 }
 

@@ -643,18 +643,49 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     unsigned char* Yb = reinterpret_cast<unsigned char*>(it.Y);
     const int n0 = nb0 * 32;
     const bool vec_ok = (dout % EPV == 0) && ((reinterpret_cast<uintptr_t>(it.Y) & 15) == 0);
-    for (int p = tid; p < BM * PPR; p += NT) {
+    const float* __restrict__ rv = it.rv;                 // fused reward: this tile's share of <Y[i,:], v>
+    const bool rv_vec = rv && (reinterpret_cast<uintptr_t>(rv) & 15) == 0 && dout % EPV == 0;
+#pragma unroll
+    for (int p0 = 0; p0 < BM * PPR; p0 += NT) {           // BM * PPR is a multiple of NT: every lane takes part in the shuffles
+        const int p = p0 + tid;
         const int row = p / PPR, piece = p % PPR;
         const int i = m0 + row, o = n0 + piece * EPV;
-        if (i >= R || o >= dout) continue;
+        const bool valid = i < R && o < dout;
         const unsigned char* src = smem + (size_t)row * CROW + piece * 16;
-        if (vec_ok && o + EPV <= dout) {
-            *reinterpret_cast<u32x4*>(Yb + ((size_t)i * dout + o) * ESZ) = *reinterpret_cast<const u32x4*>(src);
-        } else {
-            for (int e = 0; e < EPV && o + e < dout; ++e) {
-                if (YBF16) reinterpret_cast<uint16_t*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const uint16_t*>(src)[e];
-                else reinterpret_cast<float*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const float*>(src)[e];
+        const u32x4 val = *reinterpret_cast<const u32x4*>(src);
+        if (valid) {
+            if (vec_ok && o + EPV <= dout) {
+                *reinterpret_cast<u32x4*>(Yb + ((size_t)i * dout + o) * ESZ) = val;
+            } else {
+                for (int e = 0; e < EPV && o + e < dout; ++e) {
+                    if (YBF16) reinterpret_cast<uint16_t*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const uint16_t*>(src)[e];
+                    else reinterpret_cast<float*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const float*>(src)[e];
+                }
             }
+        }
+        if (rv) {
+            float yv[EPV], s = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                yv[e] = YBF16 ? __uint_as_float((e & 1) ? (val[e >> 1] & 0xffff0000u) : (val[e >> 1] << 16)) : __uint_as_float(val[e]);
+            if (valid) {
+                if (rv_vec && o + EPV <= dout) {
+#pragma unroll
+                    for (int e4 = 0; e4 < EPV / 4; ++e4) {
+                        const f32x4 r4 = *reinterpret_cast<const f32x4*>(rv + o + 4 * e4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) s = fmaf(yv[4 * e4 + e], r4[e], s);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e)
+                        if (o + e < dout) s = fmaf(yv[e], rv[o + e], s);
+                }
+            }
+#pragma unroll
+            for (int off = PPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+            // one partial per (128-channel block, row); the blocks are added in a fixed order later
+            if (piece == 0 && i < R) it.rowpart[(size_t)(nb0 >> 2) * R + i] = s;
         }
     }
     TSTAMP(5)

@@ -14,6 +14,7 @@ __all__ = [
     "essa_create", "essa_proj_create", "essa_cma_create", "essa_sample_candidates", "essa_philox_words",
     "essa_theta_to_sigma", "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
     "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards", "essa_version", "EXPORTED_SYMBOLS",
+    "ForwardGroup", "REWARD_BLOCK", "essa_svdlora_forward_reward_group", "essa_reward_finish",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libessa.so")
@@ -22,6 +23,7 @@ F32, BF16 = 0, 1
 QUANT_INT8_PERCH, QUANT_INT4_G128 = 0, 1
 COMPUTE_W8A8, LORA_ONLY, BASE_ONLY, COMPUTE_BF16 = 1, 2, 4, 8
 MAX_GROUP = 8
+REWARD_BLOCK = 128
 
 EXPORTED_SYMBOLS = [
     "essa_create", "essa_destroy", "essa_last_error", "essa_version", "essa_synchronize",
@@ -31,6 +33,7 @@ EXPORTED_SYMBOLS = [
     "essa_sample_candidates", "essa_philox_words", "essa_theta_to_sigma",
     "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
     "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards",
+    "essa_svdlora_forward_reward_group", "essa_reward_finish",
 ]
 
 
@@ -79,6 +82,8 @@ def _load():
         "essa_theta_to_sigma": (i32, [vp, i32, i32, i32, vp, vp, vp, i32, vp, vp]),
         "essa_svdlora_forward": (i32, [vp, vp, vp, i32, i32, vp, vp, vp, i64, i32, vp, i32, u32]),
         "essa_svdlora_forward_group": (i32, [vp, C.POINTER(_FwdItem), i32, i32, i32, u32]),
+        "essa_svdlora_forward_reward_group": (i32, [vp, C.POINTER(_FwdItem), i32, i32, i32, u32, C.POINTER(vp), vp, i64, i64]),
+        "essa_reward_finish": (i32, [vp, vp, i64, i32, vp, i32, vp]),
         "essa_w8a8_accumulators": (i32, [vp, vp, vp, i32, i32, vp, vp, vp]),
         "essa_reward_accumulate": (i32, [vp, vp, i32, i32, i32, vp, vp, i32, vp]),
         "essa_reward_accumulate_group": (i32, [vp, i32, C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), i32, i32, vp, i32, vp]),
@@ -350,23 +355,71 @@ def essa_svdlora_forward(ctx: Context, proj: Projection, X: torch.Tensor, row2ca
                                     pa, pb, stride, K, _dev(Y, None, "Y"), _ydtype(Y), flags))
 
 
+class ForwardGroup:
+    """The marshalled argument block of a grouped forward: build it once for a fixed set of tensors and pass it to
+    essa_svdlora_forward_group / essa_svdlora_forward_reward_group in place of the list, so that a call in a tight
+    loop costs one foreign call.  Holds references to the tensors it points at.
+
+    items: list of (proj, X, row2cand, sigmaA, sigmaB, Y); all X share a dtype and all Y share a dtype.
+    vs: optional list of reward vectors [d_out_g] (float32), one per item."""
+
+    def __init__(self, items, vs=None):
+        if not 1 <= len(items) <= MAX_GROUP:
+            raise ValueError("1..%d items" % MAX_GROUP)
+        self.n = len(items)
+        self.arr = (_FwdItem * self.n)()
+        self.xd = self.yd = None
+        for i, (proj, X, row2cand, sigmaA, sigmaB, Y) in enumerate(items):
+            R, K = X.shape[0], sigmaA.shape[0]
+            if X.dim() != 2 or X.shape[1] != proj.d_in or tuple(Y.shape) != (R, proj.d_out) or row2cand.numel() != R:
+                raise ValueError("item %d: X [R,d_in], Y [R,d_out], row2cand [R]" % i)
+            pa, pb, stride = _sigma_args(proj, sigmaA, sigmaB, K)
+            if self.xd is None:
+                self.xd, self.yd = _xdtype(X), _ydtype(Y)
+            elif self.xd != _xdtype(X) or self.yd != _ydtype(Y):
+                raise TypeError("all items of a group share the activation and output dtypes")
+            self.arr[i] = _FwdItem(proj._h, _dev(X, None, "X"), _dev(row2cand, torch.int32, "row2cand"), pa, pb, _dev(Y, None, "Y"), stride, R, K)
+        self.R = items[0][1].shape[0]
+        self.blocks = sum((it[0].d_out + REWARD_BLOCK - 1) // REWARD_BLOCK for it in items)
+        self.vp = None
+        if vs is not None:
+            if len(vs) != self.n:
+                raise ValueError("one reward vector per item")
+            self.vp = (C.c_void_p * self.n)()
+            for g, (v, it) in enumerate(zip(vs, items)):
+                if v.numel() != it[0].d_out or it[1].shape[0] != self.R:
+                    raise ValueError("v_g has d_out_g entries; all items share the rows")
+                self.vp[g] = _dev(v, torch.float32, "v").value
+        self._keep = (list(items), list(vs) if vs is not None else None)
+
+
 def essa_svdlora_forward_group(ctx: Context, items, flags: int = 0):
-    """items: list of (proj, X, row2cand, sigmaA, sigmaB, Y); all X share a dtype and all Y share a dtype."""
-    if not 1 <= len(items) <= MAX_GROUP:
-        raise ValueError("1..%d items" % MAX_GROUP)
-    arr = (_FwdItem * len(items))()
-    xd = yd = None
-    for i, (proj, X, row2cand, sigmaA, sigmaB, Y) in enumerate(items):
-        R, K = X.shape[0], sigmaA.shape[0]
-        if X.dim() != 2 or X.shape[1] != proj.d_in or tuple(Y.shape) != (R, proj.d_out) or row2cand.numel() != R:
-            raise ValueError("item %d: X [R,d_in], Y [R,d_out], row2cand [R]" % i)
-        pa, pb, stride = _sigma_args(proj, sigmaA, sigmaB, K)
-        if xd is None:
-            xd, yd = _xdtype(X), _ydtype(Y)
-        elif xd != _xdtype(X) or yd != _ydtype(Y):
-            raise TypeError("all items of a group share the activation and output dtypes")
-        arr[i] = _FwdItem(proj._h, _dev(X, None, "X"), _dev(row2cand, torch.int32, "row2cand"), pa, pb, _dev(Y, None, "Y"), stride, R, K)
-    _check(lib.essa_svdlora_forward_group(ctx._h, arr, len(items), xd, yd, flags))
+    """items: a ForwardGroup, or a list of (proj, X, row2cand, sigmaA, sigmaB, Y)."""
+    g = items if isinstance(items, ForwardGroup) else ForwardGroup(items)
+    _check(lib.essa_svdlora_forward_group(ctx._h, g.arr, g.n, g.xd, g.yd, flags))
+
+
+def essa_svdlora_forward_reward_group(ctx: Context, items, vs, rowpart: torch.Tensor, block0: int = 0, flags: int = 0):
+    """Forward of the group plus rowpart[block0 + b, i] = <Y[i, 128 b ..], v[128 b ..]> for the blocks of every item in turn.
+    items: a ForwardGroup built with vs (then pass vs=None), or a list plus the list of reward vectors.
+    rowpart: float32 [blocks, R].  Returns the first block after the ones written."""
+    g = items if isinstance(items, ForwardGroup) else ForwardGroup(items, vs)
+    if g.vp is None:
+        raise ValueError("the group carries no reward vectors")
+    if rowpart.dtype != torch.float32 or rowpart.dim() != 2 or rowpart.shape[1] != g.R:
+        raise ValueError("rowpart must be float32 [blocks, R]")
+    _check(lib.essa_svdlora_forward_reward_group(ctx._h, g.arr, g.n, g.xd, g.yd, flags, g.vp, _dev(rowpart, torch.float32, "rowpart"),
+                                                 rowpart.shape[0], block0))
+    return block0 + g.blocks
+
+
+def essa_reward_finish(ctx: Context, rowpart: torch.Tensor, n_blocks: int, row2cand: torch.Tensor, F: torch.Tensor):
+    """F[k] += mean over candidate k's rows of the sum of the first n_blocks rows of rowpart."""
+    R = row2cand.numel()
+    if rowpart.dtype != torch.float32 or rowpart.dim() != 2 or rowpart.shape[1] != R or not 1 <= n_blocks <= rowpart.shape[0]:
+        raise ValueError("rowpart must be float32 [>= n_blocks, R]")
+    _check(lib.essa_reward_finish(ctx._h, _dev(rowpart, torch.float32, "rowpart"), n_blocks, R, _dev(row2cand, torch.int32, "row2cand"),
+                                  F.numel(), _dev(F, torch.float32, "F")))
 
 
 def essa_w8a8_accumulators(ctx: Context, proj: Projection, X: torch.Tensor, xq_out: torch.Tensor, xscale_out: torch.Tensor,

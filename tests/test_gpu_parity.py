@@ -378,6 +378,87 @@ def test_reward_accumulate(essa, ctx):
     np.testing.assert_allclose(F.cpu().numpy()[:K - 1], orc.reward_accumulate(np.zeros(K), Y32, v, r2c, K)[:K - 1], rtol=1e-5, atol=1e-6)
 
 
+def _reward_bound(Yref, v, r2c, K, rel):
+    """|dF_k| allowed when Y carries a relative row error `rel`: rel * mean_i ||Y_i|| * ||v|| (Cauchy-Schwarz per row)."""
+    norms = np.linalg.norm(Yref, axis=1)
+    out = np.zeros(K)
+    for k in range(K):
+        sel = r2c == k
+        out[k] = rel * norms[sel].mean() * np.linalg.norm(v) if sel.any() else 0.0
+    return out
+
+
+@pytest.mark.parametrize("quant,x_fp32", [("int8", False), ("int4", False), ("int8", True)])
+def test_forward_reward_fused(essa, ctx, quant, x_fp32):
+    """Forward with the reward share added in the same launches, two 'layers' accumulated into one set of rows,
+    against the oracle's forward -> round -> reward chain."""
+    d_in, r, K, R = 256, 8, 5, 150
+    d_outs = [200, 72] if not x_fp32 else [96, 40]
+    _say("fused reward %s x_fp32=%s" % (quant, x_fp32))
+    g = np.random.default_rng(11)
+    r2c = g.integers(0, K - 1, R).astype(np.int32)          # candidate K-1 owns no row
+    rd = to_dev(r2c)
+    nblk = 2 * sum((d + essa.REWARD_BLOCK - 1) // essa.REWARD_BLOCK for d in d_outs)
+    rowpart = torch.full((nblk + 1, R), float("nan"), device="cuda")       # one spare block that must stay untouched
+    b0 = 0
+    F_ref = np.zeros(K)
+    bound = np.zeros(K)
+    F_sep = torch.zeros(K, device="cuda")
+    keep = []
+    for layer in range(2):
+        items, vs, Ys = [], [], []
+        for pi, d_out in enumerate(d_outs):
+            p = wl.make_projection("t", d_in, d_out, r, quant, layer=layer, proj=pi)
+            W, f = oracle_proj(p)
+            gp = gpu_proj(essa, ctx, p)
+            sA, sB = candidate_sigmas(f, K, 0.05, pert_id=layer * 2 + pi)
+            if x_fp32:
+                xv = wl.make_x_f32(R, d_in, x_id=layer)
+                Xd = to_dev(xv)
+                Y = torch.empty(R, d_out, device="cuda")
+            else:
+                xb, xv = wl.make_x_bf16(R, d_in, x_id=layer)
+                Xd = bf16_dev(xb)
+                Y = torch.empty(R, d_out, device="cuda", dtype=torch.bfloat16)
+            v = wl.reward_vector(d_out, layer, pi)
+            ref = orc.svdlora_forward(W, f, xv, r2c, sA, sB)
+            Yr = ref if x_fp32 else orc.round_to_bf16(ref)
+            F_ref = orc.reward_accumulate(F_ref, Yr, v, r2c, K)
+            bound += _reward_bound(Yr, v, r2c, K, 1e-4 if x_fp32 else 2e-3)
+            items.append((gp, Xd, rd, to_dev(sA), to_dev(sB), Y))
+            vs.append(to_dev(v))
+            Ys.append(Y)
+            keep.append(gp)
+        grp = essa.ForwardGroup(items, vs)
+        b0 = essa.essa_svdlora_forward_reward_group(ctx, grp, None, rowpart, b0)
+        essa.essa_reward_accumulate_group(ctx, Ys, vs, rd, F_sep)
+    assert b0 == nblk
+    with pytest.raises(essa.EssaError):                                   # a block range past the buffer is refused
+        essa.essa_svdlora_forward_reward_group(ctx, grp, None, rowpart, nblk)
+    F = torch.zeros(K, device="cuda")
+    essa.essa_reward_finish(ctx, rowpart, nblk, rd, F)
+    got, sep = F.cpu().numpy(), F_sep.cpu().numpy()
+    assert not torch.isnan(rowpart[:nblk]).any() and torch.isnan(rowpart[nblk]).all()
+    assert math.isnan(got[K - 1]) and math.isnan(F_ref[K - 1])
+    _say("  max |dF| %.3g (bound %.3g), vs two-pass GPU reward %.3g" % (np.abs(got[:K - 1] - F_ref[:K - 1]).max(), bound[:K - 1].min(),
+                                                                       np.abs(got[:K - 1] - sep[:K - 1]).max()))
+    assert np.all(np.abs(got[:K - 1] - F_ref[:K - 1]) <= bound[:K - 1])
+    # same Y, same definition: the fused sum and the two-pass sum differ by fp32 summation order only
+    np.testing.assert_allclose(got[:K - 1], sep[:K - 1], rtol=2e-5, atol=2e-6)
+    # fixed summation order: a second run gives the same bits
+    part2 = torch.empty(nblk // 2, R, device="cuda")
+    part3 = torch.empty(nblk // 2, R, device="cuda")
+    essa.essa_svdlora_forward_reward_group(ctx, grp, None, part2)
+    essa.essa_svdlora_forward_reward_group(ctx, grp, None, part3)
+    assert torch.equal(part2, part3) and torch.equal(part2, rowpart[nblk // 2:nblk])
+    F2, F3 = torch.zeros(K, device="cuda"), torch.zeros(K, device="cuda")
+    essa.essa_reward_finish(ctx, rowpart, nblk, rd, F2)
+    essa.essa_reward_finish(ctx, rowpart, nblk, rd, F3)
+    assert torch.equal(F2[:K - 1], F3[:K - 1]) and torch.equal(F2[:K - 1], F[:K - 1])
+    for gp in keep:
+        gp.close()
+
+
 @pytest.mark.parametrize("K", [1, 4, 32, 64, 128, 400, 1024])
 def test_rank_bit_exact(essa, ctx, K):
     g = np.random.default_rng(K)
