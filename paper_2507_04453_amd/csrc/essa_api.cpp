@@ -227,8 +227,11 @@ extern "C" essa_status essa_proj_create(essa_ctx* ctx, const essa_proj_desc* d, 
     ESSA_TRY(upload(&p->UB32, UB32.data(), UB32.size()));
     ESSA_TRY(upload(&p->UB16, UB16.data(), UB16.size()));
 
-    {   // V_A^T as bf16 heads and tails, for the MFMA down-projection
-        std::vector<uint16_t> VAp((size_t)2 * rp * din, 0);
+    {   // V_A^T as bf16 heads and tails, tiled for the MFMA down-projection: [k step of 16][block of 32 rows][lane][8],
+        // lane (h, l32) of a block holding row 32 b + l32 (rows 0..rp-1 heads of V_A's columns, rp..2rp-1 their
+        // tails), columns 16 ks + 8 h .. + 7 -- one contiguous kilobyte per wave load
+        const int ksteps = (din + 15) / 16, nbv = 2 * rp / 32;
+        std::vector<uint16_t> VAp((size_t)ksteps * nbv * 64 * 8, 0);
         for (int i = 0; i < din; ++i)
             for (int j = 0; j < r; ++j) {
                 const float v = (float)VA[(size_t)i * r + j];
@@ -236,8 +239,11 @@ extern "C" essa_status essa_proj_create(essa_ctx* ctx, const essa_proj_desc* d, 
                 uint32_t hb = (uint32_t)hi << 16;
                 float hf;
                 std::memcpy(&hf, &hb, 4);
-                VAp[(size_t)j * din + i] = hi;
-                VAp[(size_t)(rp + j) * din + i] = f32_to_bf16_rne(v - hf);
+                const uint16_t parts[2] = {hi, f32_to_bf16_rne(v - hf)};
+                for (int e = 0; e < 2; ++e) {
+                    const int row = e * rp + j, ks = i / 16, h = (i % 16) / 8;
+                    VAp[((((size_t)ks * nbv + row / 32) * 2 + h) * 32 + row % 32) * 8 + i % 8] = parts[e];
+                }
             }
         ESSA_TRY(upload(&p->VAp, VAp.data(), VAp.size()));
     }
@@ -512,6 +518,7 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
     for (auto& k : out) {
         const size_t R = k.R;
         k.U32 = (float*)w; w += align256(R * k.rp * 4);
+        k.SBrow = k.U32;                      // the int8-limb path keeps the gathered sigma_B where the generic path keeps u
         k.U16 = (uint16_t*)w; w += align256(R * k.rp * 4);
         k.xsum = (float*)w; w += align256(R * (k.groups > 0 ? k.groups : 1) * 4);
         if (flags & ESSA_COMPUTE_W8A8) {
@@ -544,7 +551,8 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
 
 // int8 weights, bf16 activations, 16-byte rows: the int8-limb kernels take the item
 static bool takes_stream(const essa_k::fwd_item& k, int x_dtype, unsigned flags) {
-    return k.Wt && x_dtype == ESSA_BF16 && k.d_in % 16 == 0 && !(flags & ESSA_COMPUTE_BF16) && ((uintptr_t)k.X & 15) == 0 &&
+    // at most 8 K slices of 1024 in the rank-space partial sums
+    return k.Wt && x_dtype == ESSA_BF16 && k.d_in % 16 == 0 && k.d_in <= 8192 && !(flags & ESSA_COMPUTE_BF16) && ((uintptr_t)k.X & 15) == 0 &&
            !(k.quant == ESSA_QUANT_INT4_G128 && (flags & ESSA_COMPUTE_W8A8));
 }
 

@@ -56,7 +56,7 @@ struct essa_proj {
     int8_t* Wt = nullptr;      // [d_in_pad/32][n_blocks][2][32][16]: block (kc,nb), half h, channel n, 16 consecutive k
     int d_in_pad = 0;          // d_in rounded up to 512 (zero weights beyond d_in)
     int n_blocks = 0;          // ceil(d_out / 32)
-    uint16_t* VAp = nullptr;   // [2*rp, d_in] bf16: rows 0..rp-1 heads of V_A's columns, rows rp..2rp-1 their tails
+    uint16_t* VAp = nullptr;   // [ceil(d_in/16)][2*rp/32][64][8] bf16: heads (rows 0..rp-1) and tails (rp..2rp-1) of V_A's columns, MFMA-operand tiles
     // 4-bit weights on the fast path: Wt holds nibbles ([d_in_pad/64][n_blocks][2][32][16] bytes: byte j of lane
     // (h, n) = columns 64p+16h+j (low nibble) and 64p+32+16h+j (high nibble) of channel n)
     float* St = nullptr;       // [d_in_pad/128][n_blocks*32] group scales, group major
@@ -149,8 +149,9 @@ struct fwd_item {              // one projection of a grouped forward, device po
     const uint16_t* SZ16;
     int Gp;
     uint16_t* XS16;            // [R][2][Gp] bf16 head and tail of delta_i * (sum of the row's fixed-point activations over a group)
-    float* Tpart;              // [tslices][R rounded up to 32][2*rp] partial sums of V_A^T x over K slices (head and tail columns)
+    float* Tpart;              // [tslices][R rounded up to 32][rp] the K slices' shares of sA_c * (V_A^T x)
     int tslices;               // K slices of 64 steps of 16
+    float* SBrow;              // [R, rp] the row's candidate's sigma_B (gathered by the prep kernel)
     // fused reward (optional)
     const float* rv;           // [d_out] reward vector, or null
     float* rowpart;            // [ceil(d_out / 128)][R] partial <Y, v> over blocks of 128 output channels

@@ -22,9 +22,17 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 #ifdef EXP_TIMING
 __device__ unsigned long long essa_dbg[8 * 1024];
 extern "C" void essa_dbg_read(unsigned long long* out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(essa_dbg), sizeof(essa_dbg)); }
-#define TSTAMP(i) if (lane == 0 && wave == 0) essa_dbg[blockIdx.x * 8 + (i)] = __builtin_amdgcn_s_memtime();
+#define TSTAMP(i) if (lane == 0 && wave == 0 && blockIdx.x < 1024) { essa_dbg[blockIdx.x * 8 + (i)] = __builtin_amdgcn_s_memtime(); if ((i) == 1) essa_dbg[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_memrealtime(); if ((i) == 2) essa_dbg[blockIdx.x * 8 + 7] = __builtin_amdgcn_s_memrealtime(); }
+__device__ unsigned long long essa_dbg2[8 * 1024];
+extern "C" void essa_dbg2_read(unsigned long long* out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(essa_dbg2), sizeof(essa_dbg2)); }
+#define QSTAMP(i) if ((threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == 0 && blockIdx.x < 1024) essa_dbg2[blockIdx.x * 8 + (i)] = __builtin_amdgcn_s_memtime();
+__device__ unsigned long long essa_dbg_prep[8 * 1024];
+extern "C" void essa_dbg_prep_read(unsigned long long* out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(essa_dbg_prep), sizeof(essa_dbg_prep)); }
+#define PSTAMP(i) if (threadIdx.x == 0 && blockIdx.x < 1024) essa_dbg_prep[blockIdx.x * 8 + (i)] = (i) == 7 ? (unsigned long long)role_ : __builtin_amdgcn_s_memtime();
 #else
 #define TSTAMP(i)
+#define QSTAMP(i)
+#define PSTAMP(i)
 #endif
 
 namespace {
@@ -65,6 +73,8 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     const int b = blockIdx.x;
     const int n_qblocks = a.quant_start[a.n_items];
     if (b < n_qblocks) {
+        const int role_ = 1; (void)role_;
+        PSTAMP(0) PSTAMP(7)
         // ---- (a) row quantisation: this 256-thread group takes row 4*b' + grp of its item ---------------
         int g = 0;
         while (b >= a.quant_start[g + 1]) ++g;
@@ -75,8 +85,21 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         const int din = it.d_in, dpad = it.d_in_pad;
         const u32x4* xrow = reinterpret_cast<const u32x4*>((const uint16_t*)it.X + (size_t)(live ? i : 0) * din);
         const int nch = din / 8;                          // 16-byte chunks of 8 bf16
+        // the row is read once: the first four chunks of every thread (rows up to 8192 wide) wait in registers
+        // between the two passes
+        u32x4 xr[4];
         float m = 0.f;
-        for (int c = t256; c < nch; c += 256) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int c = t256 + 256 * k;
+            xr[k] = c < nch ? xrow[c] : (u32x4){0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                m = fmaxf(m, fabsf(__uint_as_float(xr[k][e] << 16)));
+                m = fmaxf(m, fabsf(__uint_as_float(xr[k][e] & 0xffff0000u)));
+            }
+        }
+        for (int c = t256 + 1024; c < nch; c += 256) {
             const u32x4 v = xrow[c];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -91,27 +114,25 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         const float amax = fmaxf(fmaxf(wred[4 * grp], wred[4 * grp + 1]), fmaxf(wred[4 * grp + 2], wred[4 * grp + 3]));
         const float top = a.limbs == 2 ? 16383.0f : 127.0f;
         const float inv = amax > 0.f ? top / amax : 0.f;
+        PSTAMP(1)
         if (!live) return;
         uint2* hrow = reinterpret_cast<uint2*>(it.Xh + (size_t)i * dpad);
         uint2* lrow = reinterpret_cast<uint2*>(it.Xl + (size_t)i * dpad);
-        for (int c = t256; c < dpad / 8; c += 256) {
+        auto quantise_chunk = [&](int c, const u32x4& v) {
             uint32_t hi[2] = {0, 0}, lo[2] = {0, 0};
             int qsum = 0;
-            if (c < nch) {
-                const u32x4 v = xrow[c];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float x = (e & 1) ? __uint_as_float(v[e >> 1] & 0xffff0000u) : __uint_as_float(v[e >> 1] << 16);
-                    float q = rintf(x * inv);
-                    q = fminf(fmaxf(q, -top), top);
-                    const int qi = (int)q;
-                    qsum += qi;
-                    if (a.limbs == 2) {
-                        hi[e >> 2] |= (uint32_t)((qi >> 7) & 0xff) << (8 * (e & 3));   // arithmetic shift: hi in [-128,127]
-                        lo[e >> 2] |= (uint32_t)(qi & 127) << (8 * (e & 3));           // lo in [0,127]
-                    } else {
-                        hi[e >> 2] |= (uint32_t)(qi & 0xff) << (8 * (e & 3));
-                    }
+            for (int e = 0; e < 8; ++e) {
+                const float x = (e & 1) ? __uint_as_float(v[e >> 1] & 0xffff0000u) : __uint_as_float(v[e >> 1] << 16);
+                float q = rintf(x * inv);
+                q = fminf(fmaxf(q, -top), top);
+                const int qi = (int)q;
+                qsum += qi;
+                if (a.limbs == 2) {
+                    hi[e >> 2] |= (uint32_t)((qi >> 7) & 0xff) << (8 * (e & 3));   // arithmetic shift: hi in [-128,127]
+                    lo[e >> 2] |= (uint32_t)(qi & 127) << (8 * (e & 3));           // lo in [0,127]
+                } else {
+                    hi[e >> 2] |= (uint32_t)(qi & 0xff) << (8 * (e & 3));
                 }
             }
             hrow[c] = make_uint2(hi[0], hi[1]);
@@ -130,16 +151,24 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
                     it.XS16[(size_t)i * 2 * it.Gp + it.Gp + grp16] = f32_to_bf16_bits(xs - bf16_bits_to_f32(xh));
                 }
             }
-        }
+        };
+        // chunks past d_in (the zero padding up to d_in_pad) quantise zeros; whole waves enter or skip a chunk together
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (t256 + 256 * k < dpad / 8) quantise_chunk(t256 + 256 * k, xr[k]);
+        for (int c = t256 + 1024; c < dpad / 8; c += 256) quantise_chunk(c, c < nch ? xrow[c] : (u32x4){0, 0, 0, 0});
         if (it.quant == ESSA_QUANT_INT4_G128)
             for (int gq = dpad / 128 + t256; gq < it.Gp; gq += 256) {
                 it.XS16[(size_t)i * 2 * it.Gp + gq] = 0;
                 it.XS16[(size_t)i * 2 * it.Gp + it.Gp + gq] = 0;
             }
         if (t256 == 0) it.xdelta[i] = amax > 0.f ? amax / top : 0.f;
+        PSTAMP(2)
         return;
     }
     // ---- (b) partial t = V_A^T x for 32 rows of one item over one K slice --------------------------------
+    const int role_ = 2; (void)role_;
+    PSTAMP(0) PSTAMP(7)
     const int lb = b - n_qblocks;
     int g = 0;
     while (lb >= a.lora_start[g + 1]) ++g;
@@ -148,25 +177,42 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     const int r0 = ((lb - a.lora_start[g]) / S) * 32, slice = (lb - a.lora_start[g]) % S;
     const int l32 = lane & 31, h = lane >> 5;
     const int din = it.d_in, rp = it.rp, nbv = rp / 16, R = it.R;
-    const int arow = min(r0 + l32, R - 1);
-    const uint16_t* xp = (const uint16_t*)it.X + (size_t)arow * din + 8 * h;
-    const uint16_t* vp0 = it.VAp + (size_t)l32 * din + 8 * h;
-    const uint16_t* vp1 = it.VAp + (size_t)(32 + l32) * din + 8 * h;
     f32x16 acc0 = {0}, acc1 = {0};
     const int ksteps = din / 16;
     if (!(a.flags & ESSA_BASE_ONLY)) {
-        // wave w takes steps slice*64 + w + 16u, u = 0..3; all loads are issued before the MFMAs
-        u32x4 xa[4], v0[4], v1[4];
+        // wave w takes the four consecutive steps slice*64 + 4w + u, i.e. 64 columns = 128 bytes of each of the 32 rows.
+        // x: four coalesced loads (instruction i: rows 8i..8i+7, whole 128-byte lines), turned into operand order
+        // through a wave-private, XOR-swizzled 4 KB patch of LDS; V_A: operand tiles straight from memory.
+        unsigned char* xs = reinterpret_cast<unsigned char*>(&part[0][0][0][0]) + wave * 4096;
+        const int kbase = slice * 1024 + wave * 64;
+        const int ch = lane & 7;
+        u32x4 xg[4], xa[4], v0[4], v1[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 8 * i + (lane >> 3), col = kbase + ch * 8;
+            xg[i] = (u32x4){0, 0, 0, 0};
+            if (col < din) xg[i] = *reinterpret_cast<const u32x4*>((const uint16_t*)it.X + (size_t)min(r0 + row, R - 1) * din + col);
+        }
+        const u32x4* vt = reinterpret_cast<const u32x4*>(it.VAp) + lane;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int ks = slice * 64 + wave + 16 * u;
-            xa[u] = v0[u] = v1[u] = (u32x4){0, 0, 0, 0};
+            const int ks = slice * 64 + 4 * wave + u;
+            v0[u] = v1[u] = (u32x4){0, 0, 0, 0};
             if (ks < ksteps) {
-                xa[u] = *reinterpret_cast<const u32x4*>(xp + ks * 16);
-                v0[u] = *reinterpret_cast<const u32x4*>(vp0 + ks * 16);
-                if (nbv == 2) v1[u] = *reinterpret_cast<const u32x4*>(vp1 + ks * 16);
+                v0[u] = vt[((size_t)ks * nbv) * 64];
+                if (nbv == 2) v1[u] = vt[((size_t)ks * nbv + 1) * 64];
             }
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 8 * i + (lane >> 3);
+            *reinterpret_cast<u32x4*>(xs + row * 128 + ((ch ^ ((row >> 1) & 7)) * 16)) = xg[i];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const u32x4*>(xs + l32 * 128 + (((2 * u + h) ^ ((l32 >> 1) & 7)) * 16));
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v0[u]), acc0, 0, 0, 0);
@@ -174,6 +220,8 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
                 acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v1[u]), acc1, 0, 0, 0);
         }
     }
+    __syncthreads();          // the staging patches become the reduction buffer
+    PSTAMP(1)
     // 16 partial tiles -> 8 -> 1, always in the same order
     if (wave >= 8) {
 #pragma unroll
@@ -199,15 +247,26 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         }
     }
     __syncthreads();
-    // element (row, v): v indexes the rows of the head+tail copy of V_A (v < rp heads, v >= rp tails)
+    PSTAMP(2)
+    // element (row, j): head and tail columns of V_A's column j meet here, and the candidate's sigma_A scales the
+    // slice's share of t_j = <V_A[:, j], x>; the slice-0 workgroup also gathers the row's sigma_B
     const int rpad = (R + 31) / 32 * 32;
-    for (int idx = tid; idx < 32 * 2 * rp; idx += PREP_NT) {
-        const int row = idx / (2 * rp), v = idx % (2 * rp);
-        const int q = 4 * (row >> 3) + (row & 3), nb = v >> 5, ln = 32 * ((row >> 2) & 1) + (v & 31);
-        const float t = ((part[0][nb][q][ln] + part[1][nb][q][ln]) + (part[2][nb][q][ln] + part[3][nb][q][ln])) +
-                        ((part[4][nb][q][ln] + part[5][nb][q][ln]) + (part[6][nb][q][ln] + part[7][nb][q][ln]));
-        it.Tpart[((size_t)slice * rpad + r0 + row) * 2 * rp + v] = t;
+    for (int idx = tid; idx < 32 * rp; idx += PREP_NT) {
+        const int row = idx / rp, j = idx % rp;
+        const int q = 4 * (row >> 3) + (row & 3), lnr = 32 * ((row >> 2) & 1);
+        float th[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int v = e * rp + j, nb = v >> 5, ln = lnr + (v & 31);
+            th[e] = ((part[0][nb][q][ln] + part[1][nb][q][ln]) + (part[2][nb][q][ln] + part[3][nb][q][ln])) +
+                    ((part[4][nb][q][ln] + part[5][nb][q][ln]) + (part[6][nb][q][ln] + part[7][nb][q][ln]));
+        }
+        const int c = it.row2cand[min(r0 + row, R - 1)];
+        const float sa = j < it.r ? it.sigmaA[(size_t)c * it.sigma_stride + j] : 0.f;
+        it.Tpart[((size_t)slice * rpad + r0 + row) * rp + j] = sa * (th[0] + th[1]);
+        if (slice == 0 && r0 + row < R) it.SBrow[(size_t)(r0 + row) * rp + j] = j < it.r ? it.sigmaB[(size_t)c * it.sigma_stride + j] : 0.f;
     }
+    PSTAMP(3)
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -226,16 +285,36 @@ constexpr int PD = 4;              // weight prefetch distance in K tiles; d_in_
 constexpr int NT = 512;            // threads per workgroup
 constexpr int UROW = 144;          // LDS row of the u tile: 2 * rp bf16 (at most 128 B) + pad
 
+// Loads of the main loop are buffer loads: (wave-uniform base in a resource descriptor) + (scalar offset that moves
+// with the K tile) + (32-bit lane offset, fixed for the whole loop).  All address arithmetic is scalar, and the vector
+// ALU, which the MFMAs also issue through, stays free.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base_uniform) {
+    // raw buffer (stride 0), 32-bit data format; 2 GB window: offsets used here are far below it
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base_uniform), 0, 0x7fffffff, 0x00020000);
+}
+__device__ __forceinline__ u32x4 load16(rsrc_t r, uint32_t lane_off, uint32_t scalar_off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, scalar_off, 0);
+}
+
+// lane offsets of the activation-tile loads: vector e of thread tid is 16-byte part `part` of row `row` of limb e's tile
 template <int LIMBS, int BM, int XV>
-__device__ __forceinline__ void load_x(u32x4 (&xr)[XV], const int8_t* __restrict__ Xh, const int8_t* __restrict__ Xl, int m0, int dpad,
-                                       int kt, int tid) {
+__device__ __forceinline__ void x_lane_offsets(uint32_t (&xoff)[XV], int dpad, int tid) {
+#pragma unroll
+    for (int e = 0; e < XV; ++e) {
+        const int idx = tid + NT * e, rem = idx % (BM * 8), row = rem >> 3, part = rem & 7;
+        xoff[e] = (uint32_t)row * (uint32_t)dpad + part * 16;
+    }
+}
+
+// xbase[e]: start of the tile's rows in the limb that vector e of this wave belongs to (wave-uniform)
+template <int LIMBS, int BM, int XV>
+__device__ __forceinline__ void load_x(u32x4 (&xr)[XV], const rsrc_t (&xbase)[XV], const uint32_t (&xoff)[XV], int kt, int tid) {
 #pragma unroll
     for (int e = 0; e < XV; ++e) {
         const int idx = tid + NT * e;
         if ((LIMBS * BM * 8) % NT != 0 && idx >= LIMBS * BM * 8) continue;
-        const int limb = idx / (BM * 8), rem = idx % (BM * 8), row = rem >> 3, part = rem & 7;
-        const int8_t* src = (limb == 0 ? Xh : Xl) + (size_t)(m0 + row) * dpad + kt * KT + part * 16;
-        xr[e] = *reinterpret_cast<const u32x4*>(src);
+        xr[e] = load16(xbase[e], xoff[e], (uint32_t)kt * KT);
     }
 }
 
@@ -248,6 +327,20 @@ __device__ __forceinline__ void store_x(const u32x4 (&xr)[XV], unsigned char* sm
         const int limb = idx / (BM * 8), rem = idx % (BM * 8), row = rem >> 3, part = rem & 7;
         *reinterpret_cast<u32x4*>(smem + ((size_t)((stage * LIMBS + limb) * BM + row)) * LROW + part * 16) = xr[e];
     }
+}
+
+template <int LIMBS, int BM>
+__device__ __forceinline__ void store_x_vec(const u32x4& v, unsigned char* smem, int stage, int tid, int e) {
+    const int idx = tid + NT * e;
+    if ((LIMBS * BM * 8) % NT != 0 && idx >= LIMBS * BM * 8) return;
+    const int limb = idx / (BM * 8), rem = idx % (BM * 8), row = rem >> 3, part = rem & 7;
+    *reinterpret_cast<u32x4*>(smem + ((size_t)((stage * LIMBS + limb) * BM + row)) * LROW + part * 16) = v;
+}
+
+// fragment of (K chunk cc of the wave, limb l, row block mb) of the tile in `stage`
+template <int LIMBS, int BM>
+__device__ __forceinline__ i32x4 read_frag(const unsigned char* smem, int stage, int cc, int l, int mb, int kh, int l32, int h) {
+    return *reinterpret_cast<const i32x4*>(smem + ((size_t)((stage * LIMBS + l) * BM + mb * 32 + l32)) * LROW + (2 * kh + cc) * 32 + 16 * h);
 }
 
 // the wave's two K chunks of one tile
@@ -272,6 +365,28 @@ __device__ __forceinline__ void compute_tile(i32x16 (&acc)[LIMBS][MB], const u32
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) acc[l][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[cc][l][mb], wv, acc[l][mb], 0, 0, 0);
     }
+}
+
+// The same in two halves, with the fragments of a tile read one tile ahead of their use (int8 weights).
+template <int LIMBS, int MB>
+__device__ __forceinline__ void read_frags(i32x4 (&fr)[2][LIMBS][MB], const unsigned char* smem, int stage, int kh, int l32, int h) {
+    constexpr int BM = 32 * MB;
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+        for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                fr[cc][l][mb] = *reinterpret_cast<const i32x4*>(smem + ((size_t)((stage * LIMBS + l) * BM + mb * 32 + l32)) * LROW +
+                                                                (2 * kh + cc) * 32 + 16 * h);
+}
+template <int CC, int LIMBS, int MB>
+__device__ __forceinline__ void mfma_chunk(i32x16 (&acc)[LIMBS][MB], const i32x4 (&fr)[2][LIMBS][MB], const u32x4 (&w)[2]) {
+    const i32x4 wv = (i32x4)w[CC];
+#pragma unroll
+    for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[l][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[CC][l][mb], wv, acc[l][mb], 0, 0, 0);
 }
 
 // 4-bit weights: one 16-byte load holds the wave's two chunks of the tile (low / high nibbles); the group's scale
@@ -310,24 +425,30 @@ __device__ __forceinline__ void compute_tile_q4(f32x16 (&tot)[MB], const u32x4 (
     }
 }
 
-__device__ __forceinline__ void load_w_q4(u32x4 (&w)[2], const u32x4* __restrict__ wp, size_t wstride, const float* __restrict__ sp, size_t sstride,
-                                          int kt, int kh) {
-    w[0] = wp[(size_t)(kt * 2 + kh) * wstride];
-    w[1][0] = __float_as_uint(sp[(size_t)kt * sstride]);
+// wbase: the wave's n-block in k chunk 0 (wave-uniform); wstride_b: bytes from one k chunk to the next
+__device__ __forceinline__ void load_w_q4(u32x4 (&w)[2], rsrc_t wbase, uint32_t wstride_b, rsrc_t sbase, uint32_t sstride_b,
+                                          uint32_t lane16, uint32_t lane4, int kt, int kh) {
+    w[0] = load16(wbase, lane16, (uint32_t)(kt * 2 + kh) * wstride_b);
+    w[1][0] = __builtin_amdgcn_raw_buffer_load_b32(sbase, lane4, (uint32_t)kt * sstride_b, 0);
 }
 
-__device__ __forceinline__ void load_w(u32x4 (&w)[2], const u32x4* __restrict__ wp, size_t wstride, int kt, int kh) {
+__device__ __forceinline__ void load_w(u32x4 (&w)[2], rsrc_t wbase, uint32_t wstride_b, uint32_t lane16, int kt, int kh) {
 #pragma unroll
-    for (int cc = 0; cc < 2; ++cc) w[cc] = wp[(size_t)(kt * 4 + 2 * kh + cc) * wstride];
+    for (int cc = 0; cc < 2; ++cc) w[cc] = load16(wbase, lane16, (uint32_t)(kt * 4 + 2 * kh + cc) * wstride_b);
 }
+
+// LDS stages of the activation tiles: four where they fit (the tile of K step j sits in stage j % 4 and can be
+// written before the step's barrier), two for the 128-row tile
+template <int MB>
+constexpr int gemm_stages() { return MB <= 2 ? 4 : 2; }
 
 template <int MB, int LIMBS, bool YBF16>
 constexpr size_t gemm_smem_bytes() {
     constexpr size_t BM = 32 * MB;
-    constexpr size_t stages = 2 * LIMBS * BM * LROW;
+    constexpr size_t stages = gemm_stages<MB>() * LIMBS * BM * LROW;
     constexpr size_t exch = (size_t)4 * 2 * LIMBS * (MB >= 2 ? MB / 2 : 1) * 4096;
     constexpr size_t ctile = BM * (128 * (YBF16 ? 2 : 4) + 16);
-    constexpr size_t pre = stages + BM * 64 * 4 + BM * 33 * 4 + 32 * 33 * 4;   // + t sums, sA*t, core matrix (before the main loop)
+    constexpr size_t pre = stages + BM * 36 * 4 + 32 * 36 * 4;   // + sA*t, core matrix (before the main loop)
     constexpr size_t m1 = pre > exch ? pre : exch;
     constexpr size_t big = m1 > ctile ? m1 : ctile;
     return big + BM * 4 + BM * UROW;
@@ -344,8 +465,11 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     float* xd = reinterpret_cast<float*>(smem + BIG);                  // [BM] value of one fixed-point unit per row
     unsigned char* utile = smem + BIG + BM * 4;                        // [BM][UROW] bf16 head+tail of u_i
 
+    QSTAMP(0)
+    // which item this tile belongs to: the whole table comes in with one scalar load, the count is branch-free
     int g = 0;
-    while (g + 1 < a.n_items && (int)blockIdx.x >= a.tile_start[g + 1]) ++g;
+#pragma unroll
+    for (int i = 1; i < ESSA_MAX_GROUP; ++i) g += (i < a.n_items && (int)blockIdx.x >= a.tile_start[i]) ? 1 : 0;
     const fwd_item& it = a.it[g];
     // blocks go round-robin over the 8 XCDs; give each XCD a contiguous range of tiles so that the row
     // tiles sharing a weight tile sit behind the same L2
@@ -354,7 +478,8 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     if ((ntile & 7) == 0 && (a.tile_start[g] & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);
     const int tiles_m = (it.R + BM - 1) / BM;
     const int m0 = (tile % tiles_m) * BM, nb0 = (tile / tiles_m) * 4;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: what depends on it alone stays scalar
     const int nw = wave & 3, kh = wave >> 2;
     const int l32 = lane & 31, h = lane >> 5;
     const int R = it.R, dout = it.d_out, dpad = it.d_in_pad, rp = it.rp;
@@ -365,30 +490,68 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     const int nbw = min(nb0 + nw, it.n_blocks - 1);        // a wave past the last n-block repeats it; nothing of it is stored
     // weights are stored k-chunk major, [kc][n-block][1 KB]: at any moment the waves of the whole grid read one
     // contiguous stretch of memory, which spreads over all HBM channels
-    const size_t wstride = (size_t)it.n_blocks * 64;       // 16-byte vectors per k chunk
-    const u32x4* wp = reinterpret_cast<const u32x4*>(it.Wt) + (size_t)nbw * 64 + lane;
-    const int8_t* Xh = it.Xh;
-    const int8_t* Xl = it.Xl;
+    const uint32_t wstride_b = (uint32_t)it.n_blocks * 1024;   // bytes per k chunk; a projection's weights stay below 2 GB
+    const rsrc_t wbase = make_rsrc(reinterpret_cast<const unsigned char*>(it.Wt) + (size_t)nbw * 1024);
+    const uint32_t lane16 = lane * 16, lane4 = l32 * 4;
+    // activation tiles: per-thread offsets fixed for the whole loop, wave-uniform bases (the limb of vector e)
+    uint32_t xoff[XV];
+    x_lane_offsets<LIMBS, BM, XV>(xoff, dpad, tid);
+    rsrc_t xbase[XV];
+#pragma unroll
+    for (int e = 0; e < XV; ++e) {
+        const int limb = (wave * 64 + NT * e) / (BM * 8);     // BM * 8 is a multiple of 64: one limb per wave and vector
+        xbase[e] = make_rsrc((limb == 0 ? it.Xh : it.Xl) + (size_t)m0 * dpad);
+    }
 
     TSTAMP(0)
+    QSTAMP(1)
     // 4-bit: the group scale of this lane's channel, [group][channel]
-    const float* sp = Q4 ? it.St + (size_t)nbw * 32 + l32 : nullptr;
-    const size_t sstride = (size_t)it.n_blocks * 32;
+    const rsrc_t sbase = make_rsrc(Q4 ? it.St + (size_t)nbw * 32 : nullptr);
+    const uint32_t sstride_b = (uint32_t)it.n_blocks * 32 * 4;
     auto fetch_w = [&](u32x4 (&w)[2], int kt) {
-        if (Q4) load_w_q4(w, wp, wstride, sp, sstride, kt, kh);
-        else load_w(w, wp, wstride, kt, kh);
+        if (Q4) load_w_q4(w, wbase, wstride_b, sbase, sstride_b, lane16, lane4, kt, kh);
+        else load_w(w, wbase, wstride_b, lane16, kt, kh);
     };
+    // u tile, part 1: the loads.  t = sum of the K slices of sA_c * (V_A^T x) (ascending), u = sB_c * (M t).  Issued ahead
+    // of the weight and activation tiles so that they come back first (loads return in order) and the arithmetic
+    // below runs while those tiles are still on their way.
+    constexpr size_t STG = (size_t)gemm_stages<MB>() * LIMBS * BM * LROW;
+    constexpr int TP = 36;                                                     // LDS pitch (floats) of the two small matrices
+    float* tvec = reinterpret_cast<float*>(smem + STG);                        // [BM][TP]
+    float* Ms = tvec + BM * TP;                                                // [rp][TP]
+    const int rsh = rp == 16 ? 4 : 5;                     // rp is 16 or 32: divisions become shifts
+    constexpr int EU = (BM * 32 + NT - 1) / NT;           // (row, j) entries of u per thread at the widest rank
+    float tp[EU][8], sb[EU], mreg[2];
+    if (!DUMP) {
+        const int rpad = (R + 31) / 32 * 32, S = it.tslices;
+#pragma unroll
+        for (int i = 0; i < EU; ++i) {
+            // every load is issued unconditionally at a clamped, valid address (no branches between the loads);
+            // what does not belong is dropped when the values are used
+            const int e = min(tid + NT * i, BM * rp - 1), row = e >> rsh, j = e & (rp - 1);
+            const float* src = it.Tpart + (size_t)min(m0 + row, rpad - 1) * rp + j;
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl) tp[i][sl] = src[(size_t)min(sl, S - 1) * rpad * rp];
+            sb[i] = it.SBrow[(size_t)min(m0 + row, R - 1) * rp + j];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) mreg[i] = it.M[min(tid + NT * i, rp * rp - 1)];
+    }
+
     u32x4 w0[2], w1[2], w2[2], w3[2];
     fetch_w(w0, 0);
     fetch_w(w1, 1);
-    fetch_w(w2, 2);
-    fetch_w(w3, 3);
+    if constexpr (Q4) {
+        fetch_w(w2, 2);
+        fetch_w(w3, 3);
+    }
     u32x4 xa[XV], xb[XV];
-    load_x<LIMBS, BM, XV>(xa, Xh, Xl, m0, dpad, 0, tid);
+    load_x<LIMBS, BM, XV>(xa, xbase, xoff, 0, tid);
+    if constexpr (!Q4) load_x<LIMBS, BM, XV>(xb, xbase, xoff, min(1, nk - 1), tid);
 
     // epilogue operands, fetched now so that their latency hides behind the main loop
     const int oc = min(nbw * 32 + l32, dout - 1);
-    float wscale = 0.f;
+    float wscale = 0.f, xdreg = 0.f;
     u32x4 ubf[2][2];                                       // [ks][head, tail] fragments of U_B for this lane's channel
     if (!DUMP) {
         if (!Q4) wscale = it.scale[oc];
@@ -401,65 +564,27 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
                 ubf[ks][1] = *reinterpret_cast<const u32x4*>(bp + rp + ks * 16);
             }
         }
-        if (tid < BM) xd[tid] = it.xdelta[min(m0 + tid, R - 1)];
+        xdreg = it.xdelta[min(m0 + min(tid, BM - 1), R - 1)];   // parked in LDS once the other loads are on their way
     }
+    QSTAMP(2)
     if (!DUMP) {
-        // u tile: add up the K slices of t = V_A^T x, then u = sB_c * (M (sA_c * t)), kept as bf16 head+tail.
-        // These loads fly together with the first weight and activation tiles.
-        constexpr size_t STG = (size_t)2 * LIMBS * BM * LROW;
-        float* tsum = reinterpret_cast<float*>(smem + STG);                        // [BM][2 rp]
-        float* tvec = tsum + BM * 64;                                              // [BM][33]
-        float* Ms = tvec + BM * 33;                                                // [rp][33]
-        const int rpad = (R + 31) / 32 * 32, S = it.tslices, tw = 2 * rp;
-        const int rsh = rp == 16 ? 4 : 5, tsh = rsh + 1;   // rp is 16 or 32: divisions become shifts
-        // every global load of this block is independent of the others' results except sigma on the candidate
-        // index; they are all issued before the first use
-        constexpr int EV = (BM * 64 / 4 + NT - 1) / NT;   // 4-column pieces of the (row, column) sums per thread at the widest rank
-        constexpr int EU = (BM * 32 + NT - 1) / NT;       // (row, j) entries of u per thread
-        int cand[EU];
+        // u tile, part 2
 #pragma unroll
-        for (int i = 0; i < EU; ++i) {
+        for (int i = 0; i < 2; ++i) {
             const int e = tid + NT * i;
-            cand[i] = e < BM * rp ? it.row2cand[min(m0 + (e >> rsh), R - 1)] : 0;
+            if (e < rp * rp) Ms[(e >> rsh) * TP + (e & (rp - 1))] = mreg[i];
         }
-        f32x4 tp[EV][8];
-#pragma unroll
-        for (int i = 0; i < EV; ++i) {
-            const int e = (tid + NT * i) * 4;                   // four consecutive columns of one row
-            const int row = e >> tsh, v = e & (tw - 1);
-            const float* src = it.Tpart + (size_t)min(m0 + row, rpad - 1) * tw + v;
-#pragma unroll
-            for (int sl = 0; sl < 8; ++sl)
-                tp[i][sl] = (e < BM * tw && sl < S) ? *reinterpret_cast<const f32x4*>(src + (size_t)sl * rpad * tw) : (f32x4){0.f, 0.f, 0.f, 0.f};
-        }
-        for (int e = tid; e < rp * rp; e += NT) Ms[(e >> rsh) * 33 + (e & (rp - 1))] = it.M[e];
-        float sa[EU], sb[EU];
-#pragma unroll
-        for (int i = 0; i < EU; ++i) {
-            const int e = tid + NT * i, j = e & (rp - 1);
-            const bool ok = e < BM * rp && j < it.r;
-            sa[i] = ok ? it.sigmaA[(size_t)cand[i] * it.sigma_stride + j] : 0.f;
-            sb[i] = ok ? it.sigmaB[(size_t)cand[i] * it.sigma_stride + j] : 0.f;
-        }
-#pragma unroll
-        for (int i = 0; i < EV; ++i) {
-            const int e = (tid + NT * i) * 4;
-            if (e < BM * tw) {
-                f32x4 t = tp[i][0];
-#pragma unroll
-                for (int sl = 1; sl < 8; ++sl) t += tp[i][sl];       // slices beyond S hold zeros
-                *reinterpret_cast<f32x4*>(tsum + e) = t;            // e = row * tw + v
-            }
-        }
-        __syncthreads();
 #pragma unroll
         for (int i = 0; i < EU; ++i) {
             const int e = tid + NT * i;
             if (e < BM * rp) {
-                const int row = e >> rsh, j = e & (rp - 1);
-                tvec[row * 33 + j] = sa[i] * (tsum[row * tw + j] + tsum[row * tw + rp + j]);
+                float t = tp[i][0];
+#pragma unroll
+                for (int sl = 1; sl < 8; ++sl) t += sl < it.tslices ? tp[i][sl] : 0.f;
+                tvec[(e >> rsh) * TP + (e & (rp - 1))] = t;
             }
         }
+        QSTAMP(3)
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < EU; ++i) {
@@ -468,7 +593,17 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
                 const int row = e >> rsh, j = e & (rp - 1);
                 float u = 0.f;
                 if (!(a.flags & ESSA_BASE_ONLY)) {
-                    for (int l = 0; l < it.r; ++l) u = fmaf(Ms[j * 33 + l], tvec[row * 33 + l], u);
+                    // columns past r hold zeros in both operands; 16-byte LDS reads, sixteen terms per trip
+                    for (int l0 = 0; l0 < rp; l0 += 16) {
+                        f32x4 mv[4], tv[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            mv[q] = *reinterpret_cast<const f32x4*>(Ms + j * TP + l0 + 4 * q);
+                            tv[q] = *reinterpret_cast<const f32x4*>(tvec + row * TP + l0 + 4 * q);
+                        }
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) u = fmaf(mv[q >> 2][q & 3], tv[q >> 2][q & 3], u);
+                    }
                     u *= sb[i];
                 }
                 const uint16_t hi = f32_to_bf16_bits(u);
@@ -491,9 +626,11 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         for (int q = 0; q < 16; ++q) tot[mb][q] = 0.f;
     }
 
+    if constexpr (Q4) {
+    if (!DUMP && tid < BM) xd[tid] = xdreg;
     store_x<LIMBS, BM, XV>(xa, smem, 0, tid);
-    load_x<LIMBS, BM, XV>(xa, Xh, Xl, m0, dpad, 1, tid);
-    load_x<LIMBS, BM, XV>(xb, Xh, Xl, m0, dpad, min(2, nk - 1), tid);
+    load_x<LIMBS, BM, XV>(xa, xbase, xoff, 1, tid);
+    load_x<LIMBS, BM, XV>(xb, xbase, xoff, min(2, nk - 1), tid);
     __syncthreads();
     TSTAMP(1)
     // One step: multiply K tile kt (weights in W), refill W with tile kt+PD, move activation tile kt+1 (in XS)
@@ -502,12 +639,11 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
 #define ESSA_STEP(W, XS, KTI)                                                        \
     {                                                                                \
         const int kt_ = (KTI);                                                       \
-        if (Q4) compute_tile_q4<LIMBS, MB>(tot, W, smem, kt_ & 1, kh, l32, h);       \
-        else compute_tile<LIMBS, MB>(acc, W, smem, kt_ & 1, kh, l32, h);             \
+        compute_tile_q4<LIMBS, MB>(tot, W, smem, kt_ & 1, kh, l32, h);               \
         fetch_w(W, min(kt_ + PD, nk - 1));                                           \
         store_x<LIMBS, BM, XV>(XS, smem, (kt_ + 1) & 1, tid);                        \
         __syncthreads();                                                             \
-        load_x<LIMBS, BM, XV>(XS, Xh, Xl, m0, dpad, min(kt_ + 3, nk - 1), tid);      \
+        load_x<LIMBS, BM, XV>(XS, xbase, xoff, min(kt_ + 3, nk - 1), tid);      \
     }
     for (int kt0 = 0; kt0 < nk; kt0 += PD) {
         ESSA_STEP(w0, xa, kt0)
@@ -516,6 +652,83 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         ESSA_STEP(w3, xb, kt0 + 3)
     }
 #undef ESSA_STEP
+    } else {
+    // int8 weights.  The MFMAs of a K step run from fragments that were read during the previous step, and the one
+    // barrier of a step sits between its two halves.  With four LDS stages (tile j in stage j % 4):
+    //   first half (K chunk 0 of step kt): MFMAs interleaved with the LDS writes of tile kt+2 (loaded two steps ago)
+    //   barrier: tile kt+1 is complete in LDS, and nobody reads tile kt-1's stage any more
+    //   second half (K chunk 1): MFMAs interleaved with the fragment reads of tile kt+1; then the loads of weight
+    //   tile kt+PD and activation tile kt+4
+    // so no LDS or memory latency sits between two MFMAs of a wave.  With two stages (128-row tile) tile kt+2 is
+    // written after the barrier instead, into the stage tile kt was read from.  Tile indices past the end are
+    // clamped: that data is fetched again and never used.
+    constexpr int NS = gemm_stages<MB>();
+    constexpr bool EARLY = NS == 4;
+    constexpr int NF = LIMBS * MB;                      // MFMAs per K chunk
+    static_assert(!EARLY || NF >= XV, "one LDS write per MFMA slot");
+    QSTAMP(4)
+    if (!DUMP && tid < BM) xd[tid] = xdreg;
+    store_x<LIMBS, BM, XV>(xa, smem, 0, tid);
+    store_x<LIMBS, BM, XV>(xb, smem, 1, tid);
+    QSTAMP(5)
+    // the last loads before the loop, in the order the loop's own steps issue them: the compiler sizes the loop's
+    // waits for the tighter of the two ways into it
+    __builtin_amdgcn_sched_barrier(0);
+    fetch_w(w2, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    load_x<LIMBS, BM, XV>(xa, xbase, xoff, min(2, nk - 1), tid);
+    __builtin_amdgcn_sched_barrier(0);
+    fetch_w(w3, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    load_x<LIMBS, BM, XV>(xb, xbase, xoff, min(3, nk - 1), tid);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    i32x4 fA[2][LIMBS][MB], fB[2][LIMBS][MB];
+    read_frags<LIMBS, MB>(fA, smem, 0, kh, l32, h);
+    TSTAMP(1)
+#ifdef EXP_NOLDS
+#define EXP_LDS(...)
+#else
+#define EXP_LDS(...) __VA_ARGS__
+#endif
+#ifdef EXP_NOVMEM
+#define EXP_VMEM(...)
+#else
+#define EXP_VMEM(...) __VA_ARGS__
+#endif
+#define ESSA_STEP(W, XS, KTI, SI, FC, FN)                                                                        \
+    {                                                                                                            \
+        const int kt_ = (KTI);                                                                                   \
+        _Pragma("unroll") for (int i_ = 0; i_ < NF; ++i_) {                                                      \
+            acc[i_ / MB][i_ % MB] = __builtin_amdgcn_mfma_i32_32x32x32_i8(FC[0][i_ / MB][i_ % MB], (i32x4)W[0],  \
+                                                                          acc[i_ / MB][i_ % MB], 0, 0, 0);       \
+            if (EARLY && i_ < XV) { EXP_LDS(store_x_vec<LIMBS, BM>(XS[i_], smem, ((SI) + 2) % NS, tid, i_);) }   \
+            __builtin_amdgcn_sched_barrier(0);                                                                   \
+        }                                                                                                        \
+        __syncthreads();                                                                                         \
+        __builtin_amdgcn_sched_barrier(0);                                                                       \
+        _Pragma("unroll") for (int i_ = 0; i_ < NF; ++i_) {                                                      \
+            acc[i_ / MB][i_ % MB] = __builtin_amdgcn_mfma_i32_32x32x32_i8(FC[1][i_ / MB][i_ % MB], (i32x4)W[1],  \
+                                                                          acc[i_ / MB][i_ % MB], 0, 0, 0);       \
+            EXP_LDS(FN[0][i_ / MB][i_ % MB] = read_frag<LIMBS, BM>(smem, ((SI) + 1) % NS, 0, i_ / MB, i_ % MB, kh, l32, h);) \
+            EXP_LDS(FN[1][i_ / MB][i_ % MB] = read_frag<LIMBS, BM>(smem, ((SI) + 1) % NS, 1, i_ / MB, i_ % MB, kh, l32, h);) \
+            __builtin_amdgcn_sched_barrier(0);                                                                   \
+        }                                                                                                        \
+        if (!EARLY) { EXP_LDS(store_x<LIMBS, BM, XV>(XS, smem, (SI) % NS, tid);) }                               \
+        EXP_VMEM(fetch_w(W, min(kt_ + PD, nk - 1));)                                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                                       \
+        EXP_VMEM(load_x<LIMBS, BM, XV>(XS, xbase, xoff, min(kt_ + 4, nk - 1), tid);)                             \
+        __builtin_amdgcn_sched_barrier(0);                                                                       \
+    }
+    for (int kt0 = 0; kt0 < nk; kt0 += PD) {
+        ESSA_STEP(w0, xa, kt0, 0, fA, fB)
+        ESSA_STEP(w1, xb, kt0 + 1, 1, fB, fA)
+        ESSA_STEP(w2, xa, kt0 + 2, 2, fA, fB)
+        ESSA_STEP(w3, xb, kt0 + 3, 3, fB, fA)
+    }
+#undef ESSA_STEP
+    __syncthreads();          // the stages become the exchange area
+    }
     TSTAMP(2)
 
     // ---- epilogue 1: the two K halves exchange accumulators.  Half kh keeps row blocks with (mb & 1) == kh
