@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--rows-per-cand", type=int, default=0)
     ap.add_argument("--forward-only", action="store_true", help="time only the projections (no sampler / reward / update)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="issue every launch of a step from the host instead of replaying the recorded step")
     ap.add_argument("--two-pass-reward", action="store_true", help="reward as a second pass over Y instead of in the GEMM's epilogue")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy (a reference for HBM byte counters)")
     args = ap.parse_args()
@@ -70,7 +71,10 @@ def main():
     n = P * 2 * r
     flags = essa.COMPUTE_W8A8 if args.mode == "w8a8" else 0
     torch.cuda.set_device(0)
-    ctx = essa.Context(0)
+    # everything (the library's launches and torch's own fills) runs on one side stream, so that a step can be recorded
+    stream = torch.cuda.Stream()
+    torch.cuda.set_stream(stream)
+    ctx = essa.Context(0, stream=stream)
 
     t0 = time.time()
     projs, sft_A, sft_B, vecs = [], [], [], []
@@ -148,12 +152,24 @@ def main():
     if args.forward_only:   # sigma must exist
         essa.essa_sample_candidates(ctx, cma, seeds, theta, None)
         essa.essa_theta_to_sigma(ctx, r, sft_A, sft_B, theta, sA, sB)
-    for _ in range(args.warmup):
+    for _ in range(max(args.warmup, 1)):
         step()
     torch.cuda.synchronize()
+    # a step is a fixed sequence of launches on fixed buffers: record it once (HIP graph), replay it K times.  The
+    # replay runs every kernel of the step; only the host's per-launch work is saved.
+    run_step = step
+    graph = None
+    if not args.no_graph:
+        ctx.graph_begin()
+        step()
+        graph = ctx.graph_end()
+        run_step = graph.launch
+        for _ in range(max(args.warmup, 1)):
+            run_step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     enqueue = time.perf_counter() - t0      # host time to issue the K steps (the GPU runs behind it)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -229,6 +245,7 @@ def main():
         "roofline": roof, "cpu_baseline": cpu, "breakdown_ms": breakdown,
         "ms_per_step_with_events": 1e3 * elapsed_profiled / args.steps,
         "host_enqueue_ms_per_step": 1e3 * enqueue / args.steps,
+        "launches": "recorded step replayed (HIP graph)" if graph is not None else "issued one by one",
     }
     print(json.dumps(out), flush=True)
 

@@ -67,6 +67,23 @@ const char* essa_version(void);
 /* Blocks until everything queued on the context's stream has finished. */
 essa_status essa_synchronize(essa_ctx* ctx);
 
+/* ---------------------------------------------------------------------------------------------
+ * Record and replay.  A generation is a fixed sequence of some dozens of short launches on fixed buffers; a
+ * caller that repeats it can record the sequence once (a HIP graph of the context's stream) and replay it with
+ * one call per generation.  Between essa_graph_begin and essa_graph_end every call on the context is recorded
+ * instead of run (so is any other work the caller puts on that stream); nothing may allocate or wait meanwhile:
+ * a call that would have to grow the scratch, upload constants or synchronise fails with ESSA_ERR_STATE, so run
+ * the same sequence once, unrecorded, first.  The recorded launches keep their pointer arguments: the replay
+ * reads and writes the same buffers, with whatever they hold then (new seeds, the updated search state).
+ * The context must have been created on a stream of the caller's, not the default stream.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct essa_graph essa_graph;
+essa_status essa_graph_begin(essa_ctx* ctx);
+essa_status essa_graph_end(essa_ctx* ctx, essa_graph** out);
+/* Queues one replay on the stream the graph was recorded on. */
+essa_status essa_graph_launch(essa_graph* graph);
+void essa_graph_destroy(essa_graph* graph);
+
 /* Measurement aid: while enabled, every launch of the forward's GEMM kernel is bracketed by HIP
  * events on the context's stream.  essa_profile_read synchronises the stream, returns the summed
  * kernel time in milliseconds and the number of launches since the last read, and resets both. */

@@ -55,12 +55,67 @@ extern "C" void essa_destroy(essa_ctx* ctx) {
 
 extern "C" essa_status essa_synchronize(essa_ctx* ctx) {
     if (!ctx) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_synchronize: ctx is NULL");
+    if (ctx->capturing) return essa_fail(ESSA_ERR_STATE, "essa_synchronize: not while a graph is being recorded");
     ESSA_HIP(hipStreamSynchronize(ctx->stream));
     return ESSA_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// record and replay
+// ---------------------------------------------------------------------------------------------
+extern "C" essa_status essa_graph_begin(essa_ctx* ctx) {
+    if (!ctx) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_graph_begin: ctx is NULL");
+    if (ctx->capturing) return essa_fail(ESSA_ERR_STATE, "essa_graph_begin: already recording");
+    if (!ctx->stream) return essa_fail(ESSA_ERR_STATE, "essa_graph_begin: the context runs on the default stream, which cannot be recorded");
+    ESSA_HIP(hipSetDevice(ctx->device));
+    ESSA_HIP(hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal));
+    ctx->capturing = true;
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_graph_end(essa_ctx* ctx, essa_graph** out) {
+    if (!ctx || !out) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_graph_end: NULL argument");
+    *out = nullptr;
+    if (!ctx->capturing) return essa_fail(ESSA_ERR_STATE, "essa_graph_end: not recording");
+    ctx->capturing = false;
+    ESSA_HIP(hipSetDevice(ctx->device));
+    hipGraph_t graph = nullptr;
+    ESSA_HIP(hipStreamEndCapture(ctx->stream, &graph));
+    if (!graph) return essa_fail(ESSA_ERR_HIP, "essa_graph_end: the recording was invalidated by a call that cannot be recorded");
+    hipGraphExec_t exec = nullptr;
+    hipError_t e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        return essa_fail(ESSA_ERR_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+    }
+    auto* g = new essa_graph();
+    g->device = ctx->device;
+    g->stream = ctx->stream;
+    g->graph = graph;
+    g->exec = exec;
+    *out = g;
+    return ESSA_OK;
+}
+
+extern "C" essa_status essa_graph_launch(essa_graph* g) {
+    if (!g) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_graph_launch: graph is NULL");
+    ESSA_HIP(hipSetDevice(g->device));
+    ESSA_HIP(hipGraphLaunch(g->exec, g->stream));
+    return ESSA_OK;
+}
+
+extern "C" void essa_graph_destroy(essa_graph* g) {
+    if (!g) return;
+    (void)hipSetDevice(g->device);
+    (void)hipStreamSynchronize(g->stream);
+    if (g->exec) (void)hipGraphExecDestroy(g->exec);
+    if (g->graph) (void)hipGraphDestroy(g->graph);
+    delete g;
+}
+
 extern "C" essa_status essa_profile_enable(essa_ctx* ctx, int on) {
     if (!ctx) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_profile_enable: ctx is NULL");
+    if (ctx->capturing) return essa_fail(ESSA_ERR_STATE, "essa_profile_enable: not while a graph is being recorded");
     ESSA_HIP(hipSetDevice(ctx->device));
     ESSA_HIP(hipStreamSynchronize(ctx->stream));
     ctx->profiling = on != 0;
@@ -87,7 +142,7 @@ extern "C" essa_status essa_profile_read(essa_ctx* ctx, double* total_ms, int* l
 // next (start, stop) event pair while profiling, else (null, null)
 static essa_status next_events(essa_ctx* ctx, hipEvent_t* a, hipEvent_t* b) {
     *a = *b = nullptr;
-    if (!ctx->profiling) return ESSA_OK;
+    if (!ctx->profiling || ctx->capturing) return ESSA_OK;
     while (ctx->ev.size() < ctx->ev_used + 2) {
         hipEvent_t e;
         ESSA_HIP(hipEventCreate(&e));
@@ -101,6 +156,8 @@ static essa_status next_events(essa_ctx* ctx, hipEvent_t* a, hipEvent_t* b) {
 
 essa_status essa_ws_reserve(essa_ctx* ctx, size_t bytes) {
     if (bytes <= ctx->ws_bytes) return ESSA_OK;
+    if (ctx->capturing)
+        return essa_fail(ESSA_ERR_STATE, "scratch would have to grow to %zu bytes while a graph is being recorded: run the same calls once before essa_graph_begin", bytes);
     ESSA_HIP(hipStreamSynchronize(ctx->stream));
     if (ctx->ws) ESSA_HIP(hipFree(ctx->ws));
     ctx->ws = nullptr;
@@ -739,6 +796,8 @@ extern "C" essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uin
     std::vector<float> w;
     essa_k::cma_consts c = make_consts(n, K, w);
     if (cma->weights_K != K) {
+        if (ctx->capturing)
+            return essa_fail(ESSA_ERR_STATE, "essa_cmaes_update: the weights for K=%d are not on the device yet: run the update once before essa_graph_begin", K);
         ESSA_HIP(hipStreamSynchronize(ctx->stream));
         if (cma->weights) ESSA_HIP(hipFree(cma->weights));
         cma->weights = nullptr;

@@ -33,6 +33,13 @@ struct essa_ctx {
     bool profiling = false;    // bracket GEMM launches with events
     std::vector<hipEvent_t> ev;   // pairs (start, stop)
     size_t ev_used = 0;
+    bool capturing = false;    // between essa_graph_begin and essa_graph_end: no allocation, no synchronisation, no events
+};
+struct essa_graph {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
 };
 essa_status essa_ws_reserve(essa_ctx* ctx, size_t bytes);
 

@@ -9,7 +9,7 @@ import numpy as np
 import torch
 
 __all__ = [
-    "EssaError", "lib", "LIB_PATH", "Context", "Projection", "CmaState",
+    "EssaError", "lib", "LIB_PATH", "Context", "Graph", "Projection", "CmaState",
     "F32", "BF16", "QUANT_INT8_PERCH", "QUANT_INT4_G128", "COMPUTE_W8A8", "LORA_ONLY", "BASE_ONLY", "COMPUTE_BF16",
     "essa_create", "essa_proj_create", "essa_cma_create", "essa_sample_candidates", "essa_philox_words",
     "essa_theta_to_sigma", "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
@@ -34,6 +34,7 @@ EXPORTED_SYMBOLS = [
     "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
     "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards",
     "essa_svdlora_forward_reward_group", "essa_reward_finish",
+    "essa_graph_begin", "essa_graph_end", "essa_graph_launch", "essa_graph_destroy",
 ]
 
 
@@ -70,6 +71,10 @@ def _load():
         "essa_profile_enable": (i32, [vp, i32]),
         "essa_profile_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(i32)]),
         "essa_proj_create": (i32, [vp, C.POINTER(_ProjDesc), C.POINTER(vp)]),
+        "essa_graph_begin": (i32, [vp]),
+        "essa_graph_end": (i32, [vp, C.POINTER(vp)]),
+        "essa_graph_launch": (i32, [vp]),
+        "essa_graph_destroy": (None, [vp]),
         "essa_proj_destroy": (None, [vp]),
         "essa_proj_spectrum": (i32, [vp, vp, vp]),
         "essa_cma_create": (i32, [vp, i32, f32, vp, C.POINTER(vp)]),
@@ -134,6 +139,27 @@ def _xdtype(t):
     raise TypeError("activations must be float32 or bfloat16, got %s" % t.dtype)
 
 
+class Graph:
+    """essa_graph: a recorded launch sequence; launch() queues one replay on the stream it was recorded on."""
+
+    def __init__(self, handle):
+        self._h = handle
+
+    def launch(self):
+        _check(lib.essa_graph_launch(self._h))
+
+    def close(self):
+        if self._h:
+            lib.essa_graph_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 class Context:
     """essa_ctx: one GPU, one stream (the current torch stream at creation unless given)."""
 
@@ -156,6 +182,15 @@ class Context:
         ms, cnt = C.c_double(0), C.c_int(0)
         _check(lib.essa_profile_read(self._h, C.byref(ms), C.byref(cnt)))
         return ms.value, cnt.value
+
+    def graph_begin(self):
+        """Start recording the calls on this context (and anything else put on its stream) instead of running them."""
+        _check(lib.essa_graph_begin(self._h))
+
+    def graph_end(self) -> "Graph":
+        h = C.c_void_p()
+        _check(lib.essa_graph_end(self._h, C.byref(h)))
+        return Graph(h)
 
     def close(self):
         if self._h:

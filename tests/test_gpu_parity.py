@@ -617,3 +617,88 @@ def test_full_iteration_small(essa, ctx):
     for gp in gps:
         gp.close()
     cma.close()
+
+
+def test_recorded_generation_replays_bit_exact(essa):
+    """A whole generation recorded once as a graph and replayed with new seeds: every replay leaves the same bits as the
+    same generation run call by call (rewards and the whole search state), with eager work between the replays."""
+    layers, hidden, kv, r, K, rows_per = 2, 256, 64, 8, 6, 10
+    P, R = layers * 4, K * rows_per
+    n = P * 2 * r
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        c2 = essa.Context(0, stream=side)
+        projs = [p for l in range(layers) for p in wl.make_layer(hidden, kv, r, "int8", layer=30 + l)]
+        gps = [gpu_proj(essa, c2, p) for p in projs]
+        spec = [gp.spectrum() for gp in gps]
+        sft_A = to_dev(np.stack([a for a, _ in spec]))
+        sft_B = to_dev(np.stack([b for _, b in spec]))
+        Q, d = wl.random_covariance_basis(n, basis_id=78)
+        d = (d * 0.05).astype(np.float32)
+        C0 = ((Q.astype(np.float64) * d.astype(np.float64) ** 2) @ Q.astype(np.float64).T).astype(np.float32)
+        zero = np.zeros(n, np.float32)
+        blob0 = essa.CmaState.pack_blob(n, 0, 0.32, zero, zero, zero, d, C0, Q)
+        cma = essa.CmaState(c2, n, 0.32, None)
+        xb, _ = wl.make_x_bf16(R, hidden, x_id=98)
+        Xd, rd = bf16_dev(xb), to_dev(wl.row2cand_contiguous(K, rows_per))
+        seeds = torch.zeros(K, dtype=torch.int32, device="cuda")
+        theta = torch.empty(K, n, device="cuda")
+        sA = torch.empty(K, P, r, device="cuda")
+        sB = torch.empty(K, P, r, device="cuda")
+        F = torch.zeros(K, device="cuda")
+        groups = []
+        for l in range(layers):
+            items = [(gps[l * 4 + pi], Xd, rd, sA[:, l * 4 + pi, :], sB[:, l * 4 + pi, :],
+                      torch.empty(R, projs[l * 4 + pi].d_out, device="cuda", dtype=torch.bfloat16)) for pi in range(4)]
+            vs = [to_dev(wl.reward_vector(projs[l * 4 + pi].d_out, 30 + l, pi)) for pi in range(4)]
+            groups.append(essa.ForwardGroup(items, vs))
+        rowpart = torch.empty(sum(g.blocks for g in groups), R, device="cuda")
+
+        def generation():
+            essa.essa_sample_candidates(c2, cma, seeds, theta, None)
+            essa.essa_theta_to_sigma(c2, r, sft_A, sft_B, theta, sA, sB)
+            F.zero_()
+            b = 0
+            for g in groups:
+                b = essa.essa_svdlora_forward_reward_group(c2, g, None, rowpart, b)
+            essa.essa_reward_finish(c2, rowpart, b, rd, F)
+            essa.essa_cmaes_update(c2, cma, seeds, F, None)
+
+        seed_sets = [seeds_dev(range(1 + 10 * g, 1 + 10 * g + K)) for g in range(3)]
+        cma.import_blob(blob0)
+        eager = []
+        for sset in seed_sets:
+            seeds.copy_(sset)
+            generation()
+            side.synchronize()
+            eager.append((F.clone(), cma.export()))
+        # record (nothing runs), then replay from the same starting state
+        cma.import_blob(blob0)
+        c2.graph_begin()
+        generation()
+        graph = c2.graph_end()
+        for sset, (F_ref, st_ref) in zip(seed_sets, eager):
+            seeds.copy_(sset)
+            graph.launch()
+            side.synchronize()
+            assert torch.equal(F, F_ref)
+            st = cma.export()
+            assert st["t"] == st_ref["t"] and st["sigma"] == st_ref["sigma"]
+            for name in ("m", "p_sigma", "p_c", "C"):
+                assert np.array_equal(st[name], st_ref[name]), name
+            assert math.isfinite(float(rowpart.sum().item()))            # eager work between the replays
+        # a call that would have to grow the scratch while recording is refused, and the recording survives it
+        bigX = torch.zeros(4096, hidden, device="cuda", dtype=torch.bfloat16)
+        bigY = torch.empty(4096, projs[0].d_out, device="cuda", dtype=torch.bfloat16)
+        big_r2c = torch.zeros(4096, dtype=torch.int32, device="cuda")
+        c2.graph_begin()
+        with pytest.raises(essa.EssaError):
+            essa.essa_svdlora_forward(c2, gps[0], bigX, big_r2c, sA[:, 0, :], sB[:, 0, :], bigY)
+        essa.essa_theta_to_sigma(c2, r, sft_A, sft_B, theta, sA, sB)
+        c2.graph_end().close()
+        graph.close()
+        for gp in gps:
+            gp.close()
+        cma.close()
+        side.synchronize()
+        c2.close()
