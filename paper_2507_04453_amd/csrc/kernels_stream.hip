@@ -57,6 +57,23 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
     return (uint16_t)(u >> 16);
 }
 
+// The descriptor of one item, fetched from the kernel arguments in one batch of scalar loads: left to itself the
+// compiler loads every field where it is first used, and each of those loads is a separate wait on the way to the
+// first tile.
+__device__ __forceinline__ fwd_item fetch_item(const fwd_item& src) {
+    constexpr int NW = sizeof(fwd_item) / 4;
+    static_assert(sizeof(fwd_item) % 4 == 0, "descriptor is a whole number of words");
+    int raw[NW];
+    const int* p = reinterpret_cast<const int*>(&src);
+#pragma unroll
+    for (int i = 0; i < NW; ++i) raw[i] = p[i];
+#pragma unroll
+    for (int i = 0; i < NW; ++i) asm volatile("" : "+s"(raw[i]));      // all words are in scalar registers from here on
+    fwd_item it;
+    __builtin_memcpy(&it, raw, sizeof(fwd_item));
+    return it;
+}
+
 // ------------------------------------------------------------------------------------------------
 // prep kernel (1024 threads): two kinds of workgroups in one launch.
 //  (a) quantise four activation rows into limbs, one row per 256 threads (once per distinct X of the group);
@@ -470,7 +487,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     int g = 0;
 #pragma unroll
     for (int i = 1; i < ESSA_MAX_GROUP; ++i) g += (i < a.n_items && (int)blockIdx.x >= a.tile_start[i]) ? 1 : 0;
-    const fwd_item& it = a.it[g];
+    const fwd_item it = fetch_item(a.it[g]);
     // blocks go round-robin over the 8 XCDs; give each XCD a contiguous range of tiles so that the row
     // tiles sharing a weight tile sit behind the same L2
     const int ntile = a.tile_start[g + 1] - a.tile_start[g];
@@ -526,13 +543,14 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         const int rpad = (R + 31) / 32 * 32, S = it.tslices;
 #pragma unroll
         for (int i = 0; i < EU; ++i) {
-            // every load is issued unconditionally at a clamped, valid address (no branches between the loads);
-            // what does not belong is dropped when the values are used
+            // loads are skipped only on conditions that hold for the whole workgroup (rank 16 fills half of the
+            // entries, S slices of the eight slots): scalar branches, no per-lane masking between the loads
             const int e = min(tid + NT * i, BM * rp - 1), row = e >> rsh, j = e & (rp - 1);
             const float* src = it.Tpart + (size_t)min(m0 + row, rpad - 1) * rp + j;
+            const bool used = NT * i < BM * rp;
 #pragma unroll
-            for (int sl = 0; sl < 8; ++sl) tp[i][sl] = src[(size_t)min(sl, S - 1) * rpad * rp];
-            sb[i] = it.SBrow[(size_t)min(m0 + row, R - 1) * rp + j];
+            for (int sl = 0; sl < 8; ++sl) tp[i][sl] = (used && sl < S) ? src[(size_t)sl * rpad * rp] : 0.f;
+            sb[i] = used ? it.SBrow[(size_t)min(m0 + row, R - 1) * rp + j] : 0.f;
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i) mreg[i] = it.M[min(tid + NT * i, rp * rp - 1)];
@@ -580,7 +598,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
             if (e < BM * rp) {
                 float t = tp[i][0];
 #pragma unroll
-                for (int sl = 1; sl < 8; ++sl) t += sl < it.tslices ? tp[i][sl] : 0.f;
+                for (int sl = 1; sl < 8; ++sl) t += tp[i][sl];       // slots beyond S hold zeros
                 tvec[(e >> rsh) * TP + (e & (rp - 1))] = t;
             }
         }
@@ -936,6 +954,9 @@ hipError_t launch_gemm_mb(hipStream_t st, stream_args& a, int mb) {
 
 // rows per tile: the largest of 128/64/32 that still leaves every CU a tile
 int pick_mb(const stream_args& a) {
+#ifdef EXP_FORCE_MB
+    return EXP_FORCE_MB;
+#endif
     int maxR = 0;
     for (int g = 0; g < a.n_items; ++g) maxR = a.it[g].R > maxR ? a.it[g].R : maxR;
     for (int mb : {4, 2}) {
