@@ -471,6 +471,133 @@ constexpr size_t gemm_smem_bytes() {
     return big + BM * 4 + BM * UROW;
 }
 
+// The tile of rank-space vectors u_i = sB_c * (M t_i), t_i = sum over the K slices (ascending) of the prep kernel's
+// sA_c * (V_A^T x_i) shares, kept in LDS as bf16 head+tail rows of UROW bytes.  Two parts, so that a caller can put
+// other loads between them: the global loads, then the arithmetic (which contains one workgroup barrier).
+constexpr int UTP = 36;            // LDS pitch (floats) of the two small matrices
+template <int BM, int EU>
+__device__ __forceinline__ void u_tile_loads(const fwd_item& it, int m0, int tid, float (&tp)[EU][8], float (&sb)[EU], float (&mreg)[2]) {
+    const int R = it.R, rp = it.rp, rpad = (R + 31) / 32 * 32, S = it.tslices;
+    const int rsh = rp == 16 ? 4 : 5;                     // rp is 16 or 32: divisions become shifts
+#pragma unroll
+    for (int i = 0; i < EU; ++i) {
+        // loads are skipped only on conditions that hold for the whole workgroup (rank 16 fills half of the
+        // entries, S slices of the eight slots): scalar branches, no per-lane masking between the loads
+        const int e = min(tid + NT * i, BM * rp - 1), row = e >> rsh, j = e & (rp - 1);
+        const float* src = it.Tpart + (size_t)min(m0 + row, rpad - 1) * rp + j;
+        const bool used = NT * i < BM * rp;
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) tp[i][sl] = (used && sl < S) ? src[(size_t)sl * rpad * rp] : 0.f;
+        sb[i] = used ? it.SBrow[(size_t)min(m0 + row, R - 1) * rp + j] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) mreg[i] = it.M[min(tid + NT * i, rp * rp - 1)];
+}
+
+template <int BM, int EU>
+__device__ __forceinline__ void u_tile_finish(const fwd_item& it, unsigned flags, int tid, const float (&tp)[EU][8], const float (&sb)[EU],
+                                              const float (&mreg)[2], float* tvec, float* Ms, unsigned char* utile) {
+    const int rp = it.rp, rsh = rp == 16 ? 4 : 5;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int e = tid + NT * i;
+        if (e < rp * rp) Ms[(e >> rsh) * UTP + (e & (rp - 1))] = mreg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < EU; ++i) {
+        const int e = tid + NT * i;
+        if (e < BM * rp) {
+            float t = tp[i][0];
+#pragma unroll
+            for (int sl = 1; sl < 8; ++sl) t += tp[i][sl];       // slots beyond S hold zeros
+            tvec[(e >> rsh) * UTP + (e & (rp - 1))] = t;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < EU; ++i) {
+        const int e = tid + NT * i;
+        if (e < BM * rp) {
+            const int row = e >> rsh, j = e & (rp - 1);
+            float u = 0.f;
+            if (!(flags & ESSA_BASE_ONLY)) {
+                // columns past r hold zeros in both operands; 16-byte LDS reads, sixteen terms per trip
+                for (int l0 = 0; l0 < rp; l0 += 16) {
+                    f32x4 mv[4], tv[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        mv[q] = *reinterpret_cast<const f32x4*>(Ms + j * UTP + l0 + 4 * q);
+                        tv[q] = *reinterpret_cast<const f32x4*>(tvec + row * UTP + l0 + 4 * q);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) u = fmaf(mv[q >> 2][q & 3], tv[q >> 2][q & 3], u);
+                }
+                u *= sb[i];
+            }
+            const uint16_t hi = f32_to_bf16_bits(u);
+            uint16_t* urow = reinterpret_cast<uint16_t*>(utile + (size_t)row * UROW);
+            urow[j] = hi;
+            urow[rp + j] = f32_to_bf16_bits(u - bf16_bits_to_f32(hi));
+        }
+    }
+}
+
+// An output tile of BM rows x 128 channels, staged in LDS as rows of CROW bytes, leaves as full rows (16 bytes per
+// thread where the output allows it).  With a reward vector, the tile's share <Y[i, block], v[block]> of every row
+// goes to rowpart[blk][i]: one partial per (128-channel block, row); the blocks are added in a fixed order later.
+template <bool YBF16, int BM>
+__device__ __forceinline__ void store_ctile(const unsigned char* ctile, const fwd_item& it, int m0, int n0, int blk, int tid) {
+    constexpr int ESZ = YBF16 ? 2 : 4, EPV = 16 / ESZ, PPR = 128 / EPV;     // elements per vector, vectors per row
+    constexpr int CROW = 128 * ESZ + 16;
+    const int R = it.R, dout = it.d_out;
+    unsigned char* Yb = reinterpret_cast<unsigned char*>(it.Y);
+    const bool vec_ok = (dout % EPV == 0) && ((reinterpret_cast<uintptr_t>(it.Y) & 15) == 0);
+    const float* __restrict__ rv = it.rv;
+    const bool rv_vec = rv && (reinterpret_cast<uintptr_t>(rv) & 15) == 0 && dout % EPV == 0;
+#pragma unroll
+    for (int p0 = 0; p0 < BM * PPR; p0 += NT) {           // BM * PPR is a multiple of NT: every lane takes part in the shuffles
+        const int p = p0 + tid;
+        const int row = p / PPR, piece = p % PPR;
+        const int i = m0 + row, o = n0 + piece * EPV;
+        const bool valid = i < R && o < dout;
+        const unsigned char* src = ctile + (size_t)row * CROW + piece * 16;
+        const u32x4 val = *reinterpret_cast<const u32x4*>(src);
+        if (valid) {
+            if (vec_ok && o + EPV <= dout) {
+                *reinterpret_cast<u32x4*>(Yb + ((size_t)i * dout + o) * ESZ) = val;
+            } else {
+                for (int e = 0; e < EPV && o + e < dout; ++e) {
+                    if (YBF16) reinterpret_cast<uint16_t*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const uint16_t*>(src)[e];
+                    else reinterpret_cast<float*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const float*>(src)[e];
+                }
+            }
+        }
+        if (rv) {
+            float yv[EPV], s = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                yv[e] = YBF16 ? __uint_as_float((e & 1) ? (val[e >> 1] & 0xffff0000u) : (val[e >> 1] << 16)) : __uint_as_float(val[e]);
+            if (valid) {
+                if (rv_vec && o + EPV <= dout) {
+#pragma unroll
+                    for (int e4 = 0; e4 < EPV / 4; ++e4) {
+                        const f32x4 r4 = *reinterpret_cast<const f32x4*>(rv + o + 4 * e4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) s = fmaf(yv[4 * e4 + e], r4[e], s);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e)
+                        if (o + e < dout) s = fmaf(yv[e], rv[o + e], s);
+                }
+            }
+#pragma unroll
+            for (int off = PPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+            if (piece == 0 && i < R && n0 < dout) it.rowpart[(size_t)blk * R + i] = s;   // a half tile past the last channel has no block
+        }
+    }
+}
+
 template <int MB, int LIMBS, bool YBF16, bool DUMP, bool Q4>
 __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __restrict__ acc_out) {
     constexpr int BM = 32 * MB;
@@ -529,32 +656,14 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         if (Q4) load_w_q4(w, wbase, wstride_b, sbase, sstride_b, lane16, lane4, kt, kh);
         else load_w(w, wbase, wstride_b, lane16, kt, kh);
     };
-    // u tile, part 1: the loads.  t = sum of the K slices of sA_c * (V_A^T x) (ascending), u = sB_c * (M t).  Issued ahead
-    // of the weight and activation tiles so that they come back first (loads return in order) and the arithmetic
-    // below runs while those tiles are still on their way.
+    // u tile, part 1: the loads, issued ahead of the weight and activation tiles so that they come back first (loads
+    // return in order) and the arithmetic of part 2 runs while those tiles are still on their way
     constexpr size_t STG = (size_t)gemm_stages<MB>() * LIMBS * BM * LROW;
-    constexpr int TP = 36;                                                     // LDS pitch (floats) of the two small matrices
-    float* tvec = reinterpret_cast<float*>(smem + STG);                        // [BM][TP]
-    float* Ms = tvec + BM * TP;                                                // [rp][TP]
-    const int rsh = rp == 16 ? 4 : 5;                     // rp is 16 or 32: divisions become shifts
+    float* tvec = reinterpret_cast<float*>(smem + STG);                        // [BM][UTP]
+    float* Ms = tvec + BM * UTP;                                               // [rp][UTP]
     constexpr int EU = (BM * 32 + NT - 1) / NT;           // (row, j) entries of u per thread at the widest rank
     float tp[EU][8], sb[EU], mreg[2];
-    if (!DUMP) {
-        const int rpad = (R + 31) / 32 * 32, S = it.tslices;
-#pragma unroll
-        for (int i = 0; i < EU; ++i) {
-            // loads are skipped only on conditions that hold for the whole workgroup (rank 16 fills half of the
-            // entries, S slices of the eight slots): scalar branches, no per-lane masking between the loads
-            const int e = min(tid + NT * i, BM * rp - 1), row = e >> rsh, j = e & (rp - 1);
-            const float* src = it.Tpart + (size_t)min(m0 + row, rpad - 1) * rp + j;
-            const bool used = NT * i < BM * rp;
-#pragma unroll
-            for (int sl = 0; sl < 8; ++sl) tp[i][sl] = (used && sl < S) ? src[(size_t)sl * rpad * rp] : 0.f;
-            sb[i] = used ? it.SBrow[(size_t)min(m0 + row, R - 1) * rp + j] : 0.f;
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) mreg[i] = it.M[min(tid + NT * i, rp * rp - 1)];
-    }
+    if (!DUMP) u_tile_loads<BM, EU>(it, m0, tid, tp, sb, mreg);
 
     u32x4 w0[2], w1[2], w2[2], w3[2];
     fetch_w(w0, 0);
@@ -584,53 +693,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         }
         xdreg = it.xdelta[min(m0 + min(tid, BM - 1), R - 1)];   // parked in LDS once the other loads are on their way
     }
-    QSTAMP(2)
-    if (!DUMP) {
-        // u tile, part 2
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int e = tid + NT * i;
-            if (e < rp * rp) Ms[(e >> rsh) * TP + (e & (rp - 1))] = mreg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < EU; ++i) {
-            const int e = tid + NT * i;
-            if (e < BM * rp) {
-                float t = tp[i][0];
-#pragma unroll
-                for (int sl = 1; sl < 8; ++sl) t += tp[i][sl];       // slots beyond S hold zeros
-                tvec[(e >> rsh) * TP + (e & (rp - 1))] = t;
-            }
-        }
-        QSTAMP(3)
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < EU; ++i) {
-            const int e = tid + NT * i;
-            if (e < BM * rp) {
-                const int row = e >> rsh, j = e & (rp - 1);
-                float u = 0.f;
-                if (!(a.flags & ESSA_BASE_ONLY)) {
-                    // columns past r hold zeros in both operands; 16-byte LDS reads, sixteen terms per trip
-                    for (int l0 = 0; l0 < rp; l0 += 16) {
-                        f32x4 mv[4], tv[4];
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            mv[q] = *reinterpret_cast<const f32x4*>(Ms + j * TP + l0 + 4 * q);
-                            tv[q] = *reinterpret_cast<const f32x4*>(tvec + row * TP + l0 + 4 * q);
-                        }
-#pragma unroll
-                        for (int q = 0; q < 16; ++q) u = fmaf(mv[q >> 2][q & 3], tv[q >> 2][q & 3], u);
-                    }
-                    u *= sb[i];
-                }
-                const uint16_t hi = f32_to_bf16_bits(u);
-                uint16_t* urow = reinterpret_cast<uint16_t*>(utile + (size_t)row * UROW);
-                urow[j] = hi;
-                urow[rp + j] = f32_to_bf16_bits(u - bf16_bits_to_f32(hi));
-            }
-        }
-    }
+    if (!DUMP) u_tile_finish<BM, EU>(it, a.flags, tid, tp, sb, mreg, tvec, Ms, utile);   // part 2 (one barrier inside)
 
     i32x16 acc[LIMBS][MB];
     f32x16 tot[MB];                                          // 4-bit only: group-scaled running totals
@@ -870,56 +933,247 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     TSTAMP(4)
 
     // ---- epilogue 3: the tile leaves as full rows, 16 bytes per thread where the output allows it
-    constexpr int ESZ = YBF16 ? 2 : 4, EPV = 16 / ESZ, PPR = 128 / EPV;     // elements per vector, vectors per row
-    unsigned char* Yb = reinterpret_cast<unsigned char*>(it.Y);
-    const int n0 = nb0 * 32;
-    const bool vec_ok = (dout % EPV == 0) && ((reinterpret_cast<uintptr_t>(it.Y) & 15) == 0);
-    const float* __restrict__ rv = it.rv;                 // fused reward: this tile's share of <Y[i,:], v>
-    const bool rv_vec = rv && (reinterpret_cast<uintptr_t>(rv) & 15) == 0 && dout % EPV == 0;
-#pragma unroll
-    for (int p0 = 0; p0 < BM * PPR; p0 += NT) {           // BM * PPR is a multiple of NT: every lane takes part in the shuffles
-        const int p = p0 + tid;
-        const int row = p / PPR, piece = p % PPR;
-        const int i = m0 + row, o = n0 + piece * EPV;
-        const bool valid = i < R && o < dout;
-        const unsigned char* src = smem + (size_t)row * CROW + piece * 16;
-        const u32x4 val = *reinterpret_cast<const u32x4*>(src);
-        if (valid) {
-            if (vec_ok && o + EPV <= dout) {
-                *reinterpret_cast<u32x4*>(Yb + ((size_t)i * dout + o) * ESZ) = val;
-            } else {
-                for (int e = 0; e < EPV && o + e < dout; ++e) {
-                    if (YBF16) reinterpret_cast<uint16_t*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const uint16_t*>(src)[e];
-                    else reinterpret_cast<float*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const float*>(src)[e];
-                }
-            }
-        }
-        if (rv) {
-            float yv[EPV], s = 0.f;
-#pragma unroll
-            for (int e = 0; e < EPV; ++e)
-                yv[e] = YBF16 ? __uint_as_float((e & 1) ? (val[e >> 1] & 0xffff0000u) : (val[e >> 1] << 16)) : __uint_as_float(val[e]);
-            if (valid) {
-                if (rv_vec && o + EPV <= dout) {
-#pragma unroll
-                    for (int e4 = 0; e4 < EPV / 4; ++e4) {
-                        const f32x4 r4 = *reinterpret_cast<const f32x4*>(rv + o + 4 * e4);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) s = fmaf(yv[4 * e4 + e], r4[e], s);
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < EPV; ++e)
-                        if (o + e < dout) s = fmaf(yv[e], rv[o + e], s);
-                }
-            }
-#pragma unroll
-            for (int off = PPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-            // one partial per (128-channel block, row); the blocks are added in a fixed order later
-            if (piece == 0 && i < R) it.rowpart[(size_t)(nb0 >> 2) * R + i] = s;
-        }
-    }
+    store_ctile<YBF16, BM>(smem, it, m0, nb0 * 32, nb0 >> 2, tid);
     TSTAMP(5)
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same product for prefill-sized row counts.  Tile = 128 rows x 256 channels; the 8 waves form a 2 (rows) x 4
+// (channels) grid and each owns a 64 x 64 patch, i.e. 2 x 2 MFMA blocks per limb with no K split: every activation
+// fragment meets two weight fragments and every weight fragment four activation fragments (both limbs), so a K
+// chunk costs 6 LDS fragment reads for 8 MFMAs.  Both operands go through LDS here (a weight block is needed by two
+// waves): per K step of 64 a workgroup brings in 16 KB of limbs and 16 KB of weights for 1024 MFMA cycles per SIMD,
+// half the load per MFMA of the decode tile.  Weight blocks keep their pre-tiled operand order in LDS (1 KB each,
+// read back as one contiguous kilobyte per wave), activation rows are padded to 80 bytes.
+// One step: fragments of chunk 0 <- LDS; tile kt+1 (in registers since the previous step) -> the other LDS stage;
+// loads of tile kt+2; MFMAs of chunk 0 interleaved with the fragment reads of chunk 1; MFMAs of chunk 1; barrier.
+// ------------------------------------------------------------------------------------------------
+constexpr int BK = 64;             // K per step
+constexpr int BXROW = BK + 16;     // LDS pitch of an activation row
+constexpr int BIG_BM = 128;        // rows per tile
+constexpr int BIG_NB = 8;          // 32-channel blocks per tile (256 channels)
+
+template <int LIMBS>
+constexpr size_t big_stage_bytes() { return (size_t)LIMBS * BIG_BM * BXROW + 2 * BIG_NB * 1024; }
+
+template <int LIMBS, bool YBF16>
+constexpr size_t big_smem_bytes() {
+    constexpr size_t stages = 2 * big_stage_bytes<LIMBS>();
+    constexpr size_t ctile = (size_t)BIG_BM * (128 * (YBF16 ? 2 : 4) + 16);
+    constexpr size_t pre = stages + (size_t)BIG_BM * UTP * 4 + 32 * UTP * 4;
+    constexpr size_t big = pre > ctile ? pre : ctile;
+    return big + BIG_BM * 4 + (size_t)BIG_BM * UROW;
+}
+
+template <int LIMBS, bool YBF16>
+__global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
+    constexpr int BM = BIG_BM;
+    constexpr size_t STAGE = big_stage_bytes<LIMBS>();
+    constexpr size_t WOFF = (size_t)LIMBS * BM * BXROW;                // weight blocks inside a stage
+    constexpr size_t BIG = big_smem_bytes<LIMBS, YBF16>() - BM * 4 - (size_t)BM * UROW;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float* xd = reinterpret_cast<float*>(smem + BIG);                  // [BM] value of one fixed-point unit per row
+    unsigned char* utile = smem + BIG + BM * 4;                        // [BM][UROW] bf16 head+tail of u_i
+
+    int g = 0;
+#pragma unroll
+    for (int i = 1; i < ESSA_MAX_GROUP; ++i) g += (i < a.n_items && (int)blockIdx.x >= a.tile_start[i]) ? 1 : 0;
+    const fwd_item it = fetch_item(a.it[g]);
+    const int R = it.R, dout = it.d_out, dpad = it.d_in_pad, rp = it.rp;
+    const int tiles_m = (R + BM - 1) / BM, tiles_n = (it.n_blocks + BIG_NB - 1) / BIG_NB;
+    // blocks go round-robin over the 8 XCDs: give each XCD a contiguous range of tiles, and inside it walk patches of
+    // 4 row tiles x all column tiles, column tile fastest, so that the 32 workgroups an XCD runs at a time share a
+    // few activation and weight tiles behind its L2
+    const int ntile = a.tile_start[g + 1] - a.tile_start[g];
+    int tile = blockIdx.x - a.tile_start[g];
+    if ((ntile & 7) == 0 && (a.tile_start[g] & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);
+    int tm, tn;
+    {
+        const int per_group = 4 * tiles_n, grp = tile / per_group, rem = tile % per_group;
+        const int rows_in_group = min(4, tiles_m - 4 * grp);               // the last group may hold fewer row tiles
+        tn = rem / rows_in_group;
+        tm = 4 * grp + rem % rows_in_group;
+    }
+    const int m0 = tm * BM, nb0 = tn * BIG_NB;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 2, wc = wave & 3;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int nk = dpad / BK;                                          // even: d_in_pad is a multiple of 512
+
+    // global -> LDS staging.  Activations: vector e of thread tid is 16-byte part (tid & 3) of row (tid >> 2) of limb e.
+    // Weights: vector e of wave w is K chunk e of the step, 32-channel block w of the tile (one kilobyte per wave).
+    rsrc_t xres[LIMBS];
+#pragma unroll
+    for (int e = 0; e < LIMBS; ++e) xres[e] = make_rsrc((e == 0 ? it.Xh : it.Xl) + (size_t)m0 * dpad);
+    const uint32_t xoff = (uint32_t)(tid >> 2) * (uint32_t)dpad + (tid & 3) * 16;
+    const uint32_t xdst = (uint32_t)(tid >> 2) * BXROW + (tid & 3) * 16;
+    const uint32_t wstride_b = (uint32_t)it.n_blocks * 1024;
+    const rsrc_t wres = make_rsrc(reinterpret_cast<const unsigned char*>(it.Wt) + (size_t)min(nb0 + wave, it.n_blocks - 1) * 1024);
+    const uint32_t lane16 = lane * 16;
+    const uint32_t wdst = (uint32_t)WOFF + wave * 1024 + lane16;
+
+    u32x4 xs[LIMBS], ws[2];
+    auto load_tile = [&](int kt) {
+#pragma unroll
+        for (int e = 0; e < LIMBS; ++e) xs[e] = load16(xres[e], xoff, (uint32_t)kt * BK);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) ws[e] = load16(wres, lane16, (uint32_t)(kt * 2 + e) * wstride_b);
+    };
+    auto store_tile = [&](int stage) {
+        unsigned char* sb_ = smem + (size_t)stage * STAGE;
+#pragma unroll
+        for (int e = 0; e < LIMBS; ++e) *reinterpret_cast<u32x4*>(sb_ + (size_t)e * BM * BXROW + xdst) = xs[e];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) *reinterpret_cast<u32x4*>(sb_ + wdst + (size_t)e * BIG_NB * 1024) = ws[e];
+    };
+
+    // rank-space vectors of the tile's rows, and the rows' fixed-point units
+    float* tvec = reinterpret_cast<float*>(smem + 2 * STAGE);
+    float* Ms = tvec + BM * UTP;
+    constexpr int EU = (BM * 32 + NT - 1) / NT;
+    {
+        float tp[EU][8], sbv[EU], mreg[2];
+        u_tile_loads<BM, EU>(it, m0, tid, tp, sbv, mreg);
+        const float xdreg = it.xdelta[min(m0 + min(tid, BM - 1), R - 1)];
+        load_tile(0);
+        u_tile_finish<BM, EU>(it, a.flags, tid, tp, sbv, mreg, tvec, Ms, utile);
+        if (tid < BM) xd[tid] = xdreg;
+    }
+    store_tile(0);
+    load_tile(min(1, nk - 1));
+    __syncthreads();
+
+    i32x16 acc[LIMBS][2][2];
+#pragma unroll
+    for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[l][mb][nb][q] = 0;
+
+    // fragment addresses of this lane inside a stage
+    const uint32_t afrag = (uint32_t)(wr * 64 + l32) * BXROW + 16 * h;                 // + (l * BM + mb * 32) * BXROW + c * 32
+    const uint32_t bfrag = (uint32_t)WOFF + (uint32_t)(wc * 2) * 1024 + lane16;       // + (c * BIG_NB + nb) * 1024
+    constexpr int NA = LIMBS * 2;                       // activation fragments per chunk
+    i32x4 fa0[NA], fb0[2], fa1[NA], fb1[2];
+#define BIG_READ_A(F, ST, C, I) F[I] = *reinterpret_cast<const i32x4*>(smem + (size_t)(ST) * STAGE + afrag + (size_t)(((I) >> 1) * BM + ((I) & 1) * 32) * BXROW + (C) * 32)
+#define BIG_READ_B(F, ST, C, I) F[I] = *reinterpret_cast<const i32x4*>(smem + (size_t)(ST) * STAGE + bfrag + (size_t)((C) * BIG_NB + (I)) * 1024)
+#define BIG_STEP(KTI, ST)                                                                                      \
+    {                                                                                                          \
+        const int kt_ = (KTI);                                                                                 \
+        _Pragma("unroll") for (int i_ = 0; i_ < NA; ++i_) BIG_READ_A(fa0, ST, 0, i_);                          \
+        _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_) BIG_READ_B(fb0, ST, 0, i_);                           \
+        __builtin_amdgcn_sched_barrier(0);                                                                     \
+        store_tile((ST) ^ 1);                                                                                  \
+        __builtin_amdgcn_sched_barrier(0);                                                                     \
+        load_tile(min(kt_ + 2, nk - 1));                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                                     \
+        _Pragma("unroll") for (int i_ = 0; i_ < NA * 2; ++i_) {                                                \
+            acc[i_ >> 2][(i_ >> 1) & 1][i_ & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                       \
+                fa0[i_ >> 1], fb0[i_ & 1], acc[i_ >> 2][(i_ >> 1) & 1][i_ & 1], 0, 0, 0);                      \
+            if (i_ < NA) BIG_READ_A(fa1, ST, 1, i_);                                                           \
+            else if (i_ < NA + 2) BIG_READ_B(fb1, ST, 1, i_ - NA);                                             \
+            __builtin_amdgcn_sched_barrier(0);                                                                 \
+        }                                                                                                      \
+        _Pragma("unroll") for (int i_ = 0; i_ < NA * 2; ++i_)                                                  \
+            acc[i_ >> 2][(i_ >> 1) & 1][i_ & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                       \
+                fa1[i_ >> 1], fb1[i_ & 1], acc[i_ >> 2][(i_ >> 1) & 1][i_ & 1], 0, 0, 0);                      \
+        __builtin_amdgcn_sched_barrier(0);                                                                     \
+        __syncthreads();                                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                                     \
+    }
+    for (int kt0 = 0; kt0 < nk; kt0 += 2) {
+        BIG_STEP(kt0, 0)
+        BIG_STEP(kt0 + 1, 1)
+    }
+#undef BIG_STEP
+#undef BIG_READ_A
+#undef BIG_READ_B
+
+    // ---- epilogue, one half of the tile (128 channels) at a time: scale, rank-r term, LDS output tile, store
+    constexpr int CROW = 128 * (YBF16 ? 2 : 4) + 16;
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        if ((wc >> 1) == half) {
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const int oc = min((nb0 + wc * 2 + nb) * 32 + l32, dout - 1);
+                const float wscale = it.scale[oc];
+                u32x4 ubf[2][2];
+                const uint16_t* bp = it.UB16 + (size_t)oc * 2 * rp + 8 * h;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    ubf[ks][0] = ubf[ks][1] = (u32x4){0, 0, 0, 0};
+                    if (ks * 16 < rp) {
+                        ubf[ks][0] = *reinterpret_cast<const u32x4*>(bp + ks * 16);
+                        ubf[ks][1] = *reinterpret_cast<const u32x4*>(bp + rp + ks * 16);
+                    }
+                }
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    f32x16 v;
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) {
+                        const int rl = wr * 64 + mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+                        const float sc = xd[rl] * wscale;
+                        if (LIMBS == 2) v[q] = fmaf(128.0f, (float)acc[0][mb][nb][q], (float)acc[LIMBS - 1][mb][nb][q]) * sc;
+                        else v[q] = (float)acc[0][mb][nb][q] * sc;
+                        if (a.flags & ESSA_LORA_ONLY) v[q] = 0.f;
+                    }
+                    if (!(a.flags & ESSA_BASE_ONLY)) {
+                        // rank-r term U_B u_i: bf16 head+tail operands, lo*hi + hi*lo + hi*hi per 16 rank columns
+                        const unsigned char* up = utile + (size_t)(wr * 64 + mb * 32 + l32) * UROW + 16 * h;
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks) {
+                            if (ks * 16 < rp) {
+                                const bf16x8 ua_hi = *reinterpret_cast<const bf16x8*>(up + ks * 32);
+                                const bf16x8 ua_lo = *reinterpret_cast<const bf16x8*>(up + 2 * rp + ks * 32);
+                                const bf16x8 ub_hi = __builtin_bit_cast(bf16x8, ubf[ks][0]);
+                                const bf16x8 ub_lo = __builtin_bit_cast(bf16x8, ubf[ks][1]);
+                                v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_lo, ub_hi, v, 0, 0, 0);
+                                v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_hi, ub_lo, v, 0, 0, 0);
+                                v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_hi, ub_hi, v, 0, 0, 0);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) {
+                        const int rl = wr * 64 + mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+                        unsigned char* dst = smem + (size_t)rl * CROW + ((wc & 1) * 64 + nb * 32 + l32) * (YBF16 ? 2 : 4);
+                        if (YBF16) *reinterpret_cast<uint16_t*>(dst) = f32_to_bf16_bits(v[q]);
+                        else *reinterpret_cast<float*>(dst) = v[q];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        store_ctile<YBF16, BM>(smem, it, m0, nb0 * 32 + half * 128, (nb0 >> 2) + half, tid);
+        __syncthreads();
+    }
+}
+
+template <int LIMBS, bool YBF16>
+hipError_t launch_gemm_big(hipStream_t st, stream_args& a) {
+    int total = 0;
+    for (int g = 0; g < a.n_items; ++g) {
+        a.tile_start[g] = total;
+        total += ((a.it[g].R + BIG_BM - 1) / BIG_BM) * ((a.it[g].n_blocks + BIG_NB - 1) / BIG_NB);
+    }
+    a.tile_start[a.n_items] = total;
+    constexpr size_t smem = big_smem_bytes<LIMBS, YBF16>();
+    static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
+    auto kern = gemm_i8_big_kernel<LIMBS, YBF16>;
+    static bool attr_done = false;   // one flag per instantiation
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a);
+    return hipGetLastError();
 }
 
 template <int MB, int LIMBS, bool YBF16, bool DUMP, bool Q4 = false>
@@ -968,6 +1222,17 @@ int pick_mb(const stream_args& a) {
     return maxR <= 32 ? 1 : 2;
 }
 
+// the 128 x 256 tile pays off once it fills the chip a few times over
+bool takes_big(const stream_args& a) {
+#ifdef EXP_NO_BIG
+    return false;
+#endif
+    long long tiles = 0;
+    for (int g = 0; g < a.n_items; ++g)
+        tiles += (long long)((a.it[g].R + BIG_BM - 1) / BIG_BM) * ((a.it[g].n_blocks + BIG_NB - 1) / BIG_NB);
+    return tiles >= 1024;
+}
+
 void fill_prep_tables(stream_args& a) {
     int q = 0, l = 0;
     for (int g = 0; g < a.n_items; ++g) {
@@ -996,6 +1261,10 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
     const int mb = pick_mb(a);
     if (ev_start) (void)hipEventRecord(ev_start, st);
     hipError_t e;
+    if (items[0].quant != ESSA_QUANT_INT4_G128 && takes_big(a)) {
+        if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_big<2, true>(st, a) : launch_gemm_big<2, false>(st, a);
+        else e = y_dtype == ESSA_BF16 ? launch_gemm_big<1, true>(st, a) : launch_gemm_big<1, false>(st, a);
+    } else
     if (items[0].quant == ESSA_QUANT_INT4_G128)   // all items of a call share the weight format
         e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true, true>(st, a, mb) : launch_gemm_mb<2, false, true>(st, a, mb);
     else if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true, false>(st, a, mb) : launch_gemm_mb<2, false, false>(st, a, mb);

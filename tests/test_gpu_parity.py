@@ -459,6 +459,50 @@ def test_forward_reward_fused(essa, ctx, quant, x_fp32):
         gp.close()
 
 
+def test_forward_large_row_count_tile(essa, ctx):
+    """Row counts in the thousands take the 128 x 256 tile: ragged rows and channels (the last tile's second half lies
+    past d_out), both output types, one and two limbs, and the reward partials of every 128-channel block."""
+    d_in, d_out, r, K, R = 192, 15400, 16, 7, 2050
+    _say("large-R tile: d_in=%d d_out=%d R=%d" % (d_in, d_out, R))
+    p = wl.make_projection("t", d_in, d_out, r, "int8", layer=5, proj=2)
+    W, f = oracle_proj(p)
+    gp = gpu_proj(essa, ctx, p)
+    sA, sB = candidate_sigmas(f, K, 0.05)
+    xb, xv = wl.make_x_bf16(R, d_in, x_id=11)
+    r2c = np.random.default_rng(2).integers(0, K, R).astype(np.int32)
+    ref = orc.svdlora_forward(W, f, xv, r2c, sA, sB)
+    Xd, rd, sAd, sBd = bf16_dev(xb), to_dev(r2c), to_dev(sA), to_dev(sB)
+    Y32 = torch.empty(R, d_out, device="cuda")
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32)
+    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref)
+    _say("  fp32 out: max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= LIMB_RMS and e_max <= LIMB_MAX
+    Y16 = torch.empty(R, d_out, device="cuda", dtype=torch.bfloat16)
+    v = wl.reward_vector(d_out, 5, 2)
+    nblk = (d_out + essa.REWARD_BLOCK - 1) // essa.REWARD_BLOCK
+    rowpart = torch.full((nblk + 1, R), float("nan"), device="cuda")
+    grp = essa.ForwardGroup([(gp, Xd, rd, sAd, sBd, Y16)], [to_dev(v)])
+    assert essa.essa_svdlora_forward_reward_group(ctx, grp, None, rowpart) == nblk
+    ref16 = orc.round_to_bf16(ref)
+    e_max, e_rms = orc.rel_errors(bf16_host(Y16), ref16)
+    _say("  bf16 out: max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= BF16_RMS and e_max <= BF16_MAX
+    assert not torch.isnan(rowpart[:nblk]).any() and torch.isnan(rowpart[nblk]).all()
+    F = torch.zeros(K, device="cuda")
+    essa.essa_reward_finish(ctx, rowpart, nblk, rd, F)
+    F_ref = orc.reward_accumulate(np.zeros(K), ref16, v, r2c, K)
+    assert np.all(np.abs(F.cpu().numpy() - F_ref) <= _reward_bound(ref16, v, r2c, K, 2e-3))
+    # the rank-r term and the base alone, and the one-limb mode against its own oracle
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, essa.LORA_ONLY)
+    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), orc.svdlora_forward(W, f, xv, r2c, sA, sB, lora_only=True))
+    assert e_rms <= 1e-4 and e_max <= 1e-3
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, essa.COMPUTE_W8A8)
+    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), orc.svdlora_forward_w8a8(p.Wq, p.scales, f, xv, r2c, sA, sB))
+    _say("  w8a8: max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= EXACT_RMS and e_max <= EXACT_MAX
+    gp.close()
+
+
 @pytest.mark.parametrize("K", [1, 4, 32, 64, 128, 400, 1024])
 def test_rank_bit_exact(essa, ctx, K):
     g = np.random.default_rng(K)
