@@ -944,12 +944,14 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
 // chunk costs 6 LDS fragment reads for 8 MFMAs.  Both operands go through LDS here (a weight block is needed by two
 // waves): per K step of 64 a workgroup brings in 16 KB of limbs and 16 KB of weights for 1024 MFMA cycles per SIMD,
 // half the load per MFMA of the decode tile.  Weight blocks keep their pre-tiled operand order in LDS (1 KB each,
-// read back as one contiguous kilobyte per wave), activation rows are padded to 80 bytes.
-// One step: fragments of chunk 0 <- LDS; tile kt+1 (in registers since the previous step) -> the other LDS stage;
-// loads of tile kt+2; MFMAs of chunk 0 interleaved with the fragment reads of chunk 1; MFMAs of chunk 1; barrier.
+// read back as one contiguous kilobyte per wave); activation rows are 64 bytes with their four 16-byte parts
+// XOR-swizzled by the row, so that both the row-wise writes and the fragment reads are free of bank conflicts.
+// One step: fragments of chunk 0 <- LDS; MFMAs of chunk 0 interleaved with the fragment reads of chunk 1; tile kt+1
+// (in registers since two steps ago) -> the other LDS stage; loads of tile kt+3 into those registers; MFMAs of
+// chunk 1; barrier.
 // ------------------------------------------------------------------------------------------------
 constexpr int BK = 64;             // K per step
-constexpr int BXROW = BK + 16;     // LDS pitch of an activation row
+constexpr int BXROW = BK;          // LDS pitch of an activation row: no padding, the four 16-byte parts of row r sit at part ^ ((r >> 2) & 3)
 constexpr int BIG_BM = 128;        // rows per tile
 constexpr int BIG_NB = 8;          // 32-channel blocks per tile (256 channels)
 
@@ -958,7 +960,7 @@ constexpr size_t big_stage_bytes() { return (size_t)LIMBS * BIG_BM * BXROW + 2 *
 
 template <int LIMBS, bool YBF16>
 constexpr size_t big_smem_bytes() {
-    constexpr size_t stages = 2 * big_stage_bytes<LIMBS>();
+    constexpr size_t stages = 3 * big_stage_bytes<LIMBS>();
     constexpr size_t ctile = (size_t)BIG_BM * (128 * (YBF16 ? 2 : 4) + 16);
     constexpr size_t pre = stages + (size_t)BIG_BM * UTP * 4 + 32 * UTP * 4;
     constexpr size_t big = pre > ctile ? pre : ctile;
@@ -1000,6 +1002,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
     const int wr = wave >> 2, wc = wave & 3;
     const int l32 = lane & 31, h = lane >> 5;
     const int nk = dpad / BK;                                          // even: d_in_pad is a multiple of 512
+    TSTAMP(0)
 
     // global -> LDS staging.  Activations: vector e of thread tid is 16-byte part (tid & 3) of row (tid >> 2) of limb e.
     // Weights: vector e of wave w is K chunk e of the step, 32-channel block w of the tile (one kilobyte per wave).
@@ -1007,21 +1010,22 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
 #pragma unroll
     for (int e = 0; e < LIMBS; ++e) xres[e] = make_rsrc((e == 0 ? it.Xh : it.Xl) + (size_t)m0 * dpad);
     const uint32_t xoff = (uint32_t)(tid >> 2) * (uint32_t)dpad + (tid & 3) * 16;
-    const uint32_t xdst = (uint32_t)(tid >> 2) * BXROW + (tid & 3) * 16;
+    const uint32_t xdst = (uint32_t)(tid >> 2) * BXROW + (((tid & 3) ^ ((tid >> 4) & 3)) * 16);
     const uint32_t wstride_b = (uint32_t)it.n_blocks * 1024;
     const rsrc_t wres = make_rsrc(reinterpret_cast<const unsigned char*>(it.Wt) + (size_t)min(nb0 + wave, it.n_blocks - 1) * 1024);
     const uint32_t lane16 = lane * 16;
     const uint32_t wdst = (uint32_t)WOFF + wave * 1024 + lane16;
 
-    u32x4 xs[LIMBS], ws[2];
-    auto load_tile = [&](int kt) {
+    // two register sets: tile kt+1 waits in one (loaded two steps ago) while tile kt+2 is on its way into the other
+    u32x4 xs0[LIMBS], ws0[2], xs1[LIMBS], ws1[2];
+    auto load_tile = [&](u32x4 (&xs)[LIMBS], u32x4 (&ws)[2], int kt) {
 #pragma unroll
         for (int e = 0; e < LIMBS; ++e) xs[e] = load16(xres[e], xoff, (uint32_t)kt * BK);
 #pragma unroll
         for (int e = 0; e < 2; ++e) ws[e] = load16(wres, lane16, (uint32_t)(kt * 2 + e) * wstride_b);
     };
-    auto store_tile = [&](int stage) {
-        unsigned char* sb_ = smem + (size_t)stage * STAGE;
+    auto store_tile = [&](const u32x4 (&xs)[LIMBS], const u32x4 (&ws)[2], uint32_t stage_off) {
+        unsigned char* sb_ = smem + stage_off;
 #pragma unroll
         for (int e = 0; e < LIMBS; ++e) *reinterpret_cast<u32x4*>(sb_ + (size_t)e * BM * BXROW + xdst) = xs[e];
 #pragma unroll
@@ -1029,19 +1033,26 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
     };
 
     // rank-space vectors of the tile's rows, and the rows' fixed-point units
-    float* tvec = reinterpret_cast<float*>(smem + 2 * STAGE);
+    float* tvec = reinterpret_cast<float*>(smem + 3 * STAGE);
     float* Ms = tvec + BM * UTP;
     constexpr int EU = (BM * 32 + NT - 1) / NT;
     {
         float tp[EU][8], sbv[EU], mreg[2];
         u_tile_loads<BM, EU>(it, m0, tid, tp, sbv, mreg);
         const float xdreg = it.xdelta[min(m0 + min(tid, BM - 1), R - 1)];
-        load_tile(0);
+        load_tile(xs0, ws0, 0);
         u_tile_finish<BM, EU>(it, a.flags, tid, tp, sbv, mreg, tvec, Ms, utile);
         if (tid < BM) xd[tid] = xdreg;
     }
-    store_tile(0);
-    load_tile(min(1, nk - 1));
+    // tiles 0 and 1 go to stages 0 and 1; tiles 2 and 3 wait in the two register sets
+    load_tile(xs1, ws1, min(1, nk - 1));
+    store_tile(xs0, ws0, 0);
+    store_tile(xs1, ws1, (uint32_t)STAGE);
+    __builtin_amdgcn_sched_barrier(0);
+    load_tile(xs0, ws0, min(2, nk - 1));          // in the order the loop's steps issue them (even tile, then odd tile)
+    __builtin_amdgcn_sched_barrier(0);
+    load_tile(xs1, ws1, min(3, nk - 1));
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
 
     i32x16 acc[LIMBS][2][2];
@@ -1055,40 +1066,51 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
                 for (int q = 0; q < 16; ++q) acc[l][mb][nb][q] = 0;
 
     // fragment addresses of this lane inside a stage
-    const uint32_t afrag = (uint32_t)(wr * 64 + l32) * BXROW + 16 * h;                 // + (l * BM + mb * 32) * BXROW + c * 32
+    const uint32_t afrag = (uint32_t)(wr * 64 + l32) * BXROW;                          // + (l * BM + mb * 32) * BXROW + swizzled part
+    const uint32_t asw = (l32 >> 2) & 3;                                               // rows 32 apart share the swizzle
     const uint32_t bfrag = (uint32_t)WOFF + (uint32_t)(wc * 2) * 1024 + lane16;       // + (c * BIG_NB + nb) * 1024
     constexpr int NA = LIMBS * 2;                       // activation fragments per chunk
     i32x4 fa0[NA], fb0[2], fa1[NA], fb1[2];
-#define BIG_READ_A(F, ST, C, I) F[I] = *reinterpret_cast<const i32x4*>(smem + (size_t)(ST) * STAGE + afrag + (size_t)(((I) >> 1) * BM + ((I) & 1) * 32) * BXROW + (C) * 32)
-#define BIG_READ_B(F, ST, C, I) F[I] = *reinterpret_cast<const i32x4*>(smem + (size_t)(ST) * STAGE + bfrag + (size_t)((C) * BIG_NB + (I)) * 1024)
-#define BIG_STEP(KTI, ST)                                                                                      \
+#define BIG_READ_A(F, SOFF, C, I) F[I] = *reinterpret_cast<const i32x4*>(smem + (SOFF) + afrag + (size_t)(((I) >> 1) * BM + ((I) & 1) * 32) * BXROW + ((((C) * 2 + h) ^ asw) * 16))
+#define BIG_READ_B(F, SOFF, C, I) F[I] = *reinterpret_cast<const i32x4*>(smem + (SOFF) + bfrag + (size_t)((C) * BIG_NB + (I)) * 1024)
+    // tile j lives in stage j % 3.  One step (tile kt): MFMAs of chunk 0 (fragments read during the previous step)
+    // interleaved with the fragment reads of chunk 1; tile kt+2 (in registers since two steps ago) -> the stage tile
+    // kt-1 has left; loads of tile kt+4; MFMAs of chunk 1 interleaved with the reads of chunk 0 of tile kt+1 (complete
+    // in LDS since the last barrier); barrier.  No LDS or memory latency sits between the barrier and the next MFMA.
+    uint32_t s_cur = 0, s_nxt = (uint32_t)STAGE, s_wr = 2 * (uint32_t)STAGE;
+    _Pragma("unroll") for (int i_ = 0; i_ < NA; ++i_) BIG_READ_A(fa0, s_cur, 0, i_);
+    _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_) BIG_READ_B(fb0, s_cur, 0, i_);
+#define BIG_STEP(KTI, XS, WS)                                                                                  \
     {                                                                                                          \
         const int kt_ = (KTI);                                                                                 \
-        _Pragma("unroll") for (int i_ = 0; i_ < NA; ++i_) BIG_READ_A(fa0, ST, 0, i_);                          \
-        _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_) BIG_READ_B(fb0, ST, 0, i_);                           \
-        __builtin_amdgcn_sched_barrier(0);                                                                     \
-        store_tile((ST) ^ 1);                                                                                  \
-        __builtin_amdgcn_sched_barrier(0);                                                                     \
-        load_tile(min(kt_ + 2, nk - 1));                                                                       \
-        __builtin_amdgcn_sched_barrier(0);                                                                     \
         _Pragma("unroll") for (int i_ = 0; i_ < NA * 2; ++i_) {                                                \
             acc[i_ >> 2][(i_ >> 1) & 1][i_ & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                       \
                 fa0[i_ >> 1], fb0[i_ & 1], acc[i_ >> 2][(i_ >> 1) & 1][i_ & 1], 0, 0, 0);                      \
-            if (i_ < NA) BIG_READ_A(fa1, ST, 1, i_);                                                           \
-            else if (i_ < NA + 2) BIG_READ_B(fb1, ST, 1, i_ - NA);                                             \
+            if (i_ < NA) BIG_READ_A(fa1, s_cur, 1, i_);                                                        \
+            else if (i_ < NA + 2) BIG_READ_B(fb1, s_cur, 1, i_ - NA);                                          \
             __builtin_amdgcn_sched_barrier(0);                                                                 \
         }                                                                                                      \
-        _Pragma("unroll") for (int i_ = 0; i_ < NA * 2; ++i_)                                                  \
+        store_tile(XS, WS, s_wr);                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                     \
+        load_tile(XS, WS, min(kt_ + 4, nk - 1));                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                                                     \
+        _Pragma("unroll") for (int i_ = 0; i_ < NA * 2; ++i_) {                                                \
             acc[i_ >> 2][(i_ >> 1) & 1][i_ & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                       \
                 fa1[i_ >> 1], fb1[i_ & 1], acc[i_ >> 2][(i_ >> 1) & 1][i_ & 1], 0, 0, 0);                      \
-        __builtin_amdgcn_sched_barrier(0);                                                                     \
+            if (i_ < NA) BIG_READ_A(fa0, s_nxt, 0, i_);                                                        \
+            else if (i_ < NA + 2) BIG_READ_B(fb0, s_nxt, 0, i_ - NA);                                          \
+            __builtin_amdgcn_sched_barrier(0);                                                                 \
+        }                                                                                                      \
         __syncthreads();                                                                                       \
         __builtin_amdgcn_sched_barrier(0);                                                                     \
+        { const uint32_t t_ = s_cur; s_cur = s_nxt; s_nxt = s_wr; s_wr = t_; }                                 \
     }
+    TSTAMP(1)
     for (int kt0 = 0; kt0 < nk; kt0 += 2) {
-        BIG_STEP(kt0, 0)
-        BIG_STEP(kt0 + 1, 1)
+        BIG_STEP(kt0, xs0, ws0)
+        BIG_STEP(kt0 + 1, xs1, ws1)
     }
+    TSTAMP(2)
 #undef BIG_STEP
 #undef BIG_READ_A
 #undef BIG_READ_B
