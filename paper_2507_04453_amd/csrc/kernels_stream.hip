@@ -11,6 +11,7 @@
 // through LDS and shared by the four waves.  With one limb (ESSA_COMPUTE_W8A8) the same kernel is the
 // plain W8A8 mode.  The rank-r term is added by bf16 head+tail MFMA steps in the epilogue.
 #include "essa_internal.h"
+#include <hip/hip_ext.h>
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -950,6 +951,9 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
 // (in registers since two steps ago) -> the other LDS stage; loads of tile kt+3 into those registers; MFMAs of
 // chunk 1; barrier.
 // ------------------------------------------------------------------------------------------------
+// events of the launch being timed (set by forward_stream around its GEMM launch, null otherwise)
+thread_local hipEvent_t tl_ev_start = nullptr, tl_ev_stop = nullptr;
+
 constexpr int BK = 64;             // K per step
 constexpr int BXROW = BK;          // LDS pitch of an activation row: no padding, the four 16-byte parts of row r sit at part ^ ((r >> 2) & 3)
 constexpr int BIG_BM = 128;        // rows per tile
@@ -1194,7 +1198,8 @@ hipError_t launch_gemm_big(hipStream_t st, stream_args& a) {
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a);
+    if (tl_ev_start) hipExtLaunchKernelGGL(kern, dim3(total), dim3(NT), (uint32_t)smem, st, tl_ev_start, tl_ev_stop, 0, a);
+    else hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a);
     return hipGetLastError();
 }
 
@@ -1215,7 +1220,10 @@ hipError_t launch_gemm(hipStream_t st, stream_args& a, int32_t* acc_out) {
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a, acc_out);
+    // with a pair of events the launch itself stamps them at the kernel's first and last cycle (what a profiler reports
+    // as the kernel's duration); events recorded around the launch would add the dispatch latency
+    if (tl_ev_start) hipExtLaunchKernelGGL(kern, dim3(total), dim3(NT), (uint32_t)smem, st, tl_ev_start, tl_ev_stop, 0, a, acc_out);
+    else hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a, acc_out);
     return hipGetLastError();
 }
 
@@ -1224,7 +1232,11 @@ hipError_t launch_gemm_mb(hipStream_t st, stream_args& a, int mb) {
     switch (mb) {
         case 1: return launch_gemm<1, LIMBS, YBF16, false, Q4>(st, a, nullptr);
         case 2: return launch_gemm<2, LIMBS, YBF16, false, Q4>(st, a, nullptr);
-        default: return launch_gemm<4, LIMBS, YBF16, false, Q4>(st, a, nullptr);
+        default:
+            // the 128-row tile exists for 4-bit weights only: with int8 weights its double-buffered fragments do not
+            // fit the register file, and row counts that large take the 128 x 256 kernel anyway
+            if constexpr (Q4) return launch_gemm<4, LIMBS, YBF16, false, Q4>(st, a, nullptr);
+            else return launch_gemm<2, LIMBS, YBF16, false, Q4>(st, a, nullptr);
     }
 }
 
@@ -1252,7 +1264,7 @@ bool takes_big(const stream_args& a) {
     long long tiles = 0;
     for (int g = 0; g < a.n_items; ++g)
         tiles += (long long)((a.it[g].R + BIG_BM - 1) / BIG_BM) * ((a.it[g].n_blocks + BIG_NB - 1) / BIG_NB);
-    return tiles >= 1024;
+    return tiles >= 512;
 }
 
 void fill_prep_tables(stream_args& a) {
@@ -1281,7 +1293,8 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
     fill_prep_tables(a);
     hipLaunchKernelGGL(prep_kernel, dim3(a.quant_start[n_items] + a.lora_start[n_items]), dim3(PREP_NT), 0, st, a);
     const int mb = pick_mb(a);
-    if (ev_start) (void)hipEventRecord(ev_start, st);
+    tl_ev_start = ev_start;
+    tl_ev_stop = ev_stop;
     hipError_t e;
     if (items[0].quant != ESSA_QUANT_INT4_G128 && takes_big(a)) {
         if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_big<2, true>(st, a) : launch_gemm_big<2, false>(st, a);
@@ -1291,7 +1304,7 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
         e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true, true>(st, a, mb) : launch_gemm_mb<2, false, true>(st, a, mb);
     else if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true, false>(st, a, mb) : launch_gemm_mb<2, false, false>(st, a, mb);
     else e = y_dtype == ESSA_BF16 ? launch_gemm_mb<1, true, false>(st, a, mb) : launch_gemm_mb<1, false, false>(st, a, mb);
-    if (ev_stop) (void)hipEventRecord(ev_stop, st);
+    tl_ev_start = tl_ev_stop = nullptr;
     return e != hipSuccess ? e : hipGetLastError();
 }
 
