@@ -51,7 +51,7 @@ def test_philox_words_bit_exact(essa, ctx):
         assert np.array_equal(got[i], orc.philox_words_for_seed(s, nb)), "seed %d" % s
 
 
-@pytest.mark.parametrize("n,K", [(16, 4), (50, 3), (257, 70), (3584, 64)])
+@pytest.mark.parametrize("n,K", [(16, 4), (50, 3), (257, 70), (96, 42), (64, 400), (3584, 64)])
 def test_sample_candidates(essa, ctx, n, K):
     _say("sample n=%d K=%d" % (n, K))
     Q, d = wl.random_covariance_basis(n, basis_id=n)
@@ -503,6 +503,55 @@ def test_forward_large_row_count_tile(essa, ctx):
     gp.close()
 
 
+def test_forward_paper_sweep_values_mixed_group(essa, ctx):
+    """The population sizes, ranks and alpha of the paper's sweeps (Appendix, hyperparameter study: K in 24..400, r down to
+    2, alpha < 1) in ONE grouped launch with mixed ranks and mixed weight formats: candidates sampled from seeds, only the
+    top floor(alpha r) singular values of each factor moved, rows of the K = 42 candidates interleaved."""
+    K, rows_per, d_in = 42, 3, 256
+    R = K * rows_per
+    specs = [("int8", 200, 2), ("int4", 96, 4), ("int8", 328, 16), ("int4", 160, 32)]        # (format, d_out, rank)
+    alpha = 0.5
+    r2c = wl.row2cand_interleaved(K, rows_per, 3)
+    xb, xv = wl.make_x_bf16(R, d_in, x_id=21)
+    Xd, rd = bf16_dev(xb), to_dev(r2c)
+    items, refs, gps = [], [], []
+    for pi, (quant, d_out, r) in enumerate(specs):
+        p = wl.make_projection("t", d_in, d_out, r, quant, layer=9, proj=pi)
+        W, f = oracle_proj(p)
+        gp = gpu_proj(essa, ctx, p)
+        n_top = max(1, int(alpha * r))
+        n = 2 * n_top
+        # theta from seeds through the sampler (identity basis, step 0.05), then the top-alpha map, on both sides
+        cma = essa.CmaState(ctx, n, 0.05, None)
+        seeds = list(range(100 * pi + 1, 100 * pi + 1 + K))
+        theta = torch.empty(K, n, device="cuda")
+        essa.essa_sample_candidates(ctx, cma, seeds_dev(seeds), theta, None)
+        sA = torch.empty(K, 1, r, device="cuda")
+        sB = torch.empty(K, 1, r, device="cuda")
+        sftA, sftB = f["S_A"][None].astype(np.float32), f["S_B"][None].astype(np.float32)
+        essa.essa_theta_to_sigma(ctx, n_top, to_dev(sftA), to_dev(sftB), theta, sA, sB)
+        ref_theta, _ = orc.sample_candidates(np.zeros(n), np.float32(0.05), np.eye(n), np.ones(n), seeds)
+        rA, rB = orc.theta_to_sigma(ref_theta, sftA, sftB, n_top / r)
+        assert np.array_equal(sA.cpu().numpy()[:, 0, n_top:], np.tile(sftA[0, n_top:], (K, 1)))      # the tail stays frozen
+        np.testing.assert_allclose(sA.cpu().numpy(), rA, rtol=1e-5, atol=1e-7)
+        refs.append(orc.round_to_bf16(orc.svdlora_forward(W, f, xv, r2c, rA[:, 0, :], rB[:, 0, :])))
+        items.append((gp, Xd, rd, sA[:, 0, :], sB[:, 0, :], torch.empty(R, d_out, device="cuda", dtype=torch.bfloat16)))
+        gps.append(gp)
+        cma.close()
+    essa.essa_svdlora_forward_group(ctx, items)
+    for (quant, d_out, r), it, ref in zip(specs, items, refs):
+        e_max, e_rms = orc.rel_errors(bf16_host(it[5]), ref)
+        _say("  %s d_out=%d r=%d: max %.3g rms %.3g" % (quant, d_out, r, e_max, e_rms))
+        assert e_rms <= BF16_RMS and e_max <= BF16_MAX
+    # the same items one by one give the same bits
+    for it in items:
+        Y1 = torch.empty_like(it[5])
+        essa.essa_svdlora_forward(ctx, it[0], it[1], it[2], it[3], it[4], Y1)
+        assert torch.equal(Y1, it[5])
+    for gp in gps:
+        gp.close()
+
+
 @pytest.mark.parametrize("K", [1, 4, 32, 64, 128, 400, 1024])
 def test_rank_bit_exact(essa, ctx, K):
     g = np.random.default_rng(K)
@@ -527,7 +576,7 @@ def _state_errors(exp, ref):
     return out
 
 
-@pytest.mark.parametrize("n,K,gens", [(16, 4, 3), (50, 13, 3), (257, 24, 2), (3584, 64, 2)])
+@pytest.mark.parametrize("n,K,gens", [(16, 4, 3), (50, 13, 3), (257, 24, 2), (120, 36, 2), (130, 42, 2), (200, 400, 2), (3584, 64, 2)])
 def test_cmaes_update(essa, ctx, n, K, gens):
     _say("update n=%d K=%d" % (n, K))
     Q, d = wl.random_covariance_basis(n, basis_id=1000 + n)
