@@ -31,7 +31,8 @@ published algorithm; moment / range checks of the normals; closed-form CMA-ES
 constants; forward invariants (own singular values give W + B A from the
 unfactored factors, zero singular values give the base layer, brute-force
 dense products on tiny shapes, linearity, row permutation); CMA-ES invariants
-and convergence on sphere / ellipsoid.  The exact CMA-ES variant the paper ran
+and convergence on sphere / ellipsoid; the eigendecomposition against closed forms (2 x 2, diagonal,
+known spectrum) and its defining identities.  The exact CMA-ES variant the paper ran
 (an external library's defaults) cannot be checked here: against that library
 the update is PARITY UNPINNED; it is pinned to the tutorial's equations only.
 """
@@ -49,7 +50,7 @@ __all__ = [
     "thin_svd_factors", "candidate_weight", "svdlora_forward", "svdlora_forward_rows",
     "quantize_rows_int8", "int8_accumulators", "svdlora_forward_w8a8",
     "round_to_bf16", "reward_accumulate", "rank_desc_stable",
-    "CmaConstants", "cma_constants", "CmaState", "cma_state_init", "cma_update",
+    "CmaConstants", "cma_constants", "CmaState", "cma_state_init", "cma_update", "cma_refresh_basis",
     "rel_errors",
 ]
 
@@ -379,6 +380,20 @@ def cma_update(st: CmaState, seeds, rewards) -> tuple[CmaState, np.ndarray]:
     new = CmaState(n=st.n, t=st.t + 1, sigma=sigma, m=m, p_sigma=p_sigma, p_c=p_c, C=C, B=st.B, D=st.D,
                    extra=dict(h_sigma=h_sigma, ps_norm=ps_norm, z_w=z_w, y_w=y_w))
     return new, order
+
+
+def cma_refresh_basis(C):
+    """Eigendecomposition of the covariance, C = B diag(D^2) B^T (the decomposition step of the (mu/mu_w,
+    lambda)-CMA-ES in Hansen's tutorial, arXiv:1604.00772, Sec. B.2 "C -> B D^2 B^T"; Algorithm 1 of the paper keeps
+    (m, sigma, C) and samples through this factorisation).  C is symmetrised first, as the tutorial does; eigenvalues
+    below zero (round-off of a positive semi-definite matrix) are clamped to zero.  Returns (B, D) with the
+    eigenvalues ascending; the columns of B are orthonormal eigenvectors, each defined up to sign (and up to a
+    rotation inside an eigenspace of repeated eigenvalues)."""
+    C = np.asarray(C, dtype=np.float64)
+    if C.ndim != 2 or C.shape[0] != C.shape[1]:
+        raise ValueError("C must be square")
+    lam, B = np.linalg.eigh((C + C.T) / 2.0)
+    return B, np.sqrt(np.maximum(lam, 0.0))
 
 
 def rel_errors(y, ref):

@@ -375,3 +375,56 @@ def test_cma_converges_on_quadratics(cond):
         w, V = np.linalg.eigh((st.C + st.C.T) / 2)         # the eigen refresh sits outside the hot path
         st.B, st.D = V, np.sqrt(np.maximum(w, 1e-30))
     assert float(np.sum(a * st.m ** 2)) < 1e-8 * f0
+
+
+# ------------------------------------------------------------------------------------------------
+# eigendecomposition of the covariance (tutorial Sec. B.2: C = B D^2 B^T)
+# ------------------------------------------------------------------------------------------------
+def test_refresh_basis_closed_form_2x2():
+    """[[a, b], [b, c]]: eigenvalues (a+c)/2 -+ sqrt(((a-c)/2)^2 + b^2), eigenvector angle atan2(2b, a-c)/2."""
+    a, b, c = 3.0, 0.8, 1.5
+    B, D = orc.cma_refresh_basis(np.array([[a, b], [b, c]]))
+    mid, rad = (a + c) / 2, math.hypot((a - c) / 2, b)
+    np.testing.assert_allclose(D ** 2, [mid - rad, mid + rad], rtol=1e-14)
+    phi = 0.5 * math.atan2(2 * b, a - c)                      # direction of the larger eigenvalue
+    big = B[:, 1] * np.sign(B[0, 1])
+    np.testing.assert_allclose(big, [math.cos(phi), math.sin(phi)], atol=1e-14)
+    assert abs(B[:, 0] @ B[:, 1]) < 1e-15
+
+
+def test_refresh_basis_diagonal_and_known_spectrum():
+    d2 = np.array([4.0, 0.25, 9.0, 1.0])
+    B, D = orc.cma_refresh_basis(np.diag(d2))
+    np.testing.assert_allclose(D, np.sqrt(np.sort(d2)), rtol=1e-15)
+    np.testing.assert_allclose(np.abs(B), np.eye(4)[:, np.argsort(d2)], atol=1e-15)        # a permutation of the axes
+    # a known orthogonal basis and spectrum are recovered: eigenvalues exactly, eigenvectors up to sign
+    n = 24
+    Q, d = wl.random_covariance_basis(n, 11)
+    Q, d = np.linalg.qr(Q.astype(np.float64))[0], d.astype(np.float64)     # orthonormal to fp64 round-off
+    C = (Q * d ** 2) @ Q.T
+    B, D = orc.cma_refresh_basis(C)
+    order = np.argsort(d)
+    np.testing.assert_allclose(D, d[order], rtol=1e-10)
+    np.testing.assert_allclose(np.abs(np.sum(B * Q[:, order], axis=0)), 1.0, atol=1e-8)
+    # the defining identities
+    np.testing.assert_allclose((B * D ** 2) @ B.T, (C + C.T) / 2, atol=1e-12)
+    np.testing.assert_allclose(B.T @ B, np.eye(n), atol=1e-12)
+    # an asymmetric round-off in C does not matter (it is symmetrised), a slightly negative eigenvalue is clamped
+    B2, D2 = orc.cma_refresh_basis(C + 1e-9 * np.triu(np.ones((n, n)), 1))
+    np.testing.assert_allclose(D2, D, rtol=1e-6)
+    _, D3 = orc.cma_refresh_basis(np.array([[1.0, 1.0 + 1e-12], [1.0 + 1e-12, 1.0]]))
+    assert D3[0] == 0.0 and abs(D3[1] ** 2 - 2.0) < 1e-9
+
+
+def test_refresh_basis_keeps_the_sampling_distribution():
+    """Sampling through the refreshed (B, D) draws from N(m, sigma^2 C): the covariance of B D z is C, and a state whose
+    C moved away from its old basis samples differently before and after the refresh."""
+    n = 6
+    g = np.random.default_rng(0)
+    M = g.standard_normal((n, n))
+    C = M @ M.T + 0.1 * np.eye(n)
+    B, D = orc.cma_refresh_basis(C)
+    T = B * D                                                 # y = T z
+    np.testing.assert_allclose(T @ T.T, C, atol=1e-12)
+    th, z = orc.sample_candidates(np.zeros(n), 1.0, B, D, [5])
+    np.testing.assert_allclose(th[0], T @ z[0], atol=1e-5)
