@@ -20,7 +20,9 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) int i32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-#ifdef EXP_TIMING
+// Phase stamps of wave 0 of every workgroup (shader-clock and 100 MHz counters), read back by a test harness: compiled in
+// only with -DESSA_DEBUG_STAMPS, never in the shipped library.
+#ifdef ESSA_DEBUG_STAMPS
 __device__ unsigned long long essa_dbg[8 * 1024];
 extern "C" void essa_dbg_read(unsigned long long* out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(essa_dbg), sizeof(essa_dbg)); }
 #define TSTAMP(i) if (lane == 0 && wave == 0 && blockIdx.x < 1024) { essa_dbg[blockIdx.x * 8 + (i)] = __builtin_amdgcn_s_memtime(); if ((i) == 1) essa_dbg[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_memrealtime(); if ((i) == 2) essa_dbg[blockIdx.x * 8 + 7] = __builtin_amdgcn_s_memrealtime(); }
@@ -628,10 +630,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     const int nw = wave & 3, kh = wave >> 2;
     const int l32 = lane & 31, h = lane >> 5;
     const int R = it.R, dout = it.d_out, dpad = it.d_in_pad, rp = it.rp;
-    int nk = dpad / KT;                                    // a multiple of PD
-#ifdef EXP_NK
-    nk = EXP_NK;
-#endif
+    const int nk = dpad / KT;                              // a multiple of PD
     const int nbw = min(nb0 + nw, it.n_blocks - 1);        // a wave past the last n-block repeats it; nothing of it is stored
     // weights are stored k-chunk major, [kc][n-block][1 KB]: at any moment the waves of the whole grid read one
     // contiguous stretch of memory, which spreads over all HBM channels
@@ -768,23 +767,13 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     i32x4 fA[2][LIMBS][MB], fB[2][LIMBS][MB];
     read_frags<LIMBS, MB>(fA, smem, 0, kh, l32, h);
     TSTAMP(1)
-#ifdef EXP_NOLDS
-#define EXP_LDS(...)
-#else
-#define EXP_LDS(...) __VA_ARGS__
-#endif
-#ifdef EXP_NOVMEM
-#define EXP_VMEM(...)
-#else
-#define EXP_VMEM(...) __VA_ARGS__
-#endif
 #define ESSA_STEP(W, XS, KTI, SI, FC, FN)                                                                        \
     {                                                                                                            \
         const int kt_ = (KTI);                                                                                   \
         _Pragma("unroll") for (int i_ = 0; i_ < NF; ++i_) {                                                      \
             acc[i_ / MB][i_ % MB] = __builtin_amdgcn_mfma_i32_32x32x32_i8(FC[0][i_ / MB][i_ % MB], (i32x4)W[0],  \
                                                                           acc[i_ / MB][i_ % MB], 0, 0, 0);       \
-            if (EARLY && i_ < XV) { EXP_LDS(store_x_vec<LIMBS, BM>(XS[i_], smem, ((SI) + 2) % NS, tid, i_);) }   \
+            if (EARLY && i_ < XV) store_x_vec<LIMBS, BM>(XS[i_], smem, ((SI) + 2) % NS, tid, i_);   \
             __builtin_amdgcn_sched_barrier(0);                                                                   \
         }                                                                                                        \
         __syncthreads();                                                                                         \
@@ -792,14 +781,14 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         _Pragma("unroll") for (int i_ = 0; i_ < NF; ++i_) {                                                      \
             acc[i_ / MB][i_ % MB] = __builtin_amdgcn_mfma_i32_32x32x32_i8(FC[1][i_ / MB][i_ % MB], (i32x4)W[1],  \
                                                                           acc[i_ / MB][i_ % MB], 0, 0, 0);       \
-            EXP_LDS(FN[0][i_ / MB][i_ % MB] = read_frag<LIMBS, BM>(smem, ((SI) + 1) % NS, 0, i_ / MB, i_ % MB, kh, l32, h);) \
-            EXP_LDS(FN[1][i_ / MB][i_ % MB] = read_frag<LIMBS, BM>(smem, ((SI) + 1) % NS, 1, i_ / MB, i_ % MB, kh, l32, h);) \
+            FN[0][i_ / MB][i_ % MB] = read_frag<LIMBS, BM>(smem, ((SI) + 1) % NS, 0, i_ / MB, i_ % MB, kh, l32, h); \
+            FN[1][i_ / MB][i_ % MB] = read_frag<LIMBS, BM>(smem, ((SI) + 1) % NS, 1, i_ / MB, i_ % MB, kh, l32, h); \
             __builtin_amdgcn_sched_barrier(0);                                                                   \
         }                                                                                                        \
-        if (!EARLY) { EXP_LDS(store_x<LIMBS, BM, XV>(XS, smem, (SI) % NS, tid);) }                               \
-        EXP_VMEM(fetch_w(W, min(kt_ + PD, nk - 1));)                                                             \
+        if (!EARLY) store_x<LIMBS, BM, XV>(XS, smem, (SI) % NS, tid);                               \
+        fetch_w(W, min(kt_ + PD, nk - 1));                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                       \
-        EXP_VMEM(load_x<LIMBS, BM, XV>(XS, xbase, xoff, min(kt_ + 4, nk - 1), tid);)                             \
+        load_x<LIMBS, BM, XV>(XS, xbase, xoff, min(kt_ + 4, nk - 1), tid);                             \
         __builtin_amdgcn_sched_barrier(0);                                                                       \
     }
     for (int kt0 = 0; kt0 < nk; kt0 += PD) {
@@ -1242,9 +1231,6 @@ hipError_t launch_gemm_mb(hipStream_t st, stream_args& a, int mb) {
 
 // rows per tile: the largest of 128/64/32 that still leaves every CU a tile
 int pick_mb(const stream_args& a) {
-#ifdef EXP_FORCE_MB
-    return EXP_FORCE_MB;
-#endif
     int maxR = 0;
     for (int g = 0; g < a.n_items; ++g) maxR = a.it[g].R > maxR ? a.it[g].R : maxR;
     for (int mb : {4, 2}) {
@@ -1258,9 +1244,6 @@ int pick_mb(const stream_args& a) {
 
 // the 128 x 256 tile pays off once it fills the chip a few times over
 bool takes_big(const stream_args& a) {
-#ifdef EXP_NO_BIG
-    return false;
-#endif
     long long tiles = 0;
     for (int g = 0; g < a.n_items; ++g)
         tiles += (long long)((a.it[g].R + BIG_BM - 1) / BIG_BM) * ((a.it[g].n_blocks + BIG_NB - 1) / BIG_NB);
