@@ -262,6 +262,21 @@ essa_status essa_reward_finish(essa_ctx* ctx, const float* rowpart, int64_t n_bl
 essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uint32_t* seeds, const float* rewards, int K,
                               int32_t* order_out);
 
+/* Eigendecomposition of the covariance on the device, C = B diag(D^2) B^T (decomposition step of the CMA-ES of
+ * Hansen's tutorial, Sec. B.2; the paper's Algorithm 1 samples candidates through this factorisation of the C it
+ * updates).  Replaces the state's (B, D): columns of B are orthonormal eigenvectors (order and signs unspecified),
+ * D the square roots of the eigenvalues (negative round-off clamped to zero).  C itself is left alone (it is read as
+ * (C + C^T) / 2).  One-sided block Jacobi in fp64; sweeps until the largest |a_i . a_j| / (|a_i| |a_j|) over all
+ * pairs of columns of C V met during a sweep is <= tol, at most max_sweeps (1..64) times.  The state keeps the basis of
+ * its last refresh in fp64 and the next refresh starts from it (a few sweeps when C has moved little); after
+ * essa_cma_set_basis or essa_cma_import the next refresh starts from the identity.  Off the per-generation
+ * path: the tutorial refreshes the basis every 1 / (10 n (c_1 + c_mu)) generations.  The call waits for the device
+ * after every sweep; it cannot be recorded into a graph.
+ *   sweeps_out, off_out   HOST, optional: sweeps done and the last measure
+ * ESSA_ERR_STATE if the measure is still above tol after max_sweeps (B, D then hold the last iterate). */
+essa_status essa_cma_refresh_basis(essa_ctx* ctx, essa_cma* cma, int max_sweeps, float tol, int* sweeps_out,
+                                   float* off_out);
+
 /* The ranking alone.  rewards DEVICE float [K] -> order DEVICE int32 [K]; 1 <= K <= 1024. */
 essa_status essa_rank_rewards(essa_ctx* ctx, const float* rewards, int K, int32_t* order);
 

@@ -402,7 +402,7 @@ extern "C" void essa_cma_destroy(essa_cma* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
     (void)hipDeviceSynchronize();
-    void* ptrs[] = {c->m, c->p_sigma, c->p_c, c->D, c->C, c->B, c->sc, c->weights};
+    void* ptrs[] = {c->m, c->p_sigma, c->p_c, c->D, c->C, c->B, c->sc, c->weights, c->eigV};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
     delete c;
@@ -438,6 +438,7 @@ extern "C" essa_status essa_cma_set_basis(essa_cma* c, const float* B_dev, const
     ESSA_HIP(hipSetDevice(c->device));
     ESSA_HIP(hipMemcpyAsync(c->B, B_dev, (size_t)c->n * c->n * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
     ESSA_HIP(hipMemcpyAsync(c->D, D_dev, (size_t)c->n * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
+    c->eigV_valid = false;
     return ESSA_OK;
 }
 
@@ -482,6 +483,7 @@ extern "C" essa_status essa_cma_import(essa_cma* c, const void* blob, size_t byt
     ESSA_HIP(hipMemcpy(c->C, src, n * n * sizeof(float), hipMemcpyHostToDevice));
     src += n * n * sizeof(float);
     ESSA_HIP(hipMemcpy(c->B, src, n * n * sizeof(float), hipMemcpyHostToDevice));
+    c->eigV_valid = false;
     return ESSA_OK;
 }
 
@@ -784,6 +786,29 @@ static essa_k::cma_consts make_consts(int n, int K, std::vector<float>& w) {
     w.resize(c.mu);
     for (int i = 0; i < c.mu; ++i) w[i] = (float)wd[i];
     return c;
+}
+
+extern "C" essa_status essa_cma_refresh_basis(essa_ctx* ctx, essa_cma* cma, int max_sweeps, float tol, int* sweeps_out, float* off_out) {
+    if (!ctx || !cma) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_refresh_basis: NULL argument");
+    if (cma->ctx != ctx) return essa_fail(ESSA_ERR_STATE, "essa_cma_refresh_basis: state belongs to another context");
+    if (ctx->capturing) return essa_fail(ESSA_ERR_STATE, "essa_cma_refresh_basis: waits for the device after every sweep and cannot be recorded");
+    if (max_sweeps < 1 || max_sweeps > 64 || !(tol >= 0.f)) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_refresh_basis: max_sweeps=%d tol=%g", max_sweeps, (double)tol);
+    ESSA_HIP(hipSetDevice(ctx->device));
+    ESSA_TRY(essa_ws_reserve(ctx, essa_k::eig_workspace_bytes(cma->n)));
+    if (!cma->eigV) {
+        hipError_t e = hipMalloc((void**)&cma->eigV, essa_k::eig_basis_bytes(cma->n));
+        if (e != hipSuccess) return essa_fail(ESSA_ERR_OOM, "fp64 basis of %zu bytes: %s", essa_k::eig_basis_bytes(cma->n), hipGetErrorString(e));
+        cma->eigV_valid = false;
+    }
+    int sweeps = 0;
+    float off = 0.f;
+    ESSA_HIP(essa_k::eig_refresh(ctx->stream, cma->C, cma->n, ctx->ws, cma->eigV, cma->eigV_valid ? 1 : 0, max_sweeps, tol, cma->B, cma->D,
+                                 &sweeps, &off));
+    cma->eigV_valid = true;
+    if (sweeps_out) *sweeps_out = sweeps;
+    if (off_out) *off_out = off;
+    if (off > tol) return essa_fail(ESSA_ERR_STATE, "essa_cma_refresh_basis: not converged after %d sweeps (largest relative off-diagonal %g > %g); B and D hold the last iterate", sweeps, (double)off, (double)tol);
+    return ESSA_OK;
 }
 
 extern "C" essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uint32_t* seeds, const float* rewards, int K,

@@ -88,6 +88,8 @@ struct essa_cma {
     essa_cma_scalars* sc = nullptr;
     float* weights = nullptr;  // device [mu] for weights_K
     int weights_K = 0;
+    double* eigV = nullptr;    // the basis of the last eigendecomposition in fp64 (allocated by the first refresh)
+    bool eigV_valid = false;   // false after the basis was set from outside: the next refresh starts from the identity
 };
 
 // ---- host-side setup helpers ----------------------------------------------------------------------
@@ -107,6 +109,13 @@ hipError_t skinny_gemm_nt(hipStream_t st, const float* S, int J, const float* B,
 hipError_t theta_to_sigma(hipStream_t st, int P, int r, int n_top, const float* sftA, const float* sftB,
                           const float* theta, int K, float* sA, float* sB);
 hipError_t rank_rewards(hipStream_t st, const float* F, int K, int32_t* order);
+// C (n x n, fp32, symmetric) -> B (eigenvectors in columns), D (square roots of the eigenvalues); ws: eig_workspace_bytes(n).
+// Synchronises the stream once per sweep (the convergence measure comes back to the host).
+// Vt: the basis in fp64 (eig_basis_bytes(n)), kept by the state from one refresh to the next; warm = it holds the last result.
+size_t eig_workspace_bytes(int n);
+size_t eig_basis_bytes(int n);
+hipError_t eig_refresh(hipStream_t st, const float* C, int n, void* ws, double* Vt, int warm, int max_sweeps, float tol, float* B, float* D,
+                       int* sweeps_done, float* off_final);
 
 struct cma_consts {
     int n, K, mu;

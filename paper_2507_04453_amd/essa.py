@@ -34,7 +34,7 @@ EXPORTED_SYMBOLS = [
     "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
     "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards",
     "essa_svdlora_forward_reward_group", "essa_reward_finish",
-    "essa_graph_begin", "essa_graph_end", "essa_graph_launch", "essa_graph_destroy",
+    "essa_graph_begin", "essa_graph_end", "essa_graph_launch", "essa_graph_destroy", "essa_cma_refresh_basis",
 ]
 
 
@@ -71,6 +71,7 @@ def _load():
         "essa_profile_enable": (i32, [vp, i32]),
         "essa_profile_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(i32)]),
         "essa_proj_create": (i32, [vp, C.POINTER(_ProjDesc), C.POINTER(vp)]),
+        "essa_cma_refresh_basis": (i32, [vp, vp, i32, f32, C.POINTER(i32), C.POINTER(f32)]),
         "essa_graph_begin": (i32, [vp]),
         "essa_graph_end": (i32, [vp, C.POINTER(vp)]),
         "essa_graph_launch": (i32, [vp]),
@@ -286,6 +287,12 @@ class CmaState:
         if tuple(B.shape) != (self.n, self.n) or tuple(D.shape) != (self.n,):
             raise ValueError("B [n,n], D [n]")
         _check(lib.essa_cma_set_basis(self._h, _dev(B, torch.float32, "B"), _dev(D, torch.float32, "D")))
+
+    def refresh_basis(self, ctx: "Context", max_sweeps: int = 30, tol: float = 1e-7):
+        """C -> (B, D) on the device; returns (sweeps, last off-diagonal measure)."""
+        sw, off = C.c_int(0), C.c_float(0)
+        _check(lib.essa_cma_refresh_basis(ctx._h, self._h, max_sweeps, tol, C.byref(sw), C.byref(off)))
+        return sw.value, off.value
 
     def export_blob(self) -> bytes:
         size = C.c_size_t(0)

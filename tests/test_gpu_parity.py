@@ -795,3 +795,96 @@ def test_recorded_generation_replays_bit_exact(essa):
         cma.close()
         side.synchronize()
         c2.close()
+
+
+@pytest.mark.parametrize("n", [2, 40, 64, 100, 257])
+def test_refresh_basis(essa, ctx, n):
+    """C -> (B, D) on the device against the oracle's eigendecomposition: eigenvalues, the defining identities, and the
+    eigenvectors themselves where the spectrum separates them (each is defined up to sign)."""
+    _say("refresh basis n=%d" % n)
+    Q, d = wl.random_covariance_basis(n, basis_id=500 + n)
+    g = np.random.default_rng(n)
+    Qd = np.linalg.qr(Q.astype(np.float64))[0]
+    C = ((Qd * d.astype(np.float64) ** 2) @ Qd.T).astype(np.float32)
+    C = ((C + C.T) / 2).astype(np.float32)
+    cma = essa.CmaState(ctx, n, 0.32, None)
+    z = np.zeros(n, np.float32)
+    cma.import_blob(essa.CmaState.pack_blob(n, 3, 0.5, z, z, z, np.ones(n, np.float32), C, np.eye(n, dtype=np.float32)))
+    sweeps, off = cma.refresh_basis(ctx)
+    _say("  %d sweeps, off %.2g" % (sweeps, off))
+    st = cma.export()
+    B, D = st["B"].astype(np.float64), st["D"].astype(np.float64)
+    assert np.array_equal(st["C"], C) and st["t"] == 3                      # nothing else of the state moves
+    Bref, Dref = orc.cma_refresh_basis(C)
+    order = np.argsort(D)
+    np.testing.assert_allclose(D[order], Dref, rtol=2e-6, atol=1e-7 * Dref.max())
+    C64 = C.astype(np.float64)
+    assert np.abs((B * D ** 2) @ B.T - C64).max() <= 2e-6 * np.abs(C64).max()
+    assert np.abs(B.T @ B - np.eye(n)).max() <= 2e-6
+    # eigenvectors, up to sign, where the neighbouring eigenvalues are at least 1 % away
+    lam = Dref ** 2
+    gap = np.minimum(np.diff(lam, prepend=-np.inf), np.diff(lam, append=np.inf)) / lam
+    sel = gap > 1e-2
+    dots = np.abs(np.sum(B[:, order] * Bref, axis=0))
+    assert sel.sum() >= 1 and np.all(dots[sel] >= 1 - 1e-4)
+    # sampling goes through the new basis: candidates follow the oracle's theta = m + sigma B (D z) with the device's B, D
+    seeds = [5, 6, 7]
+    theta = torch.empty(3, n, device="cuda")
+    essa.essa_sample_candidates(ctx, cma, seeds_dev(seeds), theta, None)
+    ref_theta, _ = orc.sample_candidates(np.zeros(n), np.float32(0.5), B, D, seeds)
+    e_max, e_rms = orc.rel_errors(theta.cpu().numpy(), ref_theta)
+    assert e_rms <= FP32_RMS and e_max <= FP32_MAX
+    # a second refresh starts from the basis just found: nothing left to rotate, the same decomposition
+    sweeps2, _ = cma.refresh_basis(ctx)
+    st2 = cma.export()
+    assert sweeps2 == 1
+    np.testing.assert_allclose(st2["D"], st["D"], rtol=1e-6)
+    assert np.abs(np.abs(np.sum(st2["B"].astype(np.float64) * B, axis=0)) - 1).max() <= 1e-5
+    # same input, same bits: a fresh state (cold start) repeats the first result exactly
+    cma3 = essa.CmaState(ctx, n, 0.32, None)
+    cma3.import_blob(essa.CmaState.pack_blob(n, 3, 0.5, z, z, z, np.ones(n, np.float32), C, np.eye(n, dtype=np.float32)))
+    cma3.refresh_basis(ctx)
+    st3 = cma3.export()
+    assert np.array_equal(st3["B"], st["B"]) and np.array_equal(st3["D"], st["D"])
+    cma3.close()
+    cma.close()
+
+
+def test_refresh_basis_closes_the_loop(essa, ctx):
+    """Generations of sampling and update with the basis refreshed every third one, device against oracle: every refresh
+    is a valid factorisation of both sides' C, the candidates agree generation after generation, and a refresh that
+    starts from the previous basis needs few sweeps."""
+    n, K = 48, 12
+    g = np.random.default_rng(9)
+    cma = essa.CmaState(ctx, n, 0.3, None)
+    st = orc.cma_state_init(n, np.float32(0.3))
+    seed, warm_sweeps = 1, []
+    for gen in range(12):
+        seeds = list(range(seed, seed + K))
+        seed += K
+        theta = torch.empty(K, n, device="cuda")
+        essa.essa_sample_candidates(ctx, cma, seeds_dev(seeds), theta, None)
+        ref_theta, _ = orc.sample_candidates(st.m, st.sigma, st.B, st.D, seeds)
+        e_max, e_rms = orc.rel_errors(theta.cpu().numpy(), ref_theta)
+        assert e_rms <= 2e-5 and e_max <= 2e-4, (gen, e_max, e_rms)
+        F = (-np.sum((ref_theta - 0.5) ** 2, axis=1)).astype(np.float32)          # a quadratic to climb, same rewards both sides
+        essa.essa_cmaes_update(ctx, cma, seeds_dev(seeds), to_dev(F), None)
+        st, _ = orc.cma_update(st, seeds, F)
+        if gen % 3 == 2:
+            sweeps, _ = cma.refresh_basis(ctx)
+            if gen > 2:
+                warm_sweeps.append(sweeps)
+            _, Dref = orc.cma_refresh_basis(st.C)
+            e = cma.export()
+            B, D = e["B"].astype(np.float64), e["D"].astype(np.float64)
+            assert np.abs((B * D ** 2) @ B.T - e["C"]).max() <= 5e-6 * np.abs(e["C"]).max()
+            assert np.abs((B * D ** 2) @ B.T - st.C).max() <= 1e-4 * np.abs(st.C).max()          # ... and of the oracle's C
+            np.testing.assert_allclose(np.sort(D), Dref, rtol=1e-4)
+            # B D z depends on the signs and the order of the eigenvectors, which the decomposition leaves open: from here
+            # on the oracle samples through the device's factorisation (just checked to be one of its own C)
+            st.B, st.D = B, D
+    _say("  warm refreshes took %s sweeps" % warm_sweeps)
+    errs = _state_errors(cma.export(), st)
+    for name in ("m", "C"):
+        assert errs[name][1] <= 1e-4, (name, errs[name])
+    cma.close()
