@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--rows-per-cand", type=int, default=0)
     ap.add_argument("--forward-only", action="store_true", help="time only the projections (no sampler / reward / update)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--refresh-basis", action="store_true",
+                    help="time essa_cma_refresh_basis (C -> B, D) on the workload's search dimension instead of the step: cold, unchanged C, and after 17 generations of update")
     ap.add_argument("--no-graph", action="store_true", help="issue every launch of a step from the host instead of replaying the recorded step")
     ap.add_argument("--two-pass-reward", action="store_true", help="reward as a second pass over Y instead of in the GEMM's epilogue")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy (a reference for HBM byte counters)")
@@ -143,6 +145,24 @@ def main():
         forward_all(True)
         essa.essa_cmaes_update(ctx, cma, seeds, F, None)
 
+    if args.refresh_basis:
+        # off the per-generation path: the eigendecomposition of the covariance, timed on its own
+        def refresh():
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            sweeps, off = cma.refresh_basis(ctx)
+            torch.cuda.synchronize()
+            return {"sweeps": sweeps, "off": off, "ms": 1e3 * (time.perf_counter() - t0)}
+        cma.import_blob(essa.CmaState.pack_blob(n, 0, 0.32, zero, zero, zero, np.ones(n, np.float32), C0, np.eye(n, dtype=np.float32)))
+        out = {"metric": "essa_cma_refresh_basis", "n": n, "cold": refresh(), "unchanged": refresh()}
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(0)
+        for g in range(17):
+            sd = torch.arange(1 + g * K, 1 + (g + 1) * K, dtype=torch.int32, device="cuda")
+            essa.essa_cmaes_update(ctx, cma, sd, torch.randn(K, device="cuda", generator=gen), None)
+        out["after_17_generations"] = refresh()
+        print(json.dumps(out))
+        return
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, device="cuda")
         dst = torch.empty_like(src)
