@@ -199,6 +199,16 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     const int din = it.d_in, rp = it.rp, nbv = rp / 16, R = it.R;
     f32x16 acc0 = {0}, acc1 = {0};
     const int ksteps = din / 16;
+    // the candidate's singular values for the (row, j) element this thread finishes at the end: fetched now (a chain of
+    // two dependent loads) so that they are there when the sums are
+    const int rsh = rp == 16 ? 4 : 5;                       // rp is 16 or 32
+    const int my_row = tid >> rsh, my_j = tid & (rp - 1);   // tid < 32 * rp takes part
+    float my_sa = 0.f, my_sb = 0.f;
+    if (tid < 32 * rp && my_j < it.r) {
+        const int c = it.row2cand[min(r0 + my_row, R - 1)];
+        my_sa = it.sigmaA[(size_t)c * it.sigma_stride + my_j];
+        if (slice == 0) my_sb = it.sigmaB[(size_t)c * it.sigma_stride + my_j];
+    }
     if (!(a.flags & ESSA_BASE_ONLY)) {
         // wave w takes the four consecutive steps slice*64 + 4w + u, i.e. 64 columns = 128 bytes of each of the 32 rows.
         // x: four coalesced loads (instruction i: rows 8i..8i+7, whole 128-byte lines), turned into operand order
@@ -242,37 +252,29 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     }
     __syncthreads();          // the staging patches become the reduction buffer
     PSTAMP(1)
-    // 16 partial tiles -> 8 -> 1, always in the same order
+    // 16 partial tiles -> 8 -> 1, always in the same order (the second column block exists for rank 32 only)
     if (wave >= 8) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             part[wave - 8][0][q][lane] = acc0[q];
-            part[wave - 8][1][q][lane] = acc1[q];
+            if (nbv == 2) part[wave - 8][1][q][lane] = acc1[q];
         }
     }
     __syncthreads();
     if (wave < 8) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
-            acc0[q] += part[wave][0][q][lane];
-            acc1[q] += part[wave][1][q][lane];
-        }
-    }
-    __syncthreads();
-    if (wave < 8) {
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            part[wave][0][q][lane] = acc0[q];
-            part[wave][1][q][lane] = acc1[q];
+            part[wave][0][q][lane] += acc0[q];
+            if (nbv == 2) part[wave][1][q][lane] += acc1[q];
         }
     }
     __syncthreads();
     PSTAMP(2)
     // element (row, j): head and tail columns of V_A's column j meet here, and the candidate's sigma_A scales the
-    // slice's share of t_j = <V_A[:, j], x>; the slice-0 workgroup also gathers the row's sigma_B
+    // slice's share of t_j = <V_A[:, j], x>; the slice-0 workgroup also passes on the row's sigma_B
     const int rpad = (R + 31) / 32 * 32;
-    for (int idx = tid; idx < 32 * rp; idx += PREP_NT) {
-        const int row = idx / rp, j = idx % rp;
+    if (tid < 32 * rp) {
+        const int row = my_row, j = my_j;
         const int q = 4 * (row >> 3) + (row & 3), lnr = 32 * ((row >> 2) & 1);
         float th[2];
 #pragma unroll
@@ -281,10 +283,8 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
             th[e] = ((part[0][nb][q][ln] + part[1][nb][q][ln]) + (part[2][nb][q][ln] + part[3][nb][q][ln])) +
                     ((part[4][nb][q][ln] + part[5][nb][q][ln]) + (part[6][nb][q][ln] + part[7][nb][q][ln]));
         }
-        const int c = it.row2cand[min(r0 + row, R - 1)];
-        const float sa = j < it.r ? it.sigmaA[(size_t)c * it.sigma_stride + j] : 0.f;
-        it.Tpart[((size_t)slice * rpad + r0 + row) * rp + j] = sa * (th[0] + th[1]);
-        if (slice == 0 && r0 + row < R) it.SBrow[(size_t)(r0 + row) * rp + j] = j < it.r ? it.sigmaB[(size_t)c * it.sigma_stride + j] : 0.f;
+        it.Tpart[((size_t)slice * rpad + r0 + row) * rp + j] = my_sa * (th[0] + th[1]);
+        if (slice == 0 && r0 + row < R) it.SBrow[(size_t)(r0 + row) * rp + j] = my_sb;
     }
     PSTAMP(3)
 }
