@@ -752,16 +752,18 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     store_x<LIMBS, BM, XV>(xa, smem, 0, tid);
     store_x<LIMBS, BM, XV>(xb, smem, 1, tid);
     QSTAMP(5)
-    // the last loads before the loop, in the order the loop's own steps issue them: the compiler sizes the loop's
-    // waits for the tighter of the two ways into it
-    __builtin_amdgcn_sched_barrier(0);
-    fetch_w(w2, 2);
+    // the last loads before the loop, in the order the loop's own steps issue them (the compiler sizes the loop's
+    // waits for the tighter of the two ways into it): activations before weights, so that waiting for an activation
+    // tile (needed two steps after its load) never waits for the weight tile loaded in the same step (needed four
+    // steps later) -- loads complete in order
     __builtin_amdgcn_sched_barrier(0);
     load_x<LIMBS, BM, XV>(xa, xbase, xoff, min(2, nk - 1), tid);
     __builtin_amdgcn_sched_barrier(0);
-    fetch_w(w3, 3);
+    fetch_w(w2, 2);
     __builtin_amdgcn_sched_barrier(0);
     load_x<LIMBS, BM, XV>(xb, xbase, xoff, min(3, nk - 1), tid);
+    __builtin_amdgcn_sched_barrier(0);
+    fetch_w(w3, 3);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     i32x4 fA[2][LIMBS][MB], fB[2][LIMBS][MB];
@@ -786,9 +788,9 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
             __builtin_amdgcn_sched_barrier(0);                                                                   \
         }                                                                                                        \
         if (!EARLY) store_x<LIMBS, BM, XV>(XS, smem, (SI) % NS, tid);                               \
-        fetch_w(W, min(kt_ + PD, nk - 1));                                                             \
-        __builtin_amdgcn_sched_barrier(0);                                                                       \
         load_x<LIMBS, BM, XV>(XS, xbase, xoff, min(kt_ + 4, nk - 1), tid);                             \
+        __builtin_amdgcn_sched_barrier(0);                                                                       \
+        fetch_w(W, min(kt_ + PD, nk - 1));                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                       \
     }
     for (int kt0 = 0; kt0 < nk; kt0 += PD) {
