@@ -1231,7 +1231,7 @@ hipError_t launch_gemm_mb(hipStream_t st, stream_args& a, int mb) {
     }
 }
 
-// rows per tile: the largest of 128/64/32 that still leaves every CU a tile
+// rows per tile: the largest of 128/64 that still leaves every CU a tile, else 32
 int pick_mb(const stream_args& a) {
     int maxR = 0;
     for (int g = 0; g < a.n_items; ++g) maxR = a.it[g].R > maxR ? a.it[g].R : maxR;
@@ -1241,7 +1241,7 @@ int pick_mb(const stream_args& a) {
         for (int g = 0; g < a.n_items; ++g) tiles += (long long)((a.it[g].R + 32 * mb - 1) / (32 * mb)) * ((a.it[g].n_blocks + 3) / 4);
         if (tiles >= 256) return mb;
     }
-    return maxR <= 32 ? 1 : 2;
+    return 1;     // fewer tiles than CUs either way: the 32-row tile gives twice as many workgroups and loads less per K tile
 }
 
 // the 128 x 256 tile pays off once it fills the chip a few times over
