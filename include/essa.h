@@ -125,6 +125,41 @@ essa_status essa_proj_spectrum(const essa_proj* proj, float* sA_host, float* sB_
  * ------------------------------------------------------------------------------------------- */
 essa_status essa_cma_create(essa_ctx* ctx, int n, float sigma0, const float* m0_host /* [n] or NULL = 0 */,
                             essa_cma** out);
+/* The other rank-based optimisers that run on the same seed sampler (paper: Experiments, "Alternative
+ * gradient-free optimizers": plain isotropic (mu, lambda)-ES and ARS on the same search space and evaluation
+ * budget; the paper names them and leaves the CMA-ES variant to a library's defaults, so each kind follows
+ * its own publication).  essa_sample_candidates and essa_cmaes_update act according to the state's kind:
+ *   ESSA_OPT_CMA         what essa_cma_create makes: (mu/mu_w, lambda)-CMA-ES, positive weights.
+ *   ESSA_OPT_ACTIVE_CMA  the same with the negative weights of Hansen's tutorial (Table 1, Eqs. 46-58) in the
+ *                        rank-mu term: all K candidates enter C, a negative one with w n / |z|^2.
+ *   ESSA_OPT_SEP_CMA     Ros & Hansen 2008: only the diagonal of C exists (O(n) state, no B), both covariance
+ *                        learning rates times (n + 2) / 3; theta = m + sigma sqrt(diag C) z, and the update
+ *                        refreshes sqrt(diag C) itself, so the loop closes without an eigendecomposition.
+ *   ESSA_OPT_ES          plain isotropic (mu/mu_I, lambda)-ES: theta = m + sigma z, the new mean is the average
+ *                        of the floor(K / 2) best candidates, sigma stays at sigma0.
+ *   ESSA_OPT_ARS         Mania, Guy & Recht 2018, Algorithm 1 (V1-t): K is even, seeds holds K / 2 words,
+ *                        candidates 2j and 2j + 1 are m + sigma z_j and m - sigma z_j; the update keeps the
+ *                        ars_top directions with the largest max(r+, r-) (ties: lower index; NaN = -inf) and
+ *                        moves m by ars_alpha / (ars_top s_R) sum (r+ - r-) z, s_R the standard deviation
+ *                        (divisor 2 ars_top) of the rewards used; s_R = 0 or a non-finite reward among them
+ *                        leaves m alone.  order_out then holds the K / 2 directions, best first.
+ * The last three kinds keep no n x n state: essa_cma_set_basis and essa_cma_refresh_basis refuse them with
+ * ESSA_ERR_STATE, and their blob is header (reserved = kind) + float m[n], p_sigma[n], p_c[n], D[n], diagC[n]. */
+typedef enum {
+    ESSA_OPT_CMA = 0,
+    ESSA_OPT_ACTIVE_CMA = 1,
+    ESSA_OPT_SEP_CMA = 2,
+    ESSA_OPT_ES = 3,
+    ESSA_OPT_ARS = 4
+} essa_optimizer;
+typedef struct essa_opt_desc {
+    int kind;         /* essa_optimizer */
+    float ars_alpha;  /* ESSA_OPT_ARS: step size, > 0 */
+    int ars_top;      /* ESSA_OPT_ARS: directions kept, >= 1; an update with fewer than that many pairs fails */
+} essa_opt_desc;
+essa_status essa_cma_create_opt(essa_ctx* ctx, int n, float sigma0, const float* m0_host, const essa_opt_desc* opt,
+                                essa_cma** out);
+int essa_cma_kind(const essa_cma* cma); /* essa_optimizer, or -1 for NULL */
 void essa_cma_destroy(essa_cma* cma);
 /* B: DEVICE float [n, n] (column j = j-th axis), D: DEVICE float [n].  Copied. */
 essa_status essa_cma_set_basis(essa_cma* cma, const float* B_dev, const float* D_dev);
@@ -145,7 +180,9 @@ essa_status essa_cma_import(essa_cma* cma, const void* blob_host, size_t bytes);
  *   seeds      DEVICE uint32 [K]
  *   theta_out  DEVICE float [K, n]
  *   z_out      DEVICE float [K, n] or NULL
- * The same seed gives the same bits on every call.  K >= 1.
+ * The same seed gives the same bits on every call.  K >= 1.  States of another kind (essa_cma_create_opt)
+ * sample their own distribution; z_out holds the N(0, I) vector each candidate was built from (ESSA_OPT_ARS:
+ * with the candidate's sign, and seeds is [K / 2]).
  * ------------------------------------------------------------------------------------------- */
 essa_status essa_sample_candidates(essa_ctx* ctx, const essa_cma* cma, const uint32_t* seeds, int K,
                                    float* theta_out, float* z_out);
@@ -257,7 +294,7 @@ essa_status essa_reward_finish(essa_ctx* ctx, const float* rowpart, int64_t n_bl
  * m, p_sigma, p_c, C, sigma and t in place on the device; (B, D) are left alone.  The result is
  * bit-identical from run to run (fixed reduction order, no atomics).
  *   seeds    DEVICE uint32 [K]     rewards  DEVICE float [K]     order_out  DEVICE int32 [K] or NULL
- * K >= 2.
+ * K >= 2.  States of another kind (essa_cma_create_opt) run their own update from the same two arrays.
  * ------------------------------------------------------------------------------------------- */
 essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uint32_t* seeds, const float* rewards, int K,
                               int32_t* order_out);

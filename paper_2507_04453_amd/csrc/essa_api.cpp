@@ -402,39 +402,62 @@ extern "C" void essa_cma_destroy(essa_cma* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
     (void)hipDeviceSynchronize();
-    void* ptrs[] = {c->m, c->p_sigma, c->p_c, c->D, c->C, c->B, c->sc, c->weights, c->eigV};
+    void* ptrs[] = {c->m, c->p_sigma, c->p_c, c->D, c->C, c->B, c->Cdiag, c->sc, c->weights, c->eigV};
     for (void* q : ptrs)
         if (q) (void)hipFree(q);
     delete c;
 }
 
-extern "C" essa_status essa_cma_create(essa_ctx* ctx, int n, float sigma0, const float* m0_host, essa_cma** out) {
+static bool has_matrix(const essa_cma* c) { return c->kind == ESSA_OPT_CMA || c->kind == ESSA_OPT_ACTIVE_CMA; }
+
+extern "C" essa_status essa_cma_create_opt(essa_ctx* ctx, int n, float sigma0, const float* m0_host, const essa_opt_desc* opt,
+                                           essa_cma** out) {
     if (!ctx || !out) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_create: NULL argument");
     *out = nullptr;
-    if (n < 1 || n > 16384) return essa_fail(ESSA_ERR_SHAPE, "essa_cma_create: n=%d not in [1, 16384]", n);
+    const int kind = opt ? opt->kind : (int)ESSA_OPT_CMA;
+    if (kind < ESSA_OPT_CMA || kind > ESSA_OPT_ARS) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_create: unknown optimiser kind %d", kind);
+    if (n < 1 || n > (kind >= ESSA_OPT_SEP_CMA ? (1 << 24) : 16384))
+        return essa_fail(ESSA_ERR_SHAPE, "essa_cma_create: n=%d not in [1, %d]", n, kind >= ESSA_OPT_SEP_CMA ? (1 << 24) : 16384);
     if (!(sigma0 > 0.f) || !std::isfinite(sigma0)) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_create: sigma0 must be positive and finite");
+    if (kind == ESSA_OPT_ARS && (!(opt->ars_alpha > 0.f) || !std::isfinite(opt->ars_alpha) || opt->ars_top < 1 || opt->ars_top > 1024))
+        return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_create: ARS needs ars_alpha > 0 and 1 <= ars_top <= 1024 (got %g, %d)",
+                         (double)opt->ars_alpha, opt->ars_top);
     ESSA_HIP(hipSetDevice(ctx->device));
     std::unique_ptr<essa_cma, void (*)(essa_cma*)> c(new essa_cma(), essa_cma_destroy);
     c->ctx = ctx;
     c->device = ctx->device;
     c->stream = ctx->stream;
     c->n = n;
-    std::vector<float> zeros((size_t)n, 0.f), ones((size_t)n, 1.f), eye((size_t)n * n, 0.f);
-    for (int i = 0; i < n; ++i) eye[(size_t)i * n + i] = 1.f;
+    c->kind = kind;
+    if (kind == ESSA_OPT_ARS) { c->ars_alpha = opt->ars_alpha; c->ars_top = opt->ars_top; }
+    std::vector<float> zeros((size_t)n, 0.f), ones((size_t)n, 1.f);
     ESSA_TRY(upload(&c->m, m0_host ? m0_host : zeros.data(), (size_t)n));
     ESSA_TRY(upload(&c->p_sigma, zeros.data(), (size_t)n));
     ESSA_TRY(upload(&c->p_c, zeros.data(), (size_t)n));
     ESSA_TRY(upload(&c->D, ones.data(), (size_t)n));
-    ESSA_TRY(upload(&c->C, eye.data(), eye.size()));
-    ESSA_TRY(upload(&c->B, eye.data(), eye.size()));
+    if (has_matrix(c.get())) {
+        std::vector<float> eye((size_t)n * n, 0.f);
+        for (int i = 0; i < n; ++i) eye[(size_t)i * n + i] = 1.f;
+        ESSA_TRY(upload(&c->C, eye.data(), eye.size()));
+        ESSA_TRY(upload(&c->B, eye.data(), eye.size()));
+    } else {
+        ESSA_TRY(upload(&c->Cdiag, ones.data(), (size_t)n));
+    }
     essa_cma_scalars sc{sigma0, 0, 1.f, 0.f};
     ESSA_TRY(upload(&c->sc, &sc, 1));
     *out = c.release();
     return ESSA_OK;
 }
 
+extern "C" essa_status essa_cma_create(essa_ctx* ctx, int n, float sigma0, const float* m0_host, essa_cma** out) {
+    return essa_cma_create_opt(ctx, n, sigma0, m0_host, nullptr, out);
+}
+
+extern "C" int essa_cma_kind(const essa_cma* c) { return c ? c->kind : -1; }
+
 extern "C" essa_status essa_cma_set_basis(essa_cma* c, const float* B_dev, const float* D_dev) {
     if (!c || !B_dev || !D_dev) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_set_basis: NULL argument");
+    if (!has_matrix(c)) return essa_fail(ESSA_ERR_STATE, "essa_cma_set_basis: an optimiser of kind %d keeps no basis", c->kind);
     ESSA_HIP(hipSetDevice(c->device));
     ESSA_HIP(hipMemcpyAsync(c->B, B_dev, (size_t)c->n * c->n * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
     ESSA_HIP(hipMemcpyAsync(c->D, D_dev, (size_t)c->n * sizeof(float), hipMemcpyDeviceToDevice, c->stream));
@@ -442,35 +465,45 @@ extern "C" essa_status essa_cma_set_basis(essa_cma* c, const float* B_dev, const
     return ESSA_OK;
 }
 
+static size_t blob_bytes(const essa_cma* c) {
+    const size_t n = c->n;
+    return sizeof(cma_blob_header) + (has_matrix(c) ? 4 * n + 2 * n * n : 5 * n) * sizeof(float);
+}
+
 extern "C" essa_status essa_cma_export(const essa_cma* c, void* blob, size_t* bytes) {
     if (!c || !bytes) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_export: NULL argument");
-    const size_t n = c->n, need = sizeof(cma_blob_header) + (4 * n + 2 * n * n) * sizeof(float);
+    const size_t n = c->n, need = blob_bytes(c);
     if (!blob) { *bytes = need; return ESSA_OK; }
     if (*bytes < need) { *bytes = need; return essa_fail(ESSA_ERR_SHAPE, "essa_cma_export: blob too small, need %zu bytes", need); }
     ESSA_HIP(hipSetDevice(c->device));
     ESSA_HIP(hipStreamSynchronize(c->stream));
     essa_cma_scalars sc;
     ESSA_HIP(hipMemcpy(&sc, c->sc, sizeof sc, hipMemcpyDeviceToHost));
-    cma_blob_header h{kCmaMagic, 1u, (int32_t)n, sc.t, sc.sigma, 0u};
+    cma_blob_header h{kCmaMagic, 1u, (int32_t)n, sc.t, sc.sigma, (uint32_t)c->kind};
     char* dst = (char*)blob;
     std::memcpy(dst, &h, sizeof h);
     dst += sizeof h;
     const float* vecs[] = {c->m, c->p_sigma, c->p_c, c->D};
     for (const float* v : vecs) { ESSA_HIP(hipMemcpy(dst, v, n * sizeof(float), hipMemcpyDeviceToHost)); dst += n * sizeof(float); }
-    ESSA_HIP(hipMemcpy(dst, c->C, n * n * sizeof(float), hipMemcpyDeviceToHost));
-    dst += n * n * sizeof(float);
-    ESSA_HIP(hipMemcpy(dst, c->B, n * n * sizeof(float), hipMemcpyDeviceToHost));
+    if (has_matrix(c)) {
+        ESSA_HIP(hipMemcpy(dst, c->C, n * n * sizeof(float), hipMemcpyDeviceToHost));
+        dst += n * n * sizeof(float);
+        ESSA_HIP(hipMemcpy(dst, c->B, n * n * sizeof(float), hipMemcpyDeviceToHost));
+    } else {
+        ESSA_HIP(hipMemcpy(dst, c->Cdiag, n * sizeof(float), hipMemcpyDeviceToHost));
+    }
     *bytes = need;
     return ESSA_OK;
 }
 
 extern "C" essa_status essa_cma_import(essa_cma* c, const void* blob, size_t bytes) {
     if (!c || !blob) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_import: NULL argument");
-    const size_t n = c->n, need = sizeof(cma_blob_header) + (4 * n + 2 * n * n) * sizeof(float);
+    const size_t n = c->n, need = blob_bytes(c);
     if (bytes < sizeof(cma_blob_header)) return essa_fail(ESSA_ERR_SHAPE, "essa_cma_import: blob shorter than its header");
     cma_blob_header h;
     std::memcpy(&h, blob, sizeof h);
     if (h.magic != kCmaMagic || h.version != 1u) return essa_fail(ESSA_ERR_STATE, "essa_cma_import: not a state blob of this library");
+    if (h.reserved != (uint32_t)c->kind) return essa_fail(ESSA_ERR_STATE, "essa_cma_import: blob of optimiser kind %u, object of kind %d", h.reserved, c->kind);
     if ((size_t)h.n != n || bytes != need) return essa_fail(ESSA_ERR_STATE, "essa_cma_import: blob holds n=%d (%zu bytes), object has n=%zu (%zu bytes)", h.n, bytes, n, need);
     if (!(h.sigma > 0.f) || h.t < 0) return essa_fail(ESSA_ERR_STATE, "essa_cma_import: sigma=%g t=%d", h.sigma, h.t);
     ESSA_HIP(hipSetDevice(c->device));
@@ -480,9 +513,13 @@ extern "C" essa_status essa_cma_import(essa_cma* c, const void* blob, size_t byt
     const char* src = (const char*)blob + sizeof h;
     float* vecs[] = {c->m, c->p_sigma, c->p_c, c->D};
     for (float* v : vecs) { ESSA_HIP(hipMemcpy(v, src, n * sizeof(float), hipMemcpyHostToDevice)); src += n * sizeof(float); }
-    ESSA_HIP(hipMemcpy(c->C, src, n * n * sizeof(float), hipMemcpyHostToDevice));
-    src += n * n * sizeof(float);
-    ESSA_HIP(hipMemcpy(c->B, src, n * n * sizeof(float), hipMemcpyHostToDevice));
+    if (has_matrix(c)) {
+        ESSA_HIP(hipMemcpy(c->C, src, n * n * sizeof(float), hipMemcpyHostToDevice));
+        src += n * n * sizeof(float);
+        ESSA_HIP(hipMemcpy(c->B, src, n * n * sizeof(float), hipMemcpyHostToDevice));
+    } else {
+        ESSA_HIP(hipMemcpy(c->Cdiag, src, n * sizeof(float), hipMemcpyHostToDevice));
+    }
     c->eigV_valid = false;
     return ESSA_OK;
 }
@@ -507,6 +544,13 @@ extern "C" essa_status essa_sample_candidates(essa_ctx* ctx, const essa_cma* cma
     if (cma->ctx != ctx) return essa_fail(ESSA_ERR_STATE, "essa_sample_candidates: state belongs to another context");
     ESSA_HIP(hipSetDevice(ctx->device));
     const int n = cma->n;
+    if (!has_matrix(cma)) {
+        const int pairs = cma->kind == ESSA_OPT_ARS;
+        if (pairs && (K & 1)) return essa_fail(ESSA_ERR_SHAPE, "essa_sample_candidates: ARS draws candidates in pairs, K=%d is odd", K);
+        ESSA_HIP(essa_k::sample_diag(ctx->stream, seeds, K, n, cma->m, cma->kind == ESSA_OPT_SEP_CMA ? cma->D : nullptr, cma->sc, pairs,
+                                     theta_out, z_out));
+        return ESSA_OK;
+    }
     ESSA_TRY(essa_ws_reserve(ctx, align256((size_t)K * n * sizeof(float))));
     float* S = (float*)ctx->ws;
     ESSA_HIP(essa_k::normals_scaled(ctx->stream, seeds, nullptr, K, n, cma->D, S, z_out));
@@ -766,31 +810,51 @@ extern "C" essa_status essa_rank_rewards(essa_ctx* ctx, const float* rewards, in
     return ESSA_OK;
 }
 
-static essa_k::cma_consts make_consts(int n, int K, std::vector<float>& w) {
-    // default strategy parameters, evaluated in fp64 on the host
+static essa_k::cma_consts make_consts(int n, int K, int kind, std::vector<float>& w) {
+    // default strategy parameters of Hansen's tutorial, evaluated in fp64 on the host
     essa_k::cma_consts c{};
     c.n = n; c.K = K; c.mu = K / 2;
-    std::vector<double> wd(c.mu);
+    std::vector<double> wd(K);
     double sum = 0, sum2 = 0;
-    for (int i = 0; i < c.mu; ++i) { wd[i] = std::log((K + 1) / 2.0) - std::log(i + 1.0); sum += wd[i]; }
+    for (int i = 0; i < K; ++i) wd[i] = std::log((K + 1) / 2.0) - std::log(i + 1.0);
+    for (int i = 0; i < c.mu; ++i) sum += wd[i];
     for (int i = 0; i < c.mu; ++i) { wd[i] /= sum; sum2 += wd[i] * wd[i]; }
     const double mu_eff = 1.0 / sum2, nn = n;
     const double c_sigma = (mu_eff + 2.0) / (nn + mu_eff + 5.0);
     const double d_sigma = 1.0 + 2.0 * std::fmax(0.0, std::sqrt((mu_eff - 1.0) / (nn + 1.0)) - 1.0) + c_sigma;
     const double c_c = (4.0 + mu_eff / nn) / (nn + 4.0 + 2.0 * mu_eff / nn);
-    const double c_1 = 2.0 / ((nn + 1.3) * (nn + 1.3) + mu_eff);
-    const double c_mu = std::fmin(1.0 - c_1, 2.0 * (mu_eff - 2.0 + 1.0 / mu_eff) / ((nn + 2.0) * (nn + 2.0) + mu_eff));
+    double c_1 = 2.0 / ((nn + 1.3) * (nn + 1.3) + mu_eff);
+    double c_mu = std::fmin(1.0 - c_1, 2.0 * (mu_eff - 2.0 + 1.0 / mu_eff) / ((nn + 2.0) * (nn + 2.0) + mu_eff));
     const double chi_n = std::sqrt(nn) * (1.0 - 1.0 / (4.0 * nn) + 1.0 / (21.0 * nn * nn));
+    c.ny = c.mu;
+    double w_sum = 1.0;
+    if (kind == ESSA_OPT_ACTIVE_CMA) {
+        // tutorial, Eqs. (50)-(53), (58): the rank-mu rate with its extra 1/4, negative weights scaled to the smallest of three bounds
+        c_mu = std::fmin(1.0 - c_1, 2.0 * (0.25 + mu_eff + 1.0 / mu_eff - 2.0) / ((nn + 2.0) * (nn + 2.0) + mu_eff));
+        double nsum = 0, nsum2 = 0;
+        for (int i = c.mu; i < K; ++i) { nsum += wd[i]; nsum2 += wd[i] * wd[i]; }
+        const double mu_eff_neg = nsum2 > 0 ? nsum * nsum / nsum2 : 0.0;
+        const double a_mu = 1.0 + c_1 / c_mu, a_mueff = 1.0 + 2.0 * mu_eff_neg / (mu_eff + 2.0), a_pd = (1.0 - c_1 - c_mu) / (nn * c_mu);
+        const double a = std::fmin(a_mu, std::fmin(a_mueff, a_pd));
+        for (int i = c.mu; i < K; ++i) { wd[i] = nsum < 0 ? a * wd[i] / -nsum : 0.0; w_sum += wd[i]; }
+        c.ny = K;
+    } else if (kind == ESSA_OPT_SEP_CMA) {
+        // Ros & Hansen 2008: both learning rates of the (now diagonal) covariance times (n + 2) / 3
+        const double f = (nn + 2.0) / 3.0;
+        c_1 = std::fmin(1.0, c_1 * f);
+        c_mu = std::fmin(1.0 - c_1, c_mu * f);
+    }
     c.mu_eff = (float)mu_eff; c.c_sigma = (float)c_sigma; c.d_sigma = (float)d_sigma; c.c_c = (float)c_c;
-    c.c_1 = (float)c_1; c.c_mu = (float)c_mu; c.chi_n = (float)chi_n;
-    w.resize(c.mu);
-    for (int i = 0; i < c.mu; ++i) w[i] = (float)wd[i];
+    c.c_1 = (float)c_1; c.c_mu = (float)c_mu; c.chi_n = (float)chi_n; c.w_sum = (float)w_sum;
+    w.resize(c.ny);
+    for (int i = 0; i < c.ny; ++i) w[i] = (float)wd[i];
     return c;
 }
 
 extern "C" essa_status essa_cma_refresh_basis(essa_ctx* ctx, essa_cma* cma, int max_sweeps, float tol, int* sweeps_out, float* off_out) {
     if (!ctx || !cma) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_refresh_basis: NULL argument");
     if (cma->ctx != ctx) return essa_fail(ESSA_ERR_STATE, "essa_cma_refresh_basis: state belongs to another context");
+    if (!has_matrix(cma)) return essa_fail(ESSA_ERR_STATE, "essa_cma_refresh_basis: an optimiser of kind %d keeps no covariance matrix", cma->kind);
     if (ctx->capturing) return essa_fail(ESSA_ERR_STATE, "essa_cma_refresh_basis: waits for the device after every sweep and cannot be recorded");
     if (max_sweeps < 1 || max_sweeps > 64 || !(tol >= 0.f)) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_cma_refresh_basis: max_sweeps=%d tol=%g", max_sweeps, (double)tol);
     ESSA_HIP(hipSetDevice(ctx->device));
@@ -818,8 +882,39 @@ extern "C" essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uin
     if (K < 2 || K > 1024) return essa_fail(ESSA_ERR_SHAPE, "essa_cmaes_update: K=%d not in [2, 1024]", K);
     ESSA_HIP(hipSetDevice(ctx->device));
     const int n = cma->n;
+
+    if (cma->kind == ESSA_OPT_ARS) {
+        // Mania, Guy & Recht 2018, Algorithm 1: scratch order[N] | coef[b] | Z[b, n]
+        const int N = K / 2, b = cma->ars_top;
+        if (K & 1) return essa_fail(ESSA_ERR_SHAPE, "essa_cmaes_update: ARS evaluates candidates in pairs, K=%d is odd", K);
+        if (b > N) return essa_fail(ESSA_ERR_SHAPE, "essa_cmaes_update: ARS keeps %d directions, only %d were evaluated", b, N);
+        const size_t off_coef = align256((size_t)N * 4), off_Z = off_coef + align256((size_t)b * 4);
+        ESSA_TRY(essa_ws_reserve(ctx, off_Z + align256((size_t)b * n * 4)));
+        int32_t* order = (int32_t*)ctx->ws;
+        float* coef = (float*)((char*)ctx->ws + off_coef);
+        float* Z = (float*)((char*)ctx->ws + off_Z);
+        ESSA_HIP(essa_k::ars_prepare(ctx->stream, rewards, N, b, cma->ars_alpha, order, coef));
+        if (order_out) ESSA_HIP(hipMemcpyAsync(order_out, order, (size_t)N * 4, hipMemcpyDeviceToDevice, ctx->stream));
+        ESSA_HIP(essa_k::normals_scaled(ctx->stream, seeds, order, b, n, nullptr, Z, nullptr));
+        ESSA_HIP(essa_k::mean_step(ctx->stream, Z, coef, 0.0, b, n, cma->sc, 0, cma->m));
+        return ESSA_OK;
+    }
+    if (cma->kind == ESSA_OPT_ES) {
+        // plain (mu/mu_I, lambda)-ES: scratch order[K] | Z[mu, n]
+        const int mu = K / 2;
+        const size_t off_Z = align256((size_t)K * 4);
+        ESSA_TRY(essa_ws_reserve(ctx, off_Z + align256((size_t)mu * n * 4)));
+        int32_t* order = (int32_t*)ctx->ws;
+        float* Z = (float*)((char*)ctx->ws + off_Z);
+        ESSA_HIP(essa_k::rank_rewards(ctx->stream, rewards, K, order));
+        if (order_out) ESSA_HIP(hipMemcpyAsync(order_out, order, (size_t)K * 4, hipMemcpyDeviceToDevice, ctx->stream));
+        ESSA_HIP(essa_k::normals_scaled(ctx->stream, seeds, order, mu, n, nullptr, Z, nullptr));
+        ESSA_HIP(essa_k::mean_step(ctx->stream, Z, nullptr, 1.0 / mu, mu, n, cma->sc, 1, cma->m));
+        return ESSA_OK;
+    }
+
     std::vector<float> w;
-    essa_k::cma_consts c = make_consts(n, K, w);
+    essa_k::cma_consts c = make_consts(n, K, cma->kind, w);
     if (cma->weights_K != K) {
         if (ctx->capturing)
             return essa_fail(ESSA_ERR_STATE, "essa_cmaes_update: the weights for K=%d are not on the device yet: run the update once before essa_graph_begin", K);
@@ -830,20 +925,28 @@ extern "C" essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uin
         ESSA_TRY(upload(&cma->weights, w.data(), w.size()));
         cma->weights_K = K;
     }
-    // scratch: order[K] | S[(mu+2), n] | BY[(mu+2), n] | Z[mu, n];  S rows: D*z_i (i < mu), z_w, D*z_w
-    const size_t rows = (size_t)c.mu + 2;
-    const size_t off_S = align256((size_t)K * 4), off_BY = off_S + align256(rows * n * 4);
+    // scratch: order[K] | zn2[ny] | S[(ny+2), n] | BY[(ny+2), n] | Z[ny, n];  S rows: D*z_i (i < ny), z_w, D*z_w
+    const size_t rows = (size_t)c.ny + 2;
+    const size_t off_zn = align256((size_t)K * 4), off_S = off_zn + align256((size_t)c.ny * 4), off_BY = off_S + align256(rows * n * 4);
     const size_t off_Z = off_BY + align256(rows * n * 4);
     ESSA_TRY(essa_ws_reserve(ctx, off_Z + align256(rows * n * 4)));
     int32_t* order = (int32_t*)ctx->ws;
+    float* zn2 = (float*)((char*)ctx->ws + off_zn);
     float* S = (float*)((char*)ctx->ws + off_S);
     float* BY = (float*)((char*)ctx->ws + off_BY);
     float* Z = (float*)((char*)ctx->ws + off_Z);
     ESSA_HIP(essa_k::rank_rewards(ctx->stream, rewards, K, order));
     if (order_out) ESSA_HIP(hipMemcpyAsync(order_out, order, (size_t)K * 4, hipMemcpyDeviceToDevice, ctx->stream));
     ESSA_HIP(essa_k::cma_build_rhs(ctx->stream, seeds, order, cma->weights, c, cma->D, S, Z));
+    if (cma->kind == ESSA_OPT_SEP_CMA) {
+        // B = I: the rows of S are the y_i, z_w and y_w themselves
+        ESSA_HIP(essa_k::cma_vectors(ctx->stream, c, cma->weights, S, cma->m, cma->p_sigma, cma->p_c, cma->sc));
+        ESSA_HIP(essa_k::sep_covariance(ctx->stream, c, cma->weights, S, cma->p_c, cma->sc, cma->Cdiag, cma->D));
+        return ESSA_OK;
+    }
+    if (cma->kind == ESSA_OPT_ACTIVE_CMA) ESSA_HIP(essa_k::row_norms2(ctx->stream, Z, c.ny, n, zn2));
     ESSA_HIP(essa_k::skinny_gemm_nt(ctx->stream, S, (int)rows, cma->B, n, nullptr, nullptr, 0, BY));
     ESSA_HIP(essa_k::cma_vectors(ctx->stream, c, cma->weights, BY, cma->m, cma->p_sigma, cma->p_c, cma->sc));
-    ESSA_HIP(essa_k::cma_covariance(ctx->stream, c, cma->weights, BY, cma->p_c, cma->sc, cma->C));
+    ESSA_HIP(essa_k::cma_covariance(ctx->stream, c, cma->weights, BY, cma->p_c, cma->sc, cma->kind == ESSA_OPT_ACTIVE_CMA ? zn2 : nullptr, cma->C));
     return ESSA_OK;
 }

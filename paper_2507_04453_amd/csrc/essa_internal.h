@@ -84,9 +84,13 @@ struct essa_cma {
     int device = 0;
     hipStream_t stream = nullptr;
     int n = 0;
+    int kind = 0;              // essa_optimizer; kinds >= ESSA_OPT_SEP_CMA have no C and no B
+    float ars_alpha = 0.f;
+    int ars_top = 0;
     float *m = nullptr, *p_sigma = nullptr, *p_c = nullptr, *D = nullptr, *C = nullptr, *B = nullptr;
+    float* Cdiag = nullptr;    // [n] diagonal of C (kinds without a matrix)
     essa_cma_scalars* sc = nullptr;
-    float* weights = nullptr;  // device [mu] for weights_K
+    float* weights = nullptr;  // device [mu] (active CMA: [K]) for weights_K
     int weights_K = 0;
     double* eigV = nullptr;    // the basis of the last eigendecomposition in fp64 (allocated by the first refresh)
     bool eigV_valid = false;   // false after the basis was set from outside: the next refresh starts from the identity
@@ -102,7 +106,10 @@ namespace essa_k {
 hipError_t philox_words(hipStream_t st, const uint32_t* seeds, int K, int n_blocks, uint32_t* out);
 // S[k, :] = D * z_k (z optionally stored too)
 hipError_t normals_scaled(hipStream_t st, const uint32_t* seeds, const int32_t* sel /*null or [J]*/, int J, int n,
-                          const float* D, float* S, float* z_out);
+                          const float* D /*null = 1*/, float* S, float* z_out);
+// theta[k, l] = m[l] + s_k sigma (D ? D[l] : 1) z[l];  pairs: candidate k uses seeds[k / 2] and s_k = +1, -1, else seeds[k], +1
+hipError_t sample_diag(hipStream_t st, const uint32_t* seeds, int K, int n, const float* m, const float* D,
+                       const essa_cma_scalars* sc, int pairs, float* theta, float* z_out);
 // Out[j, i] = bias[i] + scale * sum_l S[j,l] B[i,l]; scale = use_sigma ? sc->sigma : 1; bias may be null
 hipError_t skinny_gemm_nt(hipStream_t st, const float* S, int J, const float* B, int n, const float* bias,
                           const essa_cma_scalars* sc, int use_sigma, float* Out);
@@ -119,15 +126,28 @@ hipError_t eig_refresh(hipStream_t st, const float* C, int n, void* ws, double* 
 
 struct cma_consts {
     int n, K, mu;
+    int ny;                    // rows of y in BY: mu, or K when the worse half enters the covariance with negative weights
     float mu_eff, c_sigma, d_sigma, c_c, c_1, c_mu, chi_n;
+    float w_sum;               // sum of the ny weights (1 without negative weights)
 };
-// S rows 0..mu-1 = D*z_sel, row mu = z_w (weights applied); needs order
+// S rows 0..ny-1 = D*z_sel, row ny = z_w (the mu positive weights applied), row ny+1 = D*z_w; needs order
 hipError_t cma_build_rhs(hipStream_t st, const uint32_t* seeds, const int32_t* order, const float* w,
-                         const cma_consts& c, const float* D, float* S, float* Z /*[mu,n] scratch*/);
-hipError_t cma_vectors(hipStream_t st, const cma_consts& c, const float* w, const float* BY /*[mu+1,n]*/,
+                         const cma_consts& c, const float* D, float* S, float* Z /*[ny,n] scratch*/);
+hipError_t cma_vectors(hipStream_t st, const cma_consts& c, const float* w, const float* BY /*[ny+2,n]*/,
                        float* m, float* p_sigma, float* p_c, essa_cma_scalars* sc);
+// zn2: [ny] squared lengths of the sorted z (read for negative weights only), or null
 hipError_t cma_covariance(hipStream_t st, const cma_consts& c, const float* w, const float* BY, const float* p_c,
-                          const essa_cma_scalars* sc, float* C);
+                          const essa_cma_scalars* sc, const float* zn2, float* C);
+// out[j] = |Z[j, :]|^2, fp64 sum in a fixed order
+hipError_t row_norms2(hipStream_t st, const float* Z, int J, int n, float* out);
+// diagonal covariance: Cd <- decay Cd + c_1 p_c^2 + c_mu sum_i w_i y_i^2, D <- sqrt(Cd)   (Y rows 0..mu-1)
+hipError_t sep_covariance(hipStream_t st, const cma_consts& c, const float* w, const float* Y, const float* p_c,
+                          const essa_cma_scalars* sc, float* Cd, float* D);
+// m[l] += scale * sum_j coef_j Z[j, l] (fp64 sum, j ascending); coef null = uniform; scale = use_sigma ? sigma : 1; then t += 1
+hipError_t mean_step(hipStream_t st, const float* Z, const float* coef, double uniform, int J, int n, essa_cma_scalars* sc,
+                     int use_sigma, float* m);
+// ARS: ranks the N directions by max(r+, r-), order[N] best first, coef[b] = alpha (r+ - r-) / (b s_R) or zeros
+hipError_t ars_prepare(hipStream_t st, const float* rewards, int N, int b, float alpha, int32_t* order, float* coef);
 
 struct fwd_item {              // one projection of a grouped forward, device pointers only
     const void* X;

@@ -57,8 +57,35 @@ __global__ void normals_scaled_kernel(const uint32_t* __restrict__ seeds, const 
     for (int e = 0; e < 4; ++e) {
         const int l = 4 * c + e;
         if (l < n) {
-            S[(size_t)j * n + l] = D[l] * z[e];
+            S[(size_t)j * n + l] = D ? D[l] * z[e] : z[e];
             if (z_out) z_out[(size_t)j * n + l] = z[e];
+        }
+    }
+}
+
+// Distributions with a diagonal covariance: theta[k, l] = m[l] + s_k sigma d[l] z[l] (d = 1 without D).  With
+// pairs, candidates 2j and 2j + 1 mirror each other around m on the direction of seed j (ARS, Algorithm 1).
+__global__ void sample_diag_kernel(const uint32_t* __restrict__ seeds, int K, int n, const float* __restrict__ m,
+                                   const float* __restrict__ D, const essa_cma_scalars* __restrict__ sc, int pairs,
+                                   float* __restrict__ theta, float* __restrict__ z_out) {
+    const int nb = (n + 3) / 4;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)K * nb) return;
+    const int k = (int)(idx / nb), c = (int)(idx % nb);
+    const uint32_t seed = pairs ? seeds[k >> 1] : seeds[k];
+    const float sgn = (pairs && (k & 1)) ? -1.0f : 1.0f;
+    const uint4 w = philox4x32_10(make_uint4((uint32_t)c, 0u, 0u, 0u), make_uint2(seed, 0u));
+    float z[4];
+    box_muller(w.x, w.y, z[0], z[1]);
+    box_muller(w.z, w.w, z[2], z[3]);
+    const float sigma = sc->sigma;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int l = 4 * c + e;
+        if (l < n) {
+            const float zs = sgn * z[e];
+            theta[(size_t)k * n + l] = m[l] + (D ? sigma * D[l] : sigma) * zs;
+            if (z_out) z_out[(size_t)k * n + l] = zs;
         }
     }
 }
@@ -161,6 +188,14 @@ hipError_t normals_scaled(hipStream_t st, const uint32_t* seeds, const int32_t* 
                           float* z_out) {
     const long long total = (long long)J * ((n + 3) / 4);
     hipLaunchKernelGGL(normals_scaled_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, seeds, sel, J, n, D, S, z_out);
+    return hipGetLastError();
+}
+
+hipError_t sample_diag(hipStream_t st, const uint32_t* seeds, int K, int n, const float* m, const float* D,
+                       const essa_cma_scalars* sc, int pairs, float* theta, float* z_out) {
+    const long long total = (long long)K * ((n + 3) / 4);
+    hipLaunchKernelGGL(sample_diag_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, seeds, K, n, m, D, sc, pairs, theta,
+                       z_out);
     return hipGetLastError();
 }
 

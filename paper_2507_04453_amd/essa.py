@@ -15,6 +15,7 @@ __all__ = [
     "essa_theta_to_sigma", "essa_svdlora_forward", "essa_svdlora_forward_group", "essa_w8a8_accumulators",
     "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards", "essa_version", "EXPORTED_SYMBOLS",
     "ForwardGroup", "REWARD_BLOCK", "essa_svdlora_forward_reward_group", "essa_reward_finish",
+    "essa_cma_create_opt", "OPT_CMA", "OPT_ACTIVE_CMA", "OPT_SEP_CMA", "OPT_ES", "OPT_ARS",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libessa.so")
@@ -24,6 +25,7 @@ QUANT_INT8_PERCH, QUANT_INT4_G128 = 0, 1
 COMPUTE_W8A8, LORA_ONLY, BASE_ONLY, COMPUTE_BF16 = 1, 2, 4, 8
 MAX_GROUP = 8
 REWARD_BLOCK = 128
+OPT_CMA, OPT_ACTIVE_CMA, OPT_SEP_CMA, OPT_ES, OPT_ARS = 0, 1, 2, 3, 4
 
 EXPORTED_SYMBOLS = [
     "essa_create", "essa_destroy", "essa_last_error", "essa_version", "essa_synchronize",
@@ -35,6 +37,7 @@ EXPORTED_SYMBOLS = [
     "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards",
     "essa_svdlora_forward_reward_group", "essa_reward_finish",
     "essa_graph_begin", "essa_graph_end", "essa_graph_launch", "essa_graph_destroy", "essa_cma_refresh_basis",
+    "essa_cma_create_opt", "essa_cma_kind",
 ]
 
 
@@ -48,6 +51,10 @@ class _ProjDesc(C.Structure):
     _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("r", C.c_int32), ("quant", C.c_int32),
                 ("Wq", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p),
                 ("lora_A", C.c_void_p), ("lora_B", C.c_void_p)]
+
+
+class _OptDesc(C.Structure):
+    _fields_ = [("kind", C.c_int), ("ars_alpha", C.c_float), ("ars_top", C.c_int)]
 
 
 class _FwdItem(C.Structure):
@@ -79,6 +86,8 @@ def _load():
         "essa_proj_destroy": (None, [vp]),
         "essa_proj_spectrum": (i32, [vp, vp, vp]),
         "essa_cma_create": (i32, [vp, i32, f32, vp, C.POINTER(vp)]),
+        "essa_cma_create_opt": (i32, [vp, i32, f32, vp, C.POINTER(_OptDesc), C.POINTER(vp)]),
+        "essa_cma_kind": (i32, [vp]),
         "essa_cma_destroy": (None, [vp]),
         "essa_cma_set_basis": (i32, [vp, vp, vp]),
         "essa_cma_export": (i32, [vp, vp, C.POINTER(C.c_size_t)]),
@@ -272,8 +281,8 @@ _BLOB_HEADER = np.dtype([("magic", "<u4"), ("version", "<u4"), ("n", "<i4"), ("t
 class CmaState:
     """essa_cma: the search distribution on the device."""
 
-    def __init__(self, ctx: Context, n: int, sigma0: float, m0=None):
-        self.ctx, self.n = ctx, n
+    def __init__(self, ctx: Context, n: int, sigma0: float, m0=None, kind: int = OPT_CMA, ars_alpha: float = 0.0, ars_top: int = 0):
+        self.ctx, self.n, self.kind = ctx, n, kind
         self._h = C.c_void_p()
         if m0 is not None:
             m0, mp = _host(m0, np.float32)
@@ -281,7 +290,11 @@ class CmaState:
                 raise ValueError("m0 must be [n]")
         else:
             mp = None
-        _check(lib.essa_cma_create(ctx._h, n, C.c_float(sigma0), mp, C.byref(self._h)))
+        if kind == OPT_CMA:
+            _check(lib.essa_cma_create(ctx._h, n, C.c_float(sigma0), mp, C.byref(self._h)))
+        else:
+            desc = _OptDesc(kind, ars_alpha, ars_top)
+            _check(lib.essa_cma_create_opt(ctx._h, n, C.c_float(sigma0), mp, C.byref(desc), C.byref(self._h)))
 
     def set_basis(self, B: torch.Tensor, D: torch.Tensor):
         if tuple(B.shape) != (self.n, self.n) or tuple(D.shape) != (self.n,):
@@ -306,26 +319,31 @@ class CmaState:
         _check(lib.essa_cma_import(self._h, C.cast(buf, C.c_void_p), len(blob)))
 
     def export(self) -> dict:
-        """The blob parsed into numpy arrays (t, sigma, m, p_sigma, p_c, D, C, B)."""
+        """The blob parsed into numpy arrays (t, sigma, m, p_sigma, p_c, D, then C, B or, for kinds without a matrix, c_diag)."""
         blob = self.export_blob()
         h = np.frombuffer(blob, _BLOB_HEADER, 1)[0]
         n = int(h["n"])
         body = np.frombuffer(blob, np.float32, offset=_BLOB_HEADER.itemsize)
-        out = dict(n=n, t=int(h["t"]), sigma=float(h["sigma"]))
+        out = dict(n=n, t=int(h["t"]), sigma=float(h["sigma"]), kind=int(h["reserved"]))
         off = 0
         for name in ("m", "p_sigma", "p_c", "D"):
             out[name] = body[off:off + n].copy()
             off += n
-        out["C"] = body[off:off + n * n].reshape(n, n).copy()
-        off += n * n
-        out["B"] = body[off:off + n * n].reshape(n, n).copy()
+        if out["kind"] in (OPT_CMA, OPT_ACTIVE_CMA):
+            out["C"] = body[off:off + n * n].reshape(n, n).copy()
+            off += n * n
+            out["B"] = body[off:off + n * n].reshape(n, n).copy()
+        else:
+            out["c_diag"] = body[off:off + n].copy()
         return out
 
     @staticmethod
-    def pack_blob(n, t, sigma, m, p_sigma, p_c, D, Cm, B) -> bytes:
+    def pack_blob(n, t, sigma, m, p_sigma, p_c, D, Cm, B=None, kind: int = OPT_CMA) -> bytes:
+        """Cm: the covariance matrix [n, n] followed by B, or (kinds without a matrix, B = None) its diagonal [n]."""
         h = np.zeros(1, _BLOB_HEADER)
-        h["magic"], h["version"], h["n"], h["t"], h["sigma"] = 0x41535345, 1, n, t, sigma
-        parts = [h.tobytes()] + [np.ascontiguousarray(a, np.float32).tobytes() for a in (m, p_sigma, p_c, D, Cm, B)]
+        h["magic"], h["version"], h["n"], h["t"], h["sigma"], h["reserved"] = 0x41535345, 1, n, t, sigma, kind
+        arrays = (m, p_sigma, p_c, D, Cm) if B is None else (m, p_sigma, p_c, D, Cm, B)
+        parts = [h.tobytes()] + [np.ascontiguousarray(a, np.float32).tobytes() for a in arrays]
         return b"".join(parts)
 
     def close(self):
@@ -344,8 +362,12 @@ def essa_cma_create(ctx, n, sigma0, m0=None) -> CmaState:
     return CmaState(ctx, n, sigma0, m0)
 
 
+def essa_cma_create_opt(ctx, n, sigma0, m0=None, kind: int = OPT_CMA, ars_alpha: float = 0.0, ars_top: int = 0) -> CmaState:
+    return CmaState(ctx, n, sigma0, m0, kind, ars_alpha, ars_top)
+
+
 def essa_sample_candidates(ctx: Context, cma: CmaState, seeds: torch.Tensor, theta_out: torch.Tensor, z_out: torch.Tensor | None = None):
-    K = seeds.numel()
+    K = seeds.numel() * (2 if cma.kind == OPT_ARS else 1)
     if tuple(theta_out.shape) != (K, cma.n) or (z_out is not None and tuple(z_out.shape) != (K, cma.n)):
         raise ValueError("theta_out / z_out must be [K, n]")
     _check(lib.essa_sample_candidates(ctx._h, cma._h, _dev(seeds, torch.int32, "seeds"), K, _dev(theta_out, torch.float32, "theta_out"),
@@ -496,9 +518,10 @@ def essa_reward_accumulate_group(ctx: Context, Ys, vs, row2cand: torch.Tensor, F
 
 
 def essa_cmaes_update(ctx: Context, cma: CmaState, seeds: torch.Tensor, rewards: torch.Tensor, order_out: torch.Tensor | None = None):
-    K = seeds.numel()
-    if rewards.numel() != K or (order_out is not None and order_out.numel() != K):
-        raise ValueError("seeds, rewards, order_out must all hold K entries")
+    K = rewards.numel()
+    per_seed = 2 if cma.kind == OPT_ARS else 1
+    if seeds.numel() * per_seed != K or (order_out is not None and order_out.numel() != seeds.numel()):
+        raise ValueError("seeds and order_out must hold one entry per candidate (ARS: per pair of candidates)")
     _check(lib.essa_cmaes_update(ctx._h, cma._h, _dev(seeds, torch.int32, "seeds"), _dev(rewards, torch.float32, "rewards"), K,
                                  _dev(order_out, torch.int32, "order_out")))
 

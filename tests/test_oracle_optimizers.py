@@ -49,12 +49,17 @@ def test_active_weights_make_the_decay_vanish(n, lam):
 
 
 def test_active_weights_small_n_take_the_positive_definite_bound():
-    # n = 2, lambda = 64: (1 - c_1 - c_mu) / (n c_mu) is the smallest of the three bounds, and with it the
-    # worst case of the update (every ||C^-1/2 y||^2 rescaled to n) leaves a non-negative factor in front of C
-    c = orc.active_cma_constants(2, 64)
+    # n = 2, lambda = 12: (1 - c_1 - c_mu) / (n c_mu) is the smallest of the three bounds, and with it the worst
+    # case of the update (every ||C^-1/2 y||^2 rescaled to n) leaves a non-negative factor in front of C
+    c = orc.active_cma_constants(2, 12)
     neg = -c.weights[c.mu:].sum()
+    assert neg > 0.5
     assert neg == pytest.approx((1.0 - c.c_1 - c.c_mu) / (2 * c.c_mu), rel=1e-12)
     assert neg < 1.0 + c.c_1 / c.c_mu
+    assert 1.0 - c.c_1 - c.c_mu - c.c_mu * 2 * neg >= -1e-15
+    # lambda = 64 in two dimensions: c_1 + c_mu = 1 already, nothing is left for negative weights
+    c = orc.active_cma_constants(2, 64)
+    assert c.c_1 + c.c_mu == pytest.approx(1.0, abs=1e-15) and np.all(c.weights[c.mu:] == 0.0)
 
 
 @pytest.mark.parametrize("lam", [4, 9, 32])
@@ -111,7 +116,7 @@ def test_active_update_is_stationary_under_random_selection():
 
 
 def test_active_update_keeps_the_covariance_positive_definite():
-    n, lam = 2, 64
+    n, lam = 2, 12
     rng = np.random.default_rng(5)
     st = _state(n, rng)
     for g in range(200):
