@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--refresh-basis", action="store_true",
                     help="time essa_cma_refresh_basis (C -> B, D) on the workload's search dimension instead of the step: cold, unchanged C, and after 17 generations of update")
+    ap.add_argument("--optimizer", choices=["cma", "active", "sep", "es", "ars"], default="cma",
+                    help="what samples the candidates and consumes the rewards: the (mu/mu_w, lambda)-CMA-ES of the headline (cma), the same with "
+                         "negative weights (active), separable CMA-ES (sep), plain isotropic (mu, lambda)-ES (es) or ARS on K/2 antithetic pairs (ars)")
     ap.add_argument("--no-graph", action="store_true", help="issue every launch of a step from the host instead of replaying the recorded step")
     ap.add_argument("--two-pass-reward", action="store_true", help="reward as a second pass over Y instead of in the GEMM's epilogue")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain 256 MiB device copy (a reference for HBM byte counters)")
@@ -100,12 +103,19 @@ def main():
     r2c = torch.from_numpy(wl.row2cand_interleaved(K, rows_per) if cfg.interleaved else wl.row2cand_contiguous(K, rows_per)).cuda()
     Q, d = wl.random_covariance_basis(n, 0)
     d = (d * 0.05).astype(np.float32)           # offsets of the order of 1% of a singular value
-    cma = essa.CmaState(ctx, n, 0.32, None)
-    C0 = ((Q.astype(np.float64) * d.astype(np.float64) ** 2) @ Q.astype(np.float64).T).astype(np.float32)
     zero = np.zeros(n, np.float32)
-    blob0 = essa.CmaState.pack_blob(n, 0, 0.32, zero, zero, zero, d, C0, Q)
-    cma.import_blob(blob0)
-    seeds = torch.arange(1, K + 1, dtype=torch.int32, device="cuda")
+    kind = {"cma": essa.OPT_CMA, "active": essa.OPT_ACTIVE_CMA, "sep": essa.OPT_SEP_CMA, "es": essa.OPT_ES, "ars": essa.OPT_ARS}[args.optimizer]
+    if kind in (essa.OPT_CMA, essa.OPT_ACTIVE_CMA):
+        cma = essa.CmaState(ctx, n, 0.32, None, kind=kind)
+        C0 = ((Q.astype(np.float64) * d.astype(np.float64) ** 2) @ Q.astype(np.float64).T).astype(np.float32)
+        blob0 = essa.CmaState.pack_blob(n, 0, 0.32, zero, zero, zero, d, C0, Q, kind=kind)
+        cma.import_blob(blob0)
+    elif kind == essa.OPT_SEP_CMA:
+        cma = essa.CmaState(ctx, n, 0.32, None, kind=kind)
+        cma.import_blob(essa.CmaState.pack_blob(n, 0, 0.32, zero, zero, zero, d, (d.astype(np.float64) ** 2).astype(np.float32), kind=kind))
+    else:       # isotropic: the same overall scale of the offsets in one step size
+        cma = essa.CmaState(ctx, n, 0.32 * 0.05, None, kind=kind, ars_alpha=0.01, ars_top=K // 4)
+    seeds = torch.arange(1, (K // 2 if kind == essa.OPT_ARS else K) + 1, dtype=torch.int32, device="cuda")
     theta = torch.empty(K, n, device="cuda")
     sA = torch.empty(K, P, r, device="cuda")
     sB = torch.empty(K, P, r, device="cuda")
@@ -145,6 +155,8 @@ def main():
         forward_all(True)
         essa.essa_cmaes_update(ctx, cma, seeds, F, None)
 
+    if args.refresh_basis and kind != essa.OPT_CMA:
+        raise SystemExit("bench.py --refresh-basis times the eigendecomposition of the default optimizer's covariance")
     if args.refresh_basis:
         # off the per-generation path: the eigendecomposition of the covariance, timed on its own
         def refresh():
@@ -262,7 +274,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if args.mode == "w8a16" else "int8", "data": "synthetic",
         "config": {"workload": args.workload, "layers": layers, "hidden": hidden, "kv": kv, "rank": r, "population": K,
                    "rows": R, "weights": "int8 per-channel" if cfg.quant == "int8" else "int4 g128 asymmetric", "activations": "bf16",
-                   "mode": args.mode,
+                   "mode": args.mode, "optimizer": args.optimizer,
                    "step": "forward only" if args.forward_only else "sample + sigma + %d layers x (q,k,v,o) + reward + update" % layers},
         "roofline": roof, "cpu_baseline": cpu, "breakdown_ms": breakdown,
         "ms_per_step_with_events": 1e3 * elapsed_profiled / args.steps,
