@@ -77,6 +77,15 @@ __device__ __forceinline__ fwd_item fetch_item(const fwd_item& src) {
     return it;
 }
 
+// N consecutive words of the kernel arguments in one batch of scalar loads.
+template <int N>
+__device__ __forceinline__ void fetch_words(const int* p, int (&out)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) out[i] = p[i];
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+s"(out[i]));
+}
+
 // ------------------------------------------------------------------------------------------------
 // prep kernel (1024 threads): two kinds of workgroups in one launch.
 //  (a) quantise four activation rows into limbs, one row per 256 threads (once per distinct X of the group);
@@ -91,16 +100,35 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     __shared__ float wred[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
-    const int n_qblocks = a.quant_start[a.n_items];
-    if (b < n_qblocks) {
+    // Two dependent fetches from the kernel arguments stand between the start of the kernel and its first load from
+    // memory, each a batch of scalar loads: both work tables (entries past the last item repeat the totals), then the
+    // descriptor of the item they point to.
+    constexpr int NG = ESSA_MAX_GROUP + 1;
+    static_assert(offsetof(stream_args, lora_start) == offsetof(stream_args, quant_start) + NG * sizeof(int) &&
+                  offsetof(stream_args, flags) == offsetof(stream_args, quant_start) + (2 * NG + 1) * sizeof(int) &&
+                  offsetof(stream_args, limbs) == offsetof(stream_args, flags) + sizeof(int), "tables and scalars are adjacent");
+    int tab[2 * NG + 3];
+    fetch_words(a.quant_start, tab);
+    const unsigned a_flags = (unsigned)tab[2 * NG + 1];
+    const int a_limbs = tab[2 * NG + 2];
+    const int n_qblocks = tab[NG - 1];
+    const bool quant_role = b < n_qblocks;
+    const int lb = b - n_qblocks;
+    int g = 0, first = 0;
+#pragma unroll
+    for (int i = 1; i < ESSA_MAX_GROUP; ++i) {
+        const int start = quant_role ? tab[i] : tab[NG + i];
+        const bool past = (quant_role ? b : lb) >= start;
+        g += past ? 1 : 0;
+        first = past ? start : first;
+    }
+    const fwd_item it = fetch_item(a.it[g]);
+    if (quant_role) {
         const int role_ = 1; (void)role_;
         PSTAMP(0) PSTAMP(7)
         // ---- (a) row quantisation: this 256-thread group takes row 4*b' + grp of its item ---------------
-        int g = 0;
-        while (b >= a.quant_start[g + 1]) ++g;
-        const fwd_item& it = a.it[g];
         const int grp = tid >> 8, t256 = tid & 255;
-        const int i = (b - a.quant_start[g]) * 4 + grp;
+        const int i = (b - first) * 4 + grp;
         const bool live = i < it.R;
         const int din = it.d_in, dpad = it.d_in_pad;
         const u32x4* xrow = reinterpret_cast<const u32x4*>((const uint16_t*)it.X + (size_t)(live ? i : 0) * din);
@@ -132,7 +160,7 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         if (lane == 0) wred[wave] = m;
         __syncthreads();
         const float amax = fmaxf(fmaxf(wred[4 * grp], wred[4 * grp + 1]), fmaxf(wred[4 * grp + 2], wred[4 * grp + 3]));
-        const float top = a.limbs == 2 ? 16383.0f : 127.0f;
+        const float top = a_limbs == 2 ? 16383.0f : 127.0f;
         const float inv = amax > 0.f ? top / amax : 0.f;
         PSTAMP(1)
         if (!live) return;
@@ -148,7 +176,7 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
                 q = fminf(fmaxf(q, -top), top);
                 const int qi = (int)q;
                 qsum += qi;
-                if (a.limbs == 2) {
+                if (a_limbs == 2) {
                     hi[e >> 2] |= (uint32_t)((qi >> 7) & 0xff) << (8 * (e & 3));   // arithmetic shift: hi in [-128,127]
                     lo[e >> 2] |= (uint32_t)(qi & 127) << (8 * (e & 3));           // lo in [0,127]
                 } else {
@@ -156,7 +184,7 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
                 }
             }
             hrow[c] = make_uint2(hi[0], hi[1]);
-            if (a.limbs == 2) lrow[c] = make_uint2(lo[0], lo[1]);
+            if (a_limbs == 2) lrow[c] = make_uint2(lo[0], lo[1]);
             if (it.quant == ESSA_QUANT_INT4_G128) {
                 // sum of the row's fixed-point activations over each group of 128 columns (16 consecutive lanes),
                 // times delta: what the zero-points of the 4-bit format multiply.  Kept as bf16 head + tail.
@@ -189,12 +217,8 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     // ---- (b) partial t = V_A^T x for 32 rows of one item over one K slice --------------------------------
     const int role_ = 2; (void)role_;
     PSTAMP(0) PSTAMP(7)
-    const int lb = b - n_qblocks;
-    int g = 0;
-    while (lb >= a.lora_start[g + 1]) ++g;
-    const fwd_item& it = a.it[g];
     const int S = it.tslices;
-    const int r0 = ((lb - a.lora_start[g]) / S) * 32, slice = (lb - a.lora_start[g]) % S;
+    const int r0 = ((lb - first) / S) * 32, slice = (lb - first) % S;
     const int l32 = lane & 31, h = lane >> 5;
     const int din = it.d_in, rp = it.rp, nbv = rp / 16, R = it.R;
     f32x16 acc0 = {0}, acc1 = {0};
@@ -209,7 +233,7 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         my_sa = it.sigmaA[(size_t)c * it.sigma_stride + my_j];
         if (slice == 0) my_sb = it.sigmaB[(size_t)c * it.sigma_stride + my_j];
     }
-    if (!(a.flags & ESSA_BASE_ONLY)) {
+    if (!(a_flags & ESSA_BASE_ONLY)) {
         // wave w takes the four consecutive steps slice*64 + 4w + u, i.e. 64 columns = 128 bytes of each of the 32 rows.
         // x: four coalesced loads (instruction i: rows 8i..8i+7, whole 128-byte lines), turned into operand order
         // through a wave-private, XOR-swizzled 4 KB patch of LDS; V_A: operand tiles straight from memory.
@@ -1260,8 +1284,10 @@ void fill_prep_tables(stream_args& a) {
         if (a.it[g].x_owner) q += (a.it[g].R + 3) / 4;
         l += ((a.it[g].R + 31) / 32) * a.it[g].tslices;
     }
-    a.quant_start[a.n_items] = q;
-    a.lora_start[a.n_items] = l;
+    for (int g = a.n_items; g <= ESSA_MAX_GROUP; ++g) {     // the kernel reads the totals from the last entry
+        a.quant_start[g] = q;
+        a.lora_start[g] = l;
+    }
 }
 
 }  // namespace
@@ -1300,9 +1326,7 @@ hipError_t w8a8_accumulators_stream(hipStream_t st, const fwd_item& it, int32_t*
     a.n_items = 1;
     a.flags = ESSA_BASE_ONLY | ESSA_COMPUTE_W8A8;
     a.limbs = 1;
-    a.quant_start[0] = 0;
-    a.quant_start[1] = (it.R + 3) / 4;      // quantise only: no rank-space work for the accumulator dump
-    a.lora_start[0] = a.lora_start[1] = 0;
+    for (int g = 1; g <= ESSA_MAX_GROUP; ++g) a.quant_start[g] = (it.R + 3) / 4;      // quantise only: no rank-space work (lora_start stays zero)
     hipLaunchKernelGGL(prep_kernel, dim3(a.quant_start[1]), dim3(PREP_NT), 0, st, a);
     return launch_gemm<2, 1, false, true>(st, a, acc_out);
 }
