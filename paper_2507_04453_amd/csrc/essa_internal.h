@@ -149,6 +149,10 @@ hipError_t mean_step(hipStream_t st, const float* Z, const float* coef, double u
 // ARS: ranks the N directions by max(r+, r-), order[N] best first, coef[b] = alpha (r+ - r-) / (b s_R) or zeros
 hipError_t ars_prepare(hipStream_t st, const float* rewards, int N, int b, float alpha, int32_t* order, float* coef);
 
+// columns of one K slice of the prep kernel's rank-space partial sums: never more than 8 slices up to d_in = 8192
+constexpr int prep_slice_cols(int d_in) { return d_in <= 4096 ? 512 : 1024; }
+constexpr int prep_slices(int d_in) { return (d_in + prep_slice_cols(d_in) - 1) / prep_slice_cols(d_in); }
+
 struct fwd_item {              // one projection of a grouped forward, device pointers only
     const void* X;
     const int32_t* row2cand;
@@ -186,7 +190,7 @@ struct fwd_item {              // one projection of a grouped forward, device po
     int Gp;
     uint16_t* XS16;            // [R][2][Gp] bf16 head and tail of delta_i * (sum of the row's fixed-point activations over a group)
     float* Tpart;              // [tslices][R rounded up to 32][rp] the K slices' shares of sA_c * (V_A^T x)
-    int tslices;               // K slices of 64 steps of 16
+    int tslices;               // prep_slices(d_in)
     float* SBrow;              // [R, rp] the row's candidate's sigma_B (gathered by the prep kernel)
     // fused reward (optional)
     const float* rv;           // [d_out] reward vector, or null

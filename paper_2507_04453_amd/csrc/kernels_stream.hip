@@ -77,6 +77,21 @@ __device__ __forceinline__ fwd_item fetch_item(const fwd_item& src) {
     return it;
 }
 
+// Pointers that come out of a descriptor are generic; memory instructions through them would be flat ones, which
+// count against both the vector-memory and the LDS counter and force full waits.  These name the global address space.
+template <class T> using gptr = __attribute__((address_space(1))) T*;
+template <class T> __device__ __forceinline__ gptr<const T> as_global(const T* p) { return (gptr<const T>)p; }
+template <class T> __device__ __forceinline__ gptr<T> as_global_w(T* p) { return (gptr<T>)p; }
+
+// A workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding access to
+// global memory (one counter serves loads and stores), which would put loads that are meant to fly across the
+// barrier back on the critical path.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // N consecutive words of the kernel arguments in one batch of scalar loads.
 template <int N>
 __device__ __forceinline__ void fetch_words(const int* p, int (&out)[N]) {
@@ -87,17 +102,20 @@ __device__ __forceinline__ void fetch_words(const int* p, int (&out)[N]) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// prep kernel (1024 threads): two kinds of workgroups in one launch.
-//  (a) quantise four activation rows into limbs, one row per 256 threads (once per distinct X of the group);
-//  (b) for one item, 32 rows and one K slice of 1024: the partial t = V_A^T x by bf16 MFMA against the head+tail
-//      copy of V_A; the 16 waves split the slice and their tiles are summed through LDS in a fixed order.  The
-//      GEMM kernel adds the slices up and turns t into u = sB_c * (M (sA_c * t)).
+// prep kernel (512 threads): two kinds of workgroups in one launch.
+//  (a) quantise two activation rows into limbs, one row per 256 threads (once per distinct X of the group);
+//  (b) for one item, 32 rows and one K slice: the partial t = V_A^T x by bf16 MFMA against the head+tail copy of
+//      V_A; each of the 8 waves takes 64 columns per 512 of the slice and the 8 partial tiles are summed through
+//      LDS in a fixed order.  The GEMM kernel adds the slices up and turns t into u = sB_c * (M (sA_c * t)).
+// A slice is 512 columns (1024 beyond d_in = 4096, so that there are never more than 8): the workgroups of this
+// role are bound by what one CU can load, and twice as many of them with half the columns each halve that time.
 // ------------------------------------------------------------------------------------------------
-constexpr int PREP_NT = 1024;
+constexpr int PREP_NT = 512;
+using essa_k::prep_slice_cols;
 
 __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
-    __shared__ __attribute__((aligned(16))) float part[8][2][16][64];   // lora role: partial tiles of 8 waves (64 KB)
-    __shared__ float wred[16];
+    __shared__ __attribute__((aligned(16))) float part[8][2][16][64];   // lora role: partial tiles of the 8 waves (64 KB)
+    __shared__ float wred[8];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
     // Two dependent fetches from the kernel arguments stand between the start of the kernel and its first load from
@@ -126,12 +144,12 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     if (quant_role) {
         const int role_ = 1; (void)role_;
         PSTAMP(0) PSTAMP(7)
-        // ---- (a) row quantisation: this 256-thread group takes row 4*b' + grp of its item ---------------
+        // ---- (a) row quantisation: this 256-thread group takes row 2*b' + grp of its item ---------------
         const int grp = tid >> 8, t256 = tid & 255;
-        const int i = (b - first) * 4 + grp;
+        const int i = (b - first) * 2 + grp;
         const bool live = i < it.R;
         const int din = it.d_in, dpad = it.d_in_pad;
-        const u32x4* xrow = reinterpret_cast<const u32x4*>((const uint16_t*)it.X + (size_t)(live ? i : 0) * din);
+        const gptr<const u32x4> xrow = as_global(reinterpret_cast<const u32x4*>((const uint16_t*)it.X + (size_t)(live ? i : 0) * din));
         const int nch = din / 8;                          // 16-byte chunks of 8 bf16
         // the row is read once: the first four chunks of every thread (rows up to 8192 wide) wait in registers
         // between the two passes
@@ -164,8 +182,10 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         const float inv = amax > 0.f ? top / amax : 0.f;
         PSTAMP(1)
         if (!live) return;
-        uint2* hrow = reinterpret_cast<uint2*>(it.Xh + (size_t)i * dpad);
-        uint2* lrow = reinterpret_cast<uint2*>(it.Xl + (size_t)i * dpad);
+        typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+        const gptr<u32x2> hrow = as_global_w(reinterpret_cast<u32x2*>(it.Xh + (size_t)i * dpad));
+        const gptr<u32x2> lrow = as_global_w(reinterpret_cast<u32x2*>(it.Xl + (size_t)i * dpad));
+        const gptr<uint16_t> xs16 = as_global_w(it.XS16);
         auto quantise_chunk = [&](int c, const u32x4& v) {
             uint32_t hi[2] = {0, 0}, lo[2] = {0, 0};
             int qsum = 0;
@@ -183,8 +203,8 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
                     hi[e >> 2] |= (uint32_t)(qi & 0xff) << (8 * (e & 3));
                 }
             }
-            hrow[c] = make_uint2(hi[0], hi[1]);
-            if (a_limbs == 2) lrow[c] = make_uint2(lo[0], lo[1]);
+            hrow[c] = (u32x2){hi[0], hi[1]};
+            if (a_limbs == 2) lrow[c] = (u32x2){lo[0], lo[1]};
             if (it.quant == ESSA_QUANT_INT4_G128) {
                 // sum of the row's fixed-point activations over each group of 128 columns (16 consecutive lanes),
                 // times delta: what the zero-points of the 4-bit format multiply.  Kept as bf16 head + tail.
@@ -195,8 +215,8 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
                 if ((lane & 15) == 0 && grp16 < it.Gp) {
                     const float xs = (amax > 0.f ? amax / top : 0.f) * (float)gs;
                     const uint16_t xh = f32_to_bf16_bits(xs);
-                    it.XS16[(size_t)i * 2 * it.Gp + grp16] = xh;
-                    it.XS16[(size_t)i * 2 * it.Gp + it.Gp + grp16] = f32_to_bf16_bits(xs - bf16_bits_to_f32(xh));
+                    xs16[(size_t)i * 2 * it.Gp + grp16] = xh;
+                    xs16[(size_t)i * 2 * it.Gp + it.Gp + grp16] = f32_to_bf16_bits(xs - bf16_bits_to_f32(xh));
                 }
             }
         };
@@ -207,10 +227,10 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         for (int c = t256 + 1024; c < dpad / 8; c += 256) quantise_chunk(c, c < nch ? xrow[c] : (u32x4){0, 0, 0, 0});
         if (it.quant == ESSA_QUANT_INT4_G128)
             for (int gq = dpad / 128 + t256; gq < it.Gp; gq += 256) {
-                it.XS16[(size_t)i * 2 * it.Gp + gq] = 0;
-                it.XS16[(size_t)i * 2 * it.Gp + it.Gp + gq] = 0;
+                xs16[(size_t)i * 2 * it.Gp + gq] = 0;
+                xs16[(size_t)i * 2 * it.Gp + it.Gp + gq] = 0;
             }
-        if (t256 == 0) it.xdelta[i] = amax > 0.f ? amax / top : 0.f;
+        if (t256 == 0) as_global_w(it.xdelta)[i] = amax > 0.f ? amax / top : 0.f;
         PSTAMP(2)
         return;
     }
@@ -223,92 +243,122 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     const int din = it.d_in, rp = it.rp, nbv = rp / 16, R = it.R;
     f32x16 acc0 = {0}, acc1 = {0};
     const int ksteps = din / 16;
-    // the candidate's singular values for the (row, j) element this thread finishes at the end: fetched now (a chain of
-    // two dependent loads) so that they are there when the sums are
+    const int scols = prep_slice_cols(din);
+    // The candidate's singular values for the (row, j) elements this thread finishes at the end (one for rank 16, two
+    // for rank 32) are a chain of two dependent loads: the row's candidate is asked for right behind the tile loads
+    // (loads come back in order, so it does not hold them up), the singular values once the MFMAs are issued, and
+    // they arrive during the reduction.  Every thread asks, with clamped indices: a branch around a load would make
+    // the compiler wait for the value where the branch ends.
     const int rsh = rp == 16 ? 4 : 5;                       // rp is 16 or 32
-    const int my_row = tid >> rsh, my_j = tid & (rp - 1);   // tid < 32 * rp takes part
-    float my_sa = 0.f, my_sb = 0.f;
-    if (tid < 32 * rp && my_j < it.r) {
-        const int c = it.row2cand[min(r0 + my_row, R - 1)];
-        my_sa = it.sigmaA[(size_t)c * it.sigma_stride + my_j];
-        if (slice == 0) my_sb = it.sigmaB[(size_t)c * it.sigma_stride + my_j];
+    int e_row[2], e_j[2], my_c[2];
+    float my_sa[2], my_sb[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int e = tid + PREP_NT * i;                   // element e < 32 * rp is real
+        e_row[i] = (e >> rsh) & 31;
+        e_j[i] = e & (rp - 1);
     }
-    if (!(a_flags & ESSA_BASE_ONLY)) {
-        // wave w takes the four consecutive steps slice*64 + 4w + u, i.e. 64 columns = 128 bytes of each of the 32 rows.
-        // x: four coalesced loads (instruction i: rows 8i..8i+7, whole 128-byte lines), turned into operand order
-        // through a wave-private, XOR-swizzled 4 KB patch of LDS; V_A: operand tiles straight from memory.
+    auto ask_candidates = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) my_c[i] = as_global(it.row2cand)[min(r0 + e_row[i], R - 1)];
+    };
+    if (a_flags & ESSA_BASE_ONLY) {
+        ask_candidates();
+    } else {
+        // wave w takes, of every 512 columns of the slice, the four consecutive steps 4w + u, i.e. 64 columns = 128 bytes
+        // of each of the 32 rows.  x: four coalesced loads (instruction i: rows 8i..8i+7, whole 128-byte lines), turned
+        // into operand order through a wave-private, XOR-swizzled 4 KB patch of LDS; V_A: operand tiles straight from memory.
         unsigned char* xs = reinterpret_cast<unsigned char*>(&part[0][0][0][0]) + wave * 4096;
-        const int kbase = slice * 1024 + wave * 64;
         const int ch = lane & 7;
-        u32x4 xg[4], xa[4], v0[4], v1[4];
+        const gptr<const u32x4> vt = as_global(reinterpret_cast<const u32x4*>(it.VAp)) + lane;
+        for (int c0 = 0; c0 < scols; c0 += 512) {
+            const int kbase = slice * scols + c0 + wave * 64;
+            const int ks0 = kbase / 16;
+            u32x4 xg[4], xa[4], v0[4], v1[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = 8 * i + (lane >> 3), col = kbase + ch * 8;
-            xg[i] = (u32x4){0, 0, 0, 0};
-            if (col < din) xg[i] = *reinterpret_cast<const u32x4*>((const uint16_t*)it.X + (size_t)min(r0 + row, R - 1) * din + col);
-        }
-        const u32x4* vt = reinterpret_cast<const u32x4*>(it.VAp) + lane;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int ks = slice * 64 + 4 * wave + u;
-            v0[u] = v1[u] = (u32x4){0, 0, 0, 0};
-            if (ks < ksteps) {
-                v0[u] = vt[((size_t)ks * nbv) * 64];
-                if (nbv == 2) v1[u] = vt[((size_t)ks * nbv + 1) * 64];
+            for (int i = 0; i < 4; ++i) {
+                // every lane loads (a column past the row reads the row's first chunk instead and is zeroed): no branch
+                // stands between the loads
+                const int row = 8 * i + (lane >> 3), col = kbase + ch * 8;
+                xg[i] = *as_global(reinterpret_cast<const u32x4*>((const uint16_t*)it.X + (size_t)min(r0 + row, R - 1) * din + (col < din ? col : 0)));
             }
-        }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = 8 * i + (lane >> 3);
-            *reinterpret_cast<u32x4*>(xs + row * 128 + ((ch ^ ((row >> 1) & 7)) * 16)) = xg[i];
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            for (int u = 0; u < 4; ++u) {
+                v0[u] = vt[((size_t)(ks0 + u < ksteps ? ks0 + u : 0) * nbv) * 64];
+                v1[u] = (u32x4){0, 0, 0, 0};
+            }
+            if (nbv == 2) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const u32x4*>(xs + l32 * 128 + (((2 * u + h) ^ ((l32 >> 1) & 7)) * 16));
+                for (int u = 0; u < 4; ++u) v1[u] = vt[((size_t)(ks0 + u < ksteps ? ks0 + u : 0) * 2 + 1) * 64];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (c0 == 0) ask_candidates();
+            __builtin_amdgcn_sched_barrier(0);              // all loads are out before anything waits for one of them
+            if (kbase + ch * 8 >= din) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v0[u]), acc0, 0, 0, 0);
-            if (nbv == 2)
-                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v1[u]), acc1, 0, 0, 0);
+                for (int i = 0; i < 4; ++i) xg[i] = (u32x4){0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (ks0 + u >= ksteps) v0[u] = v1[u] = (u32x4){0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = 8 * i + (lane >> 3);
+                *reinterpret_cast<u32x4*>(xs + row * 128 + ((ch ^ ((row >> 1) & 7)) * 16)) = xg[i];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int u = 0; u < 4; ++u) xa[u] = *reinterpret_cast<const u32x4*>(xs + l32 * 128 + (((2 * u + h) ^ ((l32 >> 1) & 7)) * 16));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v0[u]), acc0, 0, 0, 0);
+                if (nbv == 2)
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[u]), __builtin_bit_cast(bf16x8, v1[u]), acc1, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // the patch is read again only by this wave, after its own next stores: wave-level ordering is enough
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     }
-    __syncthreads();          // the staging patches become the reduction buffer
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const size_t at = (size_t)my_c[i] * it.sigma_stride + min(e_j[i], it.r - 1);
+        my_sa[i] = as_global(it.sigmaA)[at];
+        my_sb[i] = as_global(it.sigmaB)[at];
+    }
+    lds_barrier();            // the staging patches become the reduction buffer
     PSTAMP(1)
-    // 16 partial tiles -> 8 -> 1, always in the same order (the second column block exists for rank 32 only)
-    if (wave >= 8) {
+    // the 8 partial tiles, added up below always in the same order (the second column block exists for rank 32 only)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            part[wave - 8][0][q][lane] = acc0[q];
-            if (nbv == 2) part[wave - 8][1][q][lane] = acc1[q];
-        }
-    }
-    __syncthreads();
-    if (wave < 8) {
+    for (int q = 0; q < 16; ++q) part[wave][0][q][lane] = acc0[q];
+    if (nbv == 2) {
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            part[wave][0][q][lane] += acc0[q];
-            if (nbv == 2) part[wave][1][q][lane] += acc1[q];
-        }
+        for (int q = 0; q < 16; ++q) part[wave][1][q][lane] = acc1[q];
     }
-    __syncthreads();
+    lds_barrier();
     PSTAMP(2)
     // element (row, j): head and tail columns of V_A's column j meet here, and the candidate's sigma_A scales the
     // slice's share of t_j = <V_A[:, j], x>; the slice-0 workgroup also passes on the row's sigma_B
     const int rpad = (R + 31) / 32 * 32;
-    if (tid < 32 * rp) {
-        const int row = my_row, j = my_j;
-        const int q = 4 * (row >> 3) + (row & 3), lnr = 32 * ((row >> 2) & 1);
-        float th[2];
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int v = e * rp + j, nb = v >> 5, ln = lnr + (v & 31);
-            th[e] = ((part[0][nb][q][ln] + part[1][nb][q][ln]) + (part[2][nb][q][ln] + part[3][nb][q][ln])) +
-                    ((part[4][nb][q][ln] + part[5][nb][q][ln]) + (part[6][nb][q][ln] + part[7][nb][q][ln]));
+    for (int i = 0; i < 2; ++i) {
+        if (tid + PREP_NT * i < 32 * rp) {               // rank 16: the first element only (the same for the whole workgroup)
+            const int row = e_row[i], j = e_j[i];
+            const int q = 4 * (row >> 3) + (row & 3), lnr = 32 * ((row >> 2) & 1);
+            float th[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int v = e * rp + j, nb = v >> 5, ln = lnr + (v & 31);
+                th[e] = ((part[0][nb][q][ln] + part[1][nb][q][ln]) + (part[2][nb][q][ln] + part[3][nb][q][ln])) +
+                        ((part[4][nb][q][ln] + part[5][nb][q][ln]) + (part[6][nb][q][ln] + part[7][nb][q][ln]));
+            }
+            as_global_w(it.Tpart)[((size_t)slice * rpad + r0 + row) * rp + j] = (j < it.r ? my_sa[i] : 0.f) * (th[0] + th[1]);
+            if (slice == 0 && r0 + row < R) as_global_w(it.SBrow)[(size_t)(r0 + row) * rp + j] = j < it.r ? my_sb[i] : 0.f;
         }
-        it.Tpart[((size_t)slice * rpad + r0 + row) * rp + j] = my_sa * (th[0] + th[1]);
-        if (slice == 0 && r0 + row < R) it.SBrow[(size_t)(r0 + row) * rp + j] = my_sb;
     }
     PSTAMP(3)
 }
@@ -1281,7 +1331,7 @@ void fill_prep_tables(stream_args& a) {
     for (int g = 0; g < a.n_items; ++g) {
         a.quant_start[g] = q;
         a.lora_start[g] = l;
-        if (a.it[g].x_owner) q += (a.it[g].R + 3) / 4;
+        if (a.it[g].x_owner) q += (a.it[g].R + 1) / 2;
         l += ((a.it[g].R + 31) / 32) * a.it[g].tslices;
     }
     for (int g = a.n_items; g <= ESSA_MAX_GROUP; ++g) {     // the kernel reads the totals from the last entry
@@ -1326,7 +1376,7 @@ hipError_t w8a8_accumulators_stream(hipStream_t st, const fwd_item& it, int32_t*
     a.n_items = 1;
     a.flags = ESSA_BASE_ONLY | ESSA_COMPUTE_W8A8;
     a.limbs = 1;
-    for (int g = 1; g <= ESSA_MAX_GROUP; ++g) a.quant_start[g] = (it.R + 3) / 4;      // quantise only: no rank-space work (lora_start stays zero)
+    for (int g = 1; g <= ESSA_MAX_GROUP; ++g) a.quant_start[g] = (it.R + 1) / 2;      // quantise only: no rank-space work (lora_start stays zero)
     hipLaunchKernelGGL(prep_kernel, dim3(a.quant_start[1]), dim3(PREP_NT), 0, st, a);
     return launch_gemm<2, 1, false, true>(st, a, acc_out);
 }
