@@ -614,7 +614,7 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
         total += align256(R * p->rp * 4) + align256(R * p->rp * 4) + align256(R * (p->groups > 0 ? p->groups : 1) * 4);
         if (flags & ESSA_COMPUTE_W8A8) total += align256(R * (size_t)p->d_in) + align256(R * 4);
         if (p->Wt) total += 2 * align256((R + 255) / 256 * 256 * (size_t)p->d_in_pad) + align256(R * 4) + align256(R * 2 * (size_t)(p->Gp + 16) * 2) +
-                            align256((size_t)essa_k::prep_slices(p->d_in) * ((R + 31) / 32 * 32) * 2 * p->rp * 4);
+                            align256((size_t)((R + 31) / 32 * 32) * p->rp * 8 * 4);
     }
     ESSA_TRY(essa_ws_reserve(ctx, total));
     char* w = (char*)ctx->ws;
@@ -630,7 +630,7 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
         }
         if (k.Wt) {
             k.tslices = essa_k::prep_slices(k.d_in);
-            k.Tpart = (float*)w; w += align256((size_t)k.tslices * ((R + 31) / 32 * 32) * 2 * k.rp * 4);
+            k.Tpart = (float*)w; w += align256((size_t)((R + 31) / 32 * 32) * k.rp * 8 * 4);
             // items reading the same X share one set of limbs; the first of them quantises
             const essa_k::fwd_item* first = nullptr;
             for (auto& o : out) {

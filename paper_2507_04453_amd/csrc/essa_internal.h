@@ -189,7 +189,7 @@ struct fwd_item {              // one projection of a grouped forward, device po
     const uint16_t* SZ16;
     int Gp;
     uint16_t* XS16;            // [R][2][Gp] bf16 head and tail of delta_i * (sum of the row's fixed-point activations over a group)
-    float* Tpart;              // [tslices][R rounded up to 32][rp] the K slices' shares of sA_c * (V_A^T x)
+    float* Tpart;              // [R rounded up to 32][rp][8] the K slices' shares of sA_c * (V_A^T x); slots past tslices hold zeros
     int tslices;               // prep_slices(d_in)
     float* SBrow;              // [R, rp] the row's candidate's sigma_B (gathered by the prep kernel)
     // fused reward (optional)

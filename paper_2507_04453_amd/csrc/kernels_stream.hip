@@ -343,7 +343,6 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     PSTAMP(2)
     // element (row, j): head and tail columns of V_A's column j meet here, and the candidate's sigma_A scales the
     // slice's share of t_j = <V_A[:, j], x>; the slice-0 workgroup also passes on the row's sigma_B
-    const int rpad = (R + 31) / 32 * 32;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         if (tid + PREP_NT * i < 32 * rp) {               // rank 16: the first element only (the same for the whole workgroup)
@@ -356,8 +355,14 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
                 th[e] = ((part[0][nb][q][ln] + part[1][nb][q][ln]) + (part[2][nb][q][ln] + part[3][nb][q][ln])) +
                         ((part[4][nb][q][ln] + part[5][nb][q][ln]) + (part[6][nb][q][ln] + part[7][nb][q][ln]));
             }
-            as_global_w(it.Tpart)[((size_t)slice * rpad + r0 + row) * rp + j] = (j < it.r ? my_sa[i] : 0.f) * (th[0] + th[1]);
-            if (slice == 0 && r0 + row < R) as_global_w(it.SBrow)[(size_t)(r0 + row) * rp + j] = j < it.r ? my_sb[i] : 0.f;
+            // the eight slice slots of an element sit side by side (two 16-byte loads for the GEMM kernel); the slice-0
+            // workgroup clears the slots no slice fills
+            const gptr<float> slot = as_global_w(it.Tpart) + ((size_t)(r0 + row) * rp + j) * 8;
+            slot[slice] = (j < it.r ? my_sa[i] : 0.f) * (th[0] + th[1]);
+            if (slice == 0) {
+                for (int sl = S; sl < 8; ++sl) slot[sl] = 0.f;
+                if (r0 + row < R) as_global_w(it.SBrow)[(size_t)(r0 + row) * rp + j] = j < it.r ? my_sb[i] : 0.f;
+            }
         }
     }
     PSTAMP(3)
@@ -553,26 +558,30 @@ constexpr size_t gemm_smem_bytes() {
 // other loads between them: the global loads, then the arithmetic (which contains one workgroup barrier).
 constexpr int UTP = 36;            // LDS pitch (floats) of the two small matrices
 template <int BM, int EU>
-__device__ __forceinline__ void u_tile_loads(const fwd_item& it, int m0, int tid, float (&tp)[EU][8], float (&sb)[EU], float (&mreg)[2]) {
-    const int R = it.R, rp = it.rp, rpad = (R + 31) / 32 * 32, S = it.tslices;
+__device__ __forceinline__ void u_tile_loads(const fwd_item& it, int m0, int tid, f32x4 (&tp)[EU][2], float (&sb)[EU], float (&mreg)[2]) {
+    const int R = it.R, rp = it.rp, rpad = (R + 31) / 32 * 32;
     const int rsh = rp == 16 ? 4 : 5;                     // rp is 16 or 32: divisions become shifts
+    const gptr<const f32x4> tpart = as_global(reinterpret_cast<const f32x4*>(it.Tpart));
 #pragma unroll
     for (int i = 0; i < EU; ++i) {
-        // loads are skipped only on conditions that hold for the whole workgroup (rank 16 fills half of the
-        // entries, S slices of the eight slots): scalar branches, no per-lane masking between the loads
+        // loads are skipped only on a condition that holds for the whole workgroup (rank 16 fills half of the
+        // entries): a scalar branch, no per-lane masking between the loads
         const int e = min(tid + NT * i, BM * rp - 1), row = e >> rsh, j = e & (rp - 1);
-        const float* src = it.Tpart + (size_t)min(m0 + row, rpad - 1) * rp + j;
-        const bool used = NT * i < BM * rp;
-#pragma unroll
-        for (int sl = 0; sl < 8; ++sl) tp[i][sl] = (used && sl < S) ? src[(size_t)sl * rpad * rp] : 0.f;
-        sb[i] = used ? it.SBrow[(size_t)min(m0 + row, R - 1) * rp + j] : 0.f;
+        const size_t at = ((size_t)min(m0 + row, rpad - 1) * rp + j) * 2;
+        tp[i][0] = tp[i][1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        sb[i] = 0.f;
+        if (NT * i < BM * rp) {
+            tp[i][0] = tpart[at];
+            tp[i][1] = tpart[at + 1];
+            sb[i] = as_global(it.SBrow)[(size_t)min(m0 + row, R - 1) * rp + j];
+        }
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) mreg[i] = it.M[min(tid + NT * i, rp * rp - 1)];
+    for (int i = 0; i < 2; ++i) mreg[i] = as_global(it.M)[min(tid + NT * i, rp * rp - 1)];
 }
 
 template <int BM, int EU>
-__device__ __forceinline__ void u_tile_finish(const fwd_item& it, unsigned flags, int tid, const float (&tp)[EU][8], const float (&sb)[EU],
+__device__ __forceinline__ void u_tile_finish(const fwd_item& it, unsigned flags, int tid, const f32x4 (&tp)[EU][2], const float (&sb)[EU],
                                               const float (&mreg)[2], float* tvec, float* Ms, unsigned char* utile) {
     const int rp = it.rp, rsh = rp == 16 ? 4 : 5;
 #pragma unroll
@@ -584,9 +593,9 @@ __device__ __forceinline__ void u_tile_finish(const fwd_item& it, unsigned flags
     for (int i = 0; i < EU; ++i) {
         const int e = tid + NT * i;
         if (e < BM * rp) {
-            float t = tp[i][0];
+            float t = tp[i][0][0];
 #pragma unroll
-            for (int sl = 1; sl < 8; ++sl) t += tp[i][sl];       // slots beyond S hold zeros
+            for (int sl = 1; sl < 8; ++sl) t += tp[i][sl >> 2][sl & 3];       // slices in ascending order; unused slots hold zeros
             tvec[(e >> rsh) * UTP + (e & (rp - 1))] = t;
         }
     }
@@ -622,15 +631,46 @@ __device__ __forceinline__ void u_tile_finish(const fwd_item& it, unsigned flags
 // An output tile of BM rows x 128 channels, staged in LDS as rows of CROW bytes, leaves as full rows (16 bytes per
 // thread where the output allows it).  With a reward vector, the tile's share <Y[i, block], v[block]> of every row
 // goes to rowpart[blk][i]: one partial per (128-channel block, row); the blocks are added in a fixed order later.
+// The reward-vector entries that this thread's 16-byte piece of an output row meets.  The piece is the same for every
+// row a thread stores (NT is a multiple of the pieces per row), so they are fetched once, before the epilogue's
+// arithmetic, instead of behind it.  Entries past the last channel, and all of them without a reward vector, are 0.
+template <bool YBF16>
+struct rv_piece { float v[YBF16 ? 8 : 4]; };
+template <bool YBF16>
+__device__ __forceinline__ rv_piece<YBF16> load_rv_piece(const fwd_item& it, int n0, int tid) {
+    constexpr int EPV = YBF16 ? 8 : 4, PPR = 128 / EPV;
+    static_assert(NT % PPR == 0, "a thread keeps its piece from row to row");
+    rv_piece<YBF16> r;
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) r.v[e] = 0.f;
+    if (it.rv) {
+        const int o = n0 + (tid % PPR) * EPV, dout = it.d_out;
+        const gptr<const float> rv = as_global(it.rv);
+        if ((reinterpret_cast<uintptr_t>(it.rv) & 15) == 0 && o + EPV <= dout) {
+#pragma unroll
+            for (int e4 = 0; e4 < EPV / 4; ++e4) {
+                const f32x4 r4 = *reinterpret_cast<gptr<const f32x4>>(rv + o + 4 * e4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) r.v[4 * e4 + e] = r4[e];
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                if (o + e < dout) r.v[e] = rv[o + e];
+        }
+    }
+    return r;
+}
+
 template <bool YBF16, int BM>
-__device__ __forceinline__ void store_ctile(const unsigned char* ctile, const fwd_item& it, int m0, int n0, int blk, int tid) {
+__device__ __forceinline__ void store_ctile(const unsigned char* ctile, const fwd_item& it, int m0, int n0, int blk, int tid,
+                                            const rv_piece<YBF16>& rvp) {
     constexpr int ESZ = YBF16 ? 2 : 4, EPV = 16 / ESZ, PPR = 128 / EPV;     // elements per vector, vectors per row
     constexpr int CROW = 128 * ESZ + 16;
     const int R = it.R, dout = it.d_out;
-    unsigned char* Yb = reinterpret_cast<unsigned char*>(it.Y);
+    const gptr<unsigned char> Yb = as_global_w(reinterpret_cast<unsigned char*>(it.Y));
     const bool vec_ok = (dout % EPV == 0) && ((reinterpret_cast<uintptr_t>(it.Y) & 15) == 0);
-    const float* __restrict__ rv = it.rv;
-    const bool rv_vec = rv && (reinterpret_cast<uintptr_t>(rv) & 15) == 0 && dout % EPV == 0;
+    const bool with_reward = it.rv != nullptr;
 #pragma unroll
     for (int p0 = 0; p0 < BM * PPR; p0 += NT) {           // BM * PPR is a multiple of NT: every lane takes part in the shuffles
         const int p = p0 + tid;
@@ -641,36 +681,26 @@ __device__ __forceinline__ void store_ctile(const unsigned char* ctile, const fw
         const u32x4 val = *reinterpret_cast<const u32x4*>(src);
         if (valid) {
             if (vec_ok && o + EPV <= dout) {
-                *reinterpret_cast<u32x4*>(Yb + ((size_t)i * dout + o) * ESZ) = val;
+                *reinterpret_cast<gptr<u32x4>>(Yb + ((size_t)i * dout + o) * ESZ) = val;
             } else {
                 for (int e = 0; e < EPV && o + e < dout; ++e) {
-                    if (YBF16) reinterpret_cast<uint16_t*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const uint16_t*>(src)[e];
-                    else reinterpret_cast<float*>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const float*>(src)[e];
+                    if (YBF16) reinterpret_cast<gptr<uint16_t>>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const uint16_t*>(src)[e];
+                    else reinterpret_cast<gptr<float>>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const float*>(src)[e];
                 }
             }
         }
-        if (rv) {
-            float yv[EPV], s = 0.f;
-#pragma unroll
-            for (int e = 0; e < EPV; ++e)
-                yv[e] = YBF16 ? __uint_as_float((e & 1) ? (val[e >> 1] & 0xffff0000u) : (val[e >> 1] << 16)) : __uint_as_float(val[e]);
+        if (with_reward) {
+            float s = 0.f;
             if (valid) {
-                if (rv_vec && o + EPV <= dout) {
 #pragma unroll
-                    for (int e4 = 0; e4 < EPV / 4; ++e4) {
-                        const f32x4 r4 = *reinterpret_cast<const f32x4*>(rv + o + 4 * e4);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) s = fmaf(yv[4 * e4 + e], r4[e], s);
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < EPV; ++e)
-                        if (o + e < dout) s = fmaf(yv[e], rv[o + e], s);
+                for (int e = 0; e < EPV; ++e) {
+                    const float y = YBF16 ? __uint_as_float((e & 1) ? (val[e >> 1] & 0xffff0000u) : (val[e >> 1] << 16)) : __uint_as_float(val[e]);
+                    s = fmaf(o + e < dout ? y : 0.f, rvp.v[e], s);     // what lies past the last channel in the LDS tile is not data
                 }
             }
 #pragma unroll
             for (int off = PPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-            if (piece == 0 && i < R && n0 < dout) it.rowpart[(size_t)blk * R + i] = s;   // a half tile past the last channel has no block
+            if (piece == 0 && i < R && n0 < dout) as_global_w(it.rowpart)[(size_t)blk * R + i] = s;   // a half tile past the last channel has no block
         }
     }
 }
@@ -736,8 +766,14 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     float* tvec = reinterpret_cast<float*>(smem + STG);                        // [BM][UTP]
     float* Ms = tvec + BM * UTP;                                               // [rp][UTP]
     constexpr int EU = (BM * 32 + NT - 1) / NT;           // (row, j) entries of u per thread at the widest rank
-    float tp[EU][8], sb[EU], mreg[2];
-    if (!DUMP) u_tile_loads<BM, EU>(it, m0, tid, tp, sb, mreg);
+    f32x4 tp[EU][2];
+    float sb[EU], mreg[2];
+    float xdreg = 0.f;                                     // the row's fixed-point unit; parked in LDS on the way into the loop
+    if (!DUMP) {
+        u_tile_loads<BM, EU>(it, m0, tid, tp, sb, mreg);
+        xdreg = as_global(it.xdelta)[min(m0 + min(tid, BM - 1), R - 1)];
+    }
+    __builtin_amdgcn_sched_barrier(0);
 
     u32x4 w0[2], w1[2], w2[2], w3[2];
     fetch_w(w0, 0);
@@ -752,20 +788,19 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
 
     // epilogue operands, fetched now so that their latency hides behind the main loop
     const int oc = min(nbw * 32 + l32, dout - 1);
-    float wscale = 0.f, xdreg = 0.f;
+    float wscale = 0.f;
     u32x4 ubf[2][2];                                       // [ks][head, tail] fragments of U_B for this lane's channel
     if (!DUMP) {
-        if (!Q4) wscale = it.scale[oc];
+        if (!Q4) wscale = as_global(it.scale)[oc];
         const uint16_t* bp = it.UB16 + (size_t)oc * 2 * rp + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             ubf[ks][0] = ubf[ks][1] = (u32x4){0, 0, 0, 0};
             if (ks * 16 < rp) {
-                ubf[ks][0] = *reinterpret_cast<const u32x4*>(bp + ks * 16);
-                ubf[ks][1] = *reinterpret_cast<const u32x4*>(bp + rp + ks * 16);
+                ubf[ks][0] = *as_global(reinterpret_cast<const u32x4*>(bp + ks * 16));
+                ubf[ks][1] = *as_global(reinterpret_cast<const u32x4*>(bp + rp + ks * 16));
             }
         }
-        xdreg = it.xdelta[min(m0 + min(tid, BM - 1), R - 1)];   // parked in LDS once the other loads are on their way
     }
     if (!DUMP) u_tile_finish<BM, EU>(it, a.flags, tid, tp, sb, mreg, tvec, Ms, utile);   // part 2 (one barrier inside)
 
@@ -936,6 +971,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         }
         return;
     }
+    const rv_piece<YBF16> rvp = load_rv_piece<YBF16>(it, nb0 * 32, tid);      // used by the very last step: on its way from here
     __syncthreads();   // exchange slots are read; the same memory now becomes the output tile
     TSTAMP(3)
 
@@ -962,10 +998,10 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
             const uint16_t* xs = it.XS16 + (size_t)min(m0 + mb * 32 + l32, R - 1) * 2 * Gp + 8 * h;
             const uint16_t* sz = it.SZ16 + (size_t)(nbw * 32 + l32) * 2 * Gp + 8 * h;
             for (int ks = 0; ks < Gp / 16; ++ks) {
-                const bf16x8 xa_hi = *reinterpret_cast<const bf16x8*>(xs + ks * 16);
-                const bf16x8 xa_lo = *reinterpret_cast<const bf16x8*>(xs + Gp + ks * 16);
-                const bf16x8 zb_hi = *reinterpret_cast<const bf16x8*>(sz + ks * 16);
-                const bf16x8 zb_lo = *reinterpret_cast<const bf16x8*>(sz + Gp + ks * 16);
+                const bf16x8 xa_hi = *as_global(reinterpret_cast<const bf16x8*>(xs + ks * 16));
+                const bf16x8 xa_lo = *as_global(reinterpret_cast<const bf16x8*>(xs + Gp + ks * 16));
+                const bf16x8 zb_hi = *as_global(reinterpret_cast<const bf16x8*>(sz + ks * 16));
+                const bf16x8 zb_lo = *as_global(reinterpret_cast<const bf16x8*>(sz + Gp + ks * 16));
                 v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa_lo, zb_hi, v, 0, 0, 0);
                 v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa_hi, zb_lo, v, 0, 0, 0);
                 v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa_hi, zb_hi, v, 0, 0, 0);
@@ -999,7 +1035,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     TSTAMP(4)
 
     // ---- epilogue 3: the tile leaves as full rows, 16 bytes per thread where the output allows it
-    store_ctile<YBF16, BM>(smem, it, m0, nb0 * 32, nb0 >> 2, tid);
+    store_ctile<YBF16, BM>(smem, it, m0, nb0 * 32, nb0 >> 2, tid, rvp);
     TSTAMP(5)
 }
 
@@ -1106,9 +1142,10 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
     float* Ms = tvec + BM * UTP;
     constexpr int EU = (BM * 32 + NT - 1) / NT;
     {
-        float tp[EU][8], sbv[EU], mreg[2];
+        f32x4 tp[EU][2];
+        float sbv[EU], mreg[2];
         u_tile_loads<BM, EU>(it, m0, tid, tp, sbv, mreg);
-        const float xdreg = it.xdelta[min(m0 + min(tid, BM - 1), R - 1)];
+        const float xdreg = as_global(it.xdelta)[min(m0 + min(tid, BM - 1), R - 1)];
         load_tile(xs0, ws0, 0);
         u_tile_finish<BM, EU>(it, a.flags, tid, tp, sbv, mreg, tvec, Ms, utile);
         if (tid < BM) xd[tid] = xdreg;
@@ -1188,19 +1225,20 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
     constexpr int CROW = 128 * (YBF16 ? 2 : 4) + 16;
 #pragma unroll 1
     for (int half = 0; half < 2; ++half) {
+        const rv_piece<YBF16> rvp = load_rv_piece<YBF16>(it, nb0 * 32 + half * 128, tid);
         if ((wc >> 1) == half) {
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
                 const int oc = min((nb0 + wc * 2 + nb) * 32 + l32, dout - 1);
-                const float wscale = it.scale[oc];
+                const float wscale = as_global(it.scale)[oc];
                 u32x4 ubf[2][2];
                 const uint16_t* bp = it.UB16 + (size_t)oc * 2 * rp + 8 * h;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     ubf[ks][0] = ubf[ks][1] = (u32x4){0, 0, 0, 0};
                     if (ks * 16 < rp) {
-                        ubf[ks][0] = *reinterpret_cast<const u32x4*>(bp + ks * 16);
-                        ubf[ks][1] = *reinterpret_cast<const u32x4*>(bp + rp + ks * 16);
+                        ubf[ks][0] = *as_global(reinterpret_cast<const u32x4*>(bp + ks * 16));
+                        ubf[ks][1] = *as_global(reinterpret_cast<const u32x4*>(bp + rp + ks * 16));
                     }
                 }
 #pragma unroll
@@ -1241,7 +1279,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
             }
         }
         __syncthreads();
-        store_ctile<YBF16, BM>(smem, it, m0, nb0 * 32 + half * 128, (nb0 >> 2) + half, tid);
+        store_ctile<YBF16, BM>(smem, it, m0, nb0 * 32 + half * 128, (nb0 >> 2) + half, tid, rvp);
         __syncthreads();
     }
 }
