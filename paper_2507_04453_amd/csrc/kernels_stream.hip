@@ -54,10 +54,8 @@ struct stream_args {
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    // round to nearest even in one instruction (v_cvt_pk_bf16_f32)
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
 }
 
 // The descriptor of one item, fetched from the kernel arguments in one batch of scalar loads: left to itself the
@@ -981,6 +979,17 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     for (int mb = 0; mb < MB; ++mb) {
         const bool mine = MB >= 2 ? ((mb & 1) == kh) : (kh == 0);
         if (!mine) continue;
+        // fragments of u for the rank-r term: read now, used after the scaling arithmetic
+        bf16x8 ua[2][2];
+        {
+            const unsigned char* up = utile + (size_t)(mb * 32 + l32) * UROW + 16 * h;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const int kso = ks * 16 < rp ? ks : 0;      // rank 16: the first fragments again, unused
+                ua[ks][0] = *reinterpret_cast<const bf16x8*>(up + kso * 32);
+                ua[ks][1] = *reinterpret_cast<const bf16x8*>(up + 2 * rp + kso * 32);
+            }
+        }
         f32x16 v;
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
@@ -1009,17 +1018,14 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         }
         if (!(a.flags & ESSA_BASE_ONLY)) {
             // rank-r term U_B u_i: bf16 head+tail operands, lo*hi + hi*lo + hi*hi per 16 rank columns
-            const unsigned char* up = utile + (size_t)(mb * 32 + l32) * UROW + 16 * h;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 if (ks * 16 < rp) {
-                    const bf16x8 ua_hi = *reinterpret_cast<const bf16x8*>(up + ks * 32);
-                    const bf16x8 ua_lo = *reinterpret_cast<const bf16x8*>(up + 2 * rp + ks * 32);
                     const bf16x8 ub_hi = __builtin_bit_cast(bf16x8, ubf[ks][0]);
                     const bf16x8 ub_lo = __builtin_bit_cast(bf16x8, ubf[ks][1]);
-                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_lo, ub_hi, v, 0, 0, 0);
-                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_hi, ub_lo, v, 0, 0, 0);
-                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_hi, ub_hi, v, 0, 0, 0);
+                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua[ks][1], ub_hi, v, 0, 0, 0);
+                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua[ks][0], ub_lo, v, 0, 0, 0);
+                    v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua[ks][0], ub_hi, v, 0, 0, 0);
                 }
             }
         }
