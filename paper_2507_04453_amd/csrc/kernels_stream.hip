@@ -912,17 +912,23 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     TSTAMP(2)
 
     // ---- epilogue 1: the two K halves exchange accumulators.  Half kh keeps row blocks with (mb & 1) == kh
-    // (all of them when there is only one) and hands the others to its partner.
+    // (all of them when there is only one) and hands the others to its partner.  With two limbs each half first
+    // folds them into one fp32 value, 128 hi + lo, so that half as many bytes cross the LDS (one more rounding of
+    // 2^-24; the accumulator dump keeps its integers).
     // exchange slot (n, writer kh, limb, j): 16 x 64 ints, written as [q/4][lane] 16-byte vectors
+    constexpr bool FSUM = Q4 || (LIMBS == 2 && !DUMP);       // one fp32 value per element travels instead of the limbs
     auto slot = [&](int n_, int kh_, int l_, int j_) { return smem + ((size_t)((n_ * 2 + kh_) * LIMBS + l_) * MBO + j_) * 4096; };
-    if (Q4) {   // the running totals travel as bit patterns in the accumulator of limb 0
+    if (FSUM) {   // the values travel as bit patterns in the accumulator of limb 0
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[0][mb][q] = (int)__float_as_uint(tot[mb][q]);
+            for (int q = 0; q < 16; ++q) {
+                if (!Q4) tot[mb][q] = fmaf(128.0f, (float)acc[0][mb][q], (float)acc[LIMBS - 1][mb][q]);
+                acc[0][mb][q] = (int)__float_as_uint(tot[mb][q]);
+            }
     }
 #pragma unroll
-    for (int l = 0; l < (Q4 ? 1 : LIMBS); ++l)
+    for (int l = 0; l < (FSUM ? 1 : LIMBS); ++l)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const bool mine = MB >= 2 ? ((mb & 1) == kh) : (kh == 0);
@@ -936,7 +942,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
         }
     __syncthreads();
 #pragma unroll
-    for (int l = 0; l < (Q4 ? 1 : LIMBS); ++l)
+    for (int l = 0; l < (FSUM ? 1 : LIMBS); ++l)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const bool mine = MB >= 2 ? ((mb & 1) == kh) : (kh == 0);
@@ -947,8 +953,8 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
                     const i32x4 o4 = *reinterpret_cast<const i32x4*>(src + (q4 * 64 + lane) * 16);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        // 4-bit: fp32 totals, always (K half 0) + (K half 1)
-                        if (Q4) tot[mb][4 * q4 + e] = kh == 0 ? tot[mb][4 * q4 + e] + __uint_as_float((uint32_t)o4[e])
+                        // fp32 values: always (K half 0) + (K half 1)
+                        if (FSUM) tot[mb][4 * q4 + e] = kh == 0 ? tot[mb][4 * q4 + e] + __uint_as_float((uint32_t)o4[e])
                                                               : __uint_as_float((uint32_t)o4[e]) + tot[mb][4 * q4 + e];
                         else acc[l][mb][4 * q4 + e] += o4[e];
                     }
@@ -996,7 +1002,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
             const int rl = mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
             const float sc = xd[rl] * wscale;
             if (Q4) v[q] = tot[mb][q] * xd[rl];
-            else if (LIMBS == 2) v[q] = fmaf(128.0f, (float)acc[0][mb][q], (float)acc[LIMBS - 1][mb][q]) * sc;
+            else if (FSUM) v[q] = tot[mb][q] * sc;
             else v[q] = (float)acc[0][mb][q] * sc;
             if (a.flags & ESSA_LORA_ONLY) v[q] = 0.f;
         }
