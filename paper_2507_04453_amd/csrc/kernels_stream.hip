@@ -536,14 +536,14 @@ __device__ __forceinline__ void load_w(u32x4 (&w)[2], rsrc_t wbase, uint32_t wst
 
 // LDS stages of the activation tiles: four where they fit (the tile of K step j sits in stage j % 4 and can be
 // written before the step's barrier), two for the 128-row tile
-template <int MB>
-constexpr int gemm_stages() { return MB <= 2 ? 4 : 2; }
+template <int MB, bool Q4 = false>
+constexpr int gemm_stages() { return (MB <= 2 && !Q4) ? 4 : 2; }     // the 4-bit loop alternates between two stages
 
-template <int MB, int LIMBS, bool YBF16>
+template <int MB, int LIMBS, bool YBF16, bool Q4 = false>
 constexpr size_t gemm_smem_bytes() {
     constexpr size_t BM = 32 * MB;
-    constexpr size_t stages = gemm_stages<MB>() * LIMBS * BM * LROW;
-    constexpr size_t exch = (size_t)4 * 2 * LIMBS * (MB >= 2 ? MB / 2 : 1) * 4096;
+    constexpr size_t stages = gemm_stages<MB, Q4>() * LIMBS * BM * LROW;
+    constexpr size_t exch = (size_t)4 * 2 * LIMBS * (MB >= 2 ? MB / 2 : 1) * 4096;   // sized for the accumulator dump, which exchanges every limb
     constexpr size_t ctile = BM * (128 * (YBF16 ? 2 : 4) + 16);
     constexpr size_t pre = stages + BM * 36 * 4 + 32 * 36 * 4;   // + sA*t, core matrix (before the main loop)
     constexpr size_t m1 = pre > exch ? pre : exch;
@@ -703,13 +703,15 @@ __device__ __forceinline__ void store_ctile(const unsigned char* ctile, const fw
     }
 }
 
+// 4-bit weights, 64-row tile: registers capped at 128 so that two workgroups share a CU (what spills is the epilogue's
+// operands, across the main loop)
 template <int MB, int LIMBS, bool YBF16, bool DUMP, bool Q4>
-__global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __restrict__ acc_out) {
+__global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(stream_args a, int32_t* __restrict__ acc_out) {
     constexpr int BM = 32 * MB;
     constexpr int XTOT = LIMBS * BM * 8;               // 16-byte vectors of X per K tile
     constexpr int XV = (XTOT + NT - 1) / NT;
     constexpr int MBO = MB >= 2 ? MB / 2 : 1;          // row blocks a wave finishes in the epilogue
-    constexpr size_t BIG = gemm_smem_bytes<MB, LIMBS, YBF16>() - BM * 4 - BM * UROW;
+    constexpr size_t BIG = gemm_smem_bytes<MB, LIMBS, YBF16, Q4>() - BM * 4 - BM * UROW;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float* xd = reinterpret_cast<float*>(smem + BIG);                  // [BM] value of one fixed-point unit per row
     unsigned char* utile = smem + BIG + BM * 4;                        // [BM][UROW] bf16 head+tail of u_i
@@ -760,7 +762,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     };
     // u tile, part 1: the loads, issued ahead of the weight and activation tiles so that they come back first (loads
     // return in order) and the arithmetic of part 2 runs while those tiles are still on their way
-    constexpr size_t STG = (size_t)gemm_stages<MB>() * LIMBS * BM * LROW;
+    constexpr size_t STG = (size_t)gemm_stages<MB, Q4>() * LIMBS * BM * LROW;
     float* tvec = reinterpret_cast<float*>(smem + STG);                        // [BM][UTP]
     float* Ms = tvec + BM * UTP;                                               // [rp][UTP]
     constexpr int EU = (BM * 32 + NT - 1) / NT;           // (row, j) entries of u per thread at the widest rank
@@ -850,7 +852,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_kernel(stream_args a, int32_t* __r
     // so no LDS or memory latency sits between two MFMAs of a wave.  With two stages (128-row tile) tile kt+2 is
     // written after the barrier instead, into the stage tile kt was read from.  Tile indices past the end are
     // clamped: that data is fetched again and never used.
-    constexpr int NS = gemm_stages<MB>();
+    constexpr int NS = gemm_stages<MB, Q4>();
     constexpr bool EARLY = NS == 4;
     constexpr int NF = LIMBS * MB;                      // MFMAs per K chunk
     static_assert(!EARLY || NF >= XV, "one LDS write per MFMA slot");
@@ -1326,7 +1328,7 @@ hipError_t launch_gemm(hipStream_t st, stream_args& a, int32_t* acc_out) {
         total += ((a.it[g].R + 32 * MB - 1) / (32 * MB)) * ((a.it[g].n_blocks + 3) / 4);
     }
     a.tile_start[a.n_items] = total;
-    constexpr size_t smem = gemm_smem_bytes<MB, LIMBS, YBF16>();
+    constexpr size_t smem = gemm_smem_bytes<MB, LIMBS, YBF16, Q4>();
     static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
     auto kern = gemm_i8_kernel<MB, LIMBS, YBF16, DUMP, Q4>;
     static bool attr_done = false;   // one flag per instantiation
@@ -1348,10 +1350,11 @@ hipError_t launch_gemm_mb(hipStream_t st, stream_args& a, int mb) {
         case 1: return launch_gemm<1, LIMBS, YBF16, false, Q4>(st, a, nullptr);
         case 2: return launch_gemm<2, LIMBS, YBF16, false, Q4>(st, a, nullptr);
         default:
-            // the 128-row tile exists for 4-bit weights only: with int8 weights its double-buffered fragments do not
-            // fit the register file, and row counts that large take the 128 x 256 kernel anyway
-            if constexpr (Q4) return launch_gemm<4, LIMBS, YBF16, false, Q4>(st, a, nullptr);
-            else return launch_gemm<2, LIMBS, YBF16, false, Q4>(st, a, nullptr);
+            // no taller tile: with int8 weights its double-buffered fragments do not fit the register file (row counts
+            // that large take the 128 x 256 kernel anyway), and with 4-bit weights, whose loop runs its MFMA, scaling
+            // and LDS phases one after the other, two 64-row workgroups per CU overlap each other's phases and beat
+            // one 128-row workgroup (c4: 290 -> 240 us per launch)
+            return launch_gemm<2, LIMBS, YBF16, false, Q4>(st, a, nullptr);
     }
 }
 
@@ -1359,7 +1362,7 @@ hipError_t launch_gemm_mb(hipStream_t st, stream_args& a, int mb) {
 int pick_mb(const stream_args& a) {
     int maxR = 0;
     for (int g = 0; g < a.n_items; ++g) maxR = a.it[g].R > maxR ? a.it[g].R : maxR;
-    for (int mb : {4, 2}) {
+    for (int mb : {2}) {
         if (maxR <= 16 * mb) continue;     // tile would be more than half empty
         long long tiles = 0;
         for (int g = 0; g < a.n_items; ++g) tiles += (long long)((a.it[g].R + 32 * mb - 1) / (32 * mb)) * ((a.it[g].n_blocks + 3) / 4);
