@@ -486,47 +486,38 @@ __device__ __forceinline__ void mfma_chunk(i32x16 (&acc)[LIMBS][MB], const i32x4
         for (int mb = 0; mb < MB; ++mb) acc[l][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[CC][l][mb], wv, acc[l][mb], 0, 0, 0);
 }
 
-// 4-bit weights: one 16-byte load holds the wave's two chunks of the tile (low / high nibbles); the group's scale
-// rides along in w[1].x.  The tile's integer sums are complete for the group (a K tile is one group of 128), so they
-// are scaled and added to the fp32 totals right away: tot += s_g * (128 * <hi, q> + <lo, q>).
-template <int LIMBS, int MB>
-__device__ __forceinline__ void compute_tile_q4(f32x16 (&tot)[MB], const u32x4 (&w)[2], const unsigned char* smem, int stage, int kh, int l32,
-                                                int h) {
-    constexpr int BM = 32 * MB;
-    i32x4 fr[2][LIMBS][MB];
+// 4-bit weights: a 16-byte load holds two K chunks of the tile (low / high nibbles), two loads the whole tile.  The
+// tile's integer sums are complete for the group (a K tile is one group of 128), so they are scaled and added to the
+// fp32 totals right away: tot += s_g * (128 * <hi, q> + <lo, q>).
+// 4-bit weights: wave (n, mh) owns channels 32n.. for the rows 32mh.. of the tile over the WHOLE K tile (no K split
+// between waves; in the 32-row tile only waves 0..3 multiply).  The group's integer sums are scaled into fp32 on the
+// vector ALU, three operations per output; a K split would have both waves of a pair scale a partial sum for every
+// output of the pair, twice the vector-ALU work, which is what bounds this format -- and with the whole group summed
+// in integers before it is scaled, a row's result does not depend on the tile height.
+template <int LIMBS, int BM>
+__device__ __forceinline__ void compute_tile_q4_rows(f32x16& tot, const u32x4 (&w)[2], float sg, const unsigned char* smem, int stage, int mh,
+                                                     int l32, int h) {
+    i32x4 fr[4][LIMBS];
 #pragma unroll
-    for (int cc = 0; cc < 2; ++cc)
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int l = 0; l < LIMBS; ++l)
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                fr[cc][l][mb] = *reinterpret_cast<const i32x4*>(smem + ((size_t)((stage * LIMBS + l) * BM + mb * 32 + l32)) * LROW +
-                                                                (2 * kh + cc) * 32 + 16 * h);
+            fr[c][l] = *reinterpret_cast<const i32x4*>(smem + ((size_t)((stage * LIMBS + l) * BM + mh * 32 + l32)) * LROW + c * 32 + 16 * h);
     const u32x4 m4 = {0x0f0f0f0fu, 0x0f0f0f0fu, 0x0f0f0f0fu, 0x0f0f0f0fu};
-    const i32x4 wlo = (i32x4)(w[0] & m4), whi = (i32x4)((w[0] >> 4) & m4);
-    const float sg = __uint_as_float(w[1][0]);
+    const i32x4 wq[4] = {(i32x4)(w[0] & m4), (i32x4)((w[0] >> 4) & m4), (i32x4)(w[1] & m4), (i32x4)((w[1] >> 4) & m4)};
     const i32x16 zero = {0};
+    i32x16 t[LIMBS];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        i32x16 t[LIMBS];
+    for (int l = 0; l < LIMBS; ++l) {
+        t[l] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[0][l], wq[0], zero, 0, 0, 0);
 #pragma unroll
-        for (int l = 0; l < LIMBS; ++l) {
-            t[l] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[0][l][mb], wlo, zero, 0, 0, 0);
-            t[l] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[1][l][mb], whi, t[l], 0, 0, 0);
-        }
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int comb = LIMBS == 2 ? (t[0][q] << 7) + t[LIMBS - 1][q] : t[0][q];   // |t| < 2^17 per tile: no overflow
-            tot[mb][q] = fmaf(sg, (float)comb, tot[mb][q]);
-        }
+        for (int c = 1; c < 4; ++c) t[l] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[c][l], wq[c], t[l], 0, 0, 0);
     }
-}
-
-// wbase: the wave's n-block in k chunk 0 (wave-uniform); wstride_b: bytes from one k chunk to the next
-__device__ __forceinline__ void load_w_q4(u32x4 (&w)[2], rsrc_t wbase, uint32_t wstride_b, rsrc_t sbase, uint32_t sstride_b,
-                                          uint32_t lane16, uint32_t lane4, int kt, int kh) {
-    w[0] = load16(wbase, lane16, (uint32_t)(kt * 2 + kh) * wstride_b);
-    w[1][0] = __builtin_amdgcn_raw_buffer_load_b32(sbase, lane4, (uint32_t)kt * sstride_b, 0);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int comb = LIMBS == 2 ? (t[0][q] << 7) + t[LIMBS - 1][q] : t[0][q];   // |t| <= 2^17 per tile: no overflow
+        tot[q] = fmaf(sg, (float)comb, tot[q]);
+    }
 }
 
 __device__ __forceinline__ void load_w(u32x4 (&w)[2], rsrc_t wbase, uint32_t wstride_b, uint32_t lane16, int kt, int kh) {
@@ -756,10 +747,7 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
     // 4-bit: the group scale of this lane's channel, [group][channel]
     const rsrc_t sbase = make_rsrc(Q4 ? it.St + (size_t)nbw * 32 : nullptr);
     const uint32_t sstride_b = (uint32_t)it.n_blocks * 32 * 4;
-    auto fetch_w = [&](u32x4 (&w)[2], int kt) {
-        if (Q4) load_w_q4(w, wbase, wstride_b, sbase, sstride_b, lane16, lane4, kt, kh);
-        else load_w(w, wbase, wstride_b, lane16, kt, kh);
-    };
+    auto fetch_w = [&](u32x4 (&w)[2], int kt) { load_w(w, wbase, wstride_b, lane16, kt, kh); };
     // u tile, part 1: the loads, issued ahead of the weight and activation tiles so that they come back first (loads
     // return in order) and the arithmetic of part 2 runs while those tiles are still on their way
     constexpr size_t STG = (size_t)gemm_stages<MB, Q4>() * LIMBS * BM * LROW;
@@ -776,11 +764,25 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
     __builtin_amdgcn_sched_barrier(0);
 
     u32x4 w0[2], w1[2], w2[2], w3[2];
-    fetch_w(w0, 0);
-    fetch_w(w1, 1);
-    if constexpr (Q4) {
-        fetch_w(w2, 2);
-        fetch_w(w3, 3);
+    constexpr bool ROWSPLIT = Q4;                         // 4-bit: waves split the rows of the tile, not K (kh names the row half)
+    static_assert(!Q4 || MB <= 2, "one row block per wave");
+    const bool q4_works = MB == 2 || kh == 0;             // 32-row tile: waves 4..7 only move activation tiles
+    float sg0 = 0.f, sg1 = 0.f, sg2 = 0.f, sg3 = 0.f;     // ROWSPLIT: the group scales travel beside the two nibble vectors
+    auto fetch_q = [&](u32x4 (&w)[2], float& sg, int kt) {
+        w[0] = load16(wbase, lane16, (uint32_t)(kt * 2) * wstride_b);
+        w[1] = load16(wbase, lane16, (uint32_t)(kt * 2 + 1) * wstride_b);
+        sg = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sbase, lane4, (uint32_t)kt * sstride_b, 0));
+    };
+    if constexpr (ROWSPLIT) {
+        if (q4_works) {
+            fetch_q(w0, sg0, 0);
+            fetch_q(w1, sg1, 1);
+            fetch_q(w2, sg2, 2);
+            fetch_q(w3, sg3, 3);
+        }
+    } else {
+        fetch_w(w0, 0);
+        fetch_w(w1, 1);
     }
     u32x4 xa[XV], xb[XV];
     load_x<LIMBS, BM, XV>(xa, xbase, xoff, 0, tid);
@@ -826,22 +828,27 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
     // One step: multiply K tile kt (weights in W), refill W with tile kt+PD, move activation tile kt+1 (in XS)
     // into the other LDS stage and refill XS with tile kt+3.  Tile indices past the end are clamped: that data
     // is fetched again and never used.
-#define ESSA_STEP(W, XS, KTI)                                                        \
+    f32x16 trow = {0};                                    // ROWSPLIT: the wave's own row block (kh names the row half there)
+#define ESSA_STEP(W, SG, XS, KTI)                                                    \
     {                                                                                \
         const int kt_ = (KTI);                                                       \
-        compute_tile_q4<LIMBS, MB>(tot, W, smem, kt_ & 1, kh, l32, h);               \
-        fetch_w(W, min(kt_ + PD, nk - 1));                                           \
+        if (q4_works) {                                                              \
+            compute_tile_q4_rows<LIMBS, BM>(trow, W, SG, smem, kt_ & 1, MB == 2 ? kh : 0, l32, h); \
+            fetch_q(W, SG, min(kt_ + PD, nk - 1));                                   \
+        }                                                                            \
         store_x<LIMBS, BM, XV>(XS, smem, (kt_ + 1) & 1, tid);                        \
         __syncthreads();                                                             \
         load_x<LIMBS, BM, XV>(XS, xbase, xoff, min(kt_ + 3, nk - 1), tid);      \
     }
     for (int kt0 = 0; kt0 < nk; kt0 += PD) {
-        ESSA_STEP(w0, xa, kt0)
-        ESSA_STEP(w1, xb, kt0 + 1)
-        ESSA_STEP(w2, xa, kt0 + 2)
-        ESSA_STEP(w3, xb, kt0 + 3)
+        ESSA_STEP(w0, sg0, xa, kt0)
+        ESSA_STEP(w1, sg1, xb, kt0 + 1)
+        ESSA_STEP(w2, sg2, xa, kt0 + 2)
+        ESSA_STEP(w3, sg3, xb, kt0 + 3)
     }
 #undef ESSA_STEP
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) tot[mb] = trow;        // the epilogue reads the block this wave finishes
     } else {
     // int8 weights.  The MFMAs of a K step run from fragments that were read during the previous step, and the one
     // barrier of a step sits between its two halves.  With four LDS stages (tile j in stage j % 4):
@@ -920,6 +927,7 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
     // exchange slot (n, writer kh, limb, j): 16 x 64 ints, written as [q/4][lane] 16-byte vectors
     constexpr bool FSUM = Q4 || (LIMBS == 2 && !DUMP);       // one fp32 value per element travels instead of the limbs
     auto slot = [&](int n_, int kh_, int l_, int j_) { return smem + ((size_t)((n_ * 2 + kh_) * LIMBS + l_) * MBO + j_) * 4096; };
+    if constexpr (!ROWSPLIT) {
     if (FSUM) {   // the values travel as bit patterns in the accumulator of limb 0
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
@@ -942,7 +950,9 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
                         (i32x4){acc[l][mb][4 * q4], acc[l][mb][4 * q4 + 1], acc[l][mb][4 * q4 + 2], acc[l][mb][4 * q4 + 3]};
             }
         }
+    }
     __syncthreads();
+    if constexpr (!ROWSPLIT) {
 #pragma unroll
     for (int l = 0; l < (FSUM ? 1 : LIMBS); ++l)
 #pragma unroll
@@ -963,6 +973,7 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
                 }
             }
         }
+    }
     if (DUMP) {
         const int o = (nb0 + nw) * 32 + l32;
 #pragma unroll
