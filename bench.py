@@ -260,7 +260,10 @@ def main():
         roof["traffic"] = 74.8e6
     # the library takes its 128 x 256 tile once the group fills the chip twice over with such tiles (int8 weights)
     big_tiles = -(-R // 128) * sum(-(-(-(-p.d_out // 32)) // 8) for p in projs[:4])
-    roof.update({"kernel": "gemm_i8_big_kernel" if (cfg.quant == "int8" and big_tiles >= 512) else "gemm_i8_kernel", "avg_launch_us": avg_s * 1e6, "launches": gemm_launches,
+    # ... and, for 4-bit weights, its 64 x 256 tile once that gives every CU a workgroup
+    q4_tiles = -(-R // 64) * sum(-(-(-(-p.d_out // 32)) // 8) for p in projs[:4])
+    kernel = "gemm_i8_big_kernel" if (cfg.quant == "int8" and big_tiles >= 512) else ("gemm_q4_wide_kernel" if (cfg.quant != "int8" and q4_tiles >= 256) else "gemm_i8_kernel")
+    roof.update({"kernel": kernel, "avg_launch_us": avg_s * 1e6, "launches": gemm_launches,
                  "flops_per_launch": flops_per_launch, "bytes_per_launch": bytes_per_launch,
                  "achieved_GBs": bytes_per_launch / avg_s / 1e9, "achieved_TFLOPs": flops_per_launch / avg_s / 1e12})
 

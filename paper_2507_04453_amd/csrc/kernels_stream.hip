@@ -1065,6 +1065,204 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
 }
 
 // ------------------------------------------------------------------------------------------------
+// 4-bit weights, once the group fills the chip with tiles of 64 rows x 256 channels.  What bounds this format next to
+// the vector-ALU scaling is the number of 128-byte requests a workgroup sends to the L2 per K tile; with 256 channels
+// per tile the activation limbs (as many bytes per K tile as the nibbles of 256 channels) are asked for half as often
+// as with 128.  Wave n owns channels 32n.. of the tile for both blocks of 32 rows, over the whole K tile: per row
+// block the hi-limb MFMAs, a shift by 7 of their sums, the lo-limb MFMAs on top of them, then one conversion and one
+// FMA with the group's scale per output -- the same integer sum and the same fp32 operations as the narrower tiles,
+// so a row's result does not depend on which kernel took it.  Registers are capped at 128: two workgroups share a CU
+// and overlap each other's MFMA, scaling and LDS phases (the loop itself runs them one after the other).
+// ------------------------------------------------------------------------------------------------
+constexpr int QW_NB = 8;           // 32-channel blocks per tile
+
+template <int LIMBS, bool YBF16, int RB>
+constexpr size_t q4w_smem_bytes() {
+    constexpr int QW_BM = 32 * RB;
+    constexpr size_t stages = (size_t)2 * LIMBS * QW_BM * LROW;
+    constexpr size_t pre = stages + (size_t)QW_BM * UTP * 4 + 32 * UTP * 4;
+    constexpr size_t ctile = (size_t)QW_BM * (128 * (YBF16 ? 2 : 4) + 16);
+    constexpr size_t big = pre > ctile ? pre : ctile;
+    return big + QW_BM * 4 + (size_t)QW_BM * UROW;
+}
+
+template <int LIMBS, bool YBF16, int RB>
+__global__ __launch_bounds__(NT, 4) void gemm_q4_wide_kernel(stream_args a) {
+    constexpr int BM = 32 * RB;
+    constexpr int XV = (LIMBS * BM * 8 + NT - 1) / NT;
+    constexpr size_t BIG = q4w_smem_bytes<LIMBS, YBF16, RB>() - BM * 4 - (size_t)BM * UROW;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float* xd = reinterpret_cast<float*>(smem + BIG);
+    unsigned char* utile = smem + BIG + BM * 4;
+
+    int g = 0;
+#pragma unroll
+    for (int i = 1; i < ESSA_MAX_GROUP; ++i) g += (i < a.n_items && (int)blockIdx.x >= a.tile_start[i]) ? 1 : 0;
+    const fwd_item it = fetch_item(a.it[g]);
+    const int ntile = a.tile_start[g + 1] - a.tile_start[g];
+    int tile = blockIdx.x - a.tile_start[g];
+    if ((ntile & 7) == 0 && (a.tile_start[g] & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);   // an XCD takes a contiguous range of tiles
+    const int R = it.R, dout = it.d_out, dpad = it.d_in_pad, rp = it.rp;
+    const int tiles_m = (R + BM - 1) / BM;
+    const int m0 = (tile % tiles_m) * BM, nb0 = (tile / tiles_m) * QW_NB;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, h = lane >> 5;
+    const int nk = dpad / KT;
+    const int nbw = min(nb0 + wave, it.n_blocks - 1);      // a wave past the last block repeats it; nothing of it is stored
+    const uint32_t wstride_b = (uint32_t)it.n_blocks * 1024;
+    const rsrc_t wbase = make_rsrc(reinterpret_cast<const unsigned char*>(it.Wt) + (size_t)nbw * 1024);
+    const rsrc_t sbase = make_rsrc(it.St + (size_t)nbw * 32);
+    const uint32_t sstride_b = (uint32_t)it.n_blocks * 32 * 4;
+    const uint32_t lane16 = lane * 16, lane4 = l32 * 4;
+    uint32_t xoff[XV];
+    x_lane_offsets<LIMBS, BM, XV>(xoff, dpad, tid);
+    rsrc_t xbase[XV];
+#pragma unroll
+    for (int e = 0; e < XV; ++e) {
+        const int limb = (wave * 64 + NT * e) / (BM * 8);
+        xbase[e] = make_rsrc((limb == 0 ? it.Xh : it.Xl) + (size_t)m0 * dpad);
+    }
+    auto fetch_q = [&](u32x4 (&w)[2], float& sg, int kt) {
+        w[0] = load16(wbase, lane16, (uint32_t)(kt * 2) * wstride_b);
+        w[1] = load16(wbase, lane16, (uint32_t)(kt * 2 + 1) * wstride_b);
+        sg = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sbase, lane4, (uint32_t)kt * sstride_b, 0));
+    };
+
+    // rank-space vectors of the tile's rows and the rows' fixed-point units, then the first tiles
+    constexpr size_t STG = (size_t)2 * LIMBS * BM * LROW;
+    float* tvec = reinterpret_cast<float*>(smem + STG);
+    float* Ms = tvec + BM * UTP;
+    constexpr int EU = (BM * 32 + NT - 1) / NT;
+    u32x4 w0[2], w1[2], xa[XV], xb[XV];
+    float sg0, sg1;
+    {
+        f32x4 tp[EU][2];
+        float sbv[EU], mreg[2];
+        u_tile_loads<BM, EU>(it, m0, tid, tp, sbv, mreg);
+        const float xdreg = as_global(it.xdelta)[min(m0 + min(tid, BM - 1), R - 1)];
+        fetch_q(w0, sg0, 0);
+        fetch_q(w1, sg1, min(1, nk - 1));
+        load_x<LIMBS, BM, XV>(xa, xbase, xoff, 0, tid);
+        u_tile_finish<BM, EU>(it, a.flags, tid, tp, sbv, mreg, tvec, Ms, utile);
+        if (tid < BM) xd[tid] = xdreg;
+    }
+    store_x<LIMBS, BM, XV>(xa, smem, 0, tid);
+    load_x<LIMBS, BM, XV>(xa, xbase, xoff, min(1, nk - 1), tid);
+    load_x<LIMBS, BM, XV>(xb, xbase, xoff, min(2, nk - 1), tid);
+    __syncthreads();
+
+    f32x16 tot[RB];
+#pragma unroll
+    for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) tot[mb][q] = 0.f;
+    const u32x4 m4 = {0x0f0f0f0fu, 0x0f0f0f0fu, 0x0f0f0f0fu, 0x0f0f0f0fu};
+    const i32x16 zero = {0};
+    // One step: multiply K tile kt (weights in W), refill W with tile kt+2, move activation tile kt+1 (in XS) into the
+    // other LDS stage and refill XS with tile kt+3.  Tile indices past the end are clamped: fetched again, never used.
+#define Q4W_STEP(W, SG, XS, KTI)                                                                                   \
+    {                                                                                                              \
+        const int kt_ = (KTI);                                                                                     \
+        const i32x4 wq_[4] = {(i32x4)(W[0] & m4), (i32x4)((W[0] >> 4) & m4), (i32x4)(W[1] & m4), (i32x4)((W[1] >> 4) & m4)}; \
+        const unsigned char* st_ = smem + (size_t)((kt_ & 1) * LIMBS) * BM * LROW + (size_t)l32 * LROW + 16 * h;    \
+        _Pragma("unroll") for (int mb = 0; mb < RB; ++mb) {                                                         \
+            i32x16 t_ = zero;                                                                                      \
+            _Pragma("unroll") for (int l = 0; l < LIMBS; ++l) {                                                    \
+                if (l == 1) { _Pragma("unroll") for (int q = 0; q < 16; ++q) t_[q] <<= 7; }                        \
+                _Pragma("unroll") for (int c = 0; c < 4; ++c) {                                                    \
+                    const i32x4 fr_ = *reinterpret_cast<const i32x4*>(st_ + (size_t)(l * BM + mb * 32) * LROW + c * 32); \
+                    t_ = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr_, wq_[c], t_, 0, 0, 0);                          \
+                }                                                                                                  \
+            }                                                                                                      \
+            _Pragma("unroll") for (int q = 0; q < 16; ++q) tot[mb][q] = fmaf(SG, (float)t_[q], tot[mb][q]);        \
+        }                                                                                                          \
+        fetch_q(W, SG, min(kt_ + 2, nk - 1));                                                                      \
+        store_x<LIMBS, BM, XV>(XS, smem, (kt_ + 1) & 1, tid);                                                      \
+        __syncthreads();                                                                                           \
+        load_x<LIMBS, BM, XV>(XS, xbase, xoff, min(kt_ + 3, nk - 1), tid);                                         \
+    }
+    for (int kt0 = 0; kt0 < nk; kt0 += 2) {                // d_in_pad is a multiple of 512: nk is even
+        Q4W_STEP(w0, sg0, xa, kt0)
+        Q4W_STEP(w1, sg1, xb, kt0 + 1)
+    }
+#undef Q4W_STEP
+
+    // ---- epilogue, one half of the tile (128 channels, four waves) at a time
+    constexpr int CROW = 128 * (YBF16 ? 2 : 4) + 16;
+    const int oc = min(nbw * 32 + l32, dout - 1);
+    u32x4 ubf[2][2];
+    {
+        const uint16_t* bp = it.UB16 + (size_t)oc * 2 * rp + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            ubf[ks][0] = ubf[ks][1] = (u32x4){0, 0, 0, 0};
+            if (ks * 16 < rp) {
+                ubf[ks][0] = *as_global(reinterpret_cast<const u32x4*>(bp + ks * 16));
+                ubf[ks][1] = *as_global(reinterpret_cast<const u32x4*>(bp + rp + ks * 16));
+            }
+        }
+    }
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        const rv_piece<YBF16> rvp = load_rv_piece<YBF16>(it, nb0 * 32 + half * 128, tid);
+        if ((wave >> 2) == half) {
+#pragma unroll
+            for (int mb = 0; mb < RB; ++mb) {
+                f32x16 v;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int rl = mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+                    v[q] = (a.flags & ESSA_LORA_ONLY) ? 0.f : tot[mb][q] * xd[rl];
+                }
+                if (!(a.flags & ESSA_LORA_ONLY)) {
+                    // zero-point term of the asymmetric format, - sum_g (s z)[o,g] * (delta_i * sum_{k in g} x^[i,k]): one more
+                    // low-rank product over the groups, bf16 head+tail operands straight from memory
+                    const int Gp = it.Gp;
+                    const uint16_t* xs = it.XS16 + (size_t)min(m0 + mb * 32 + l32, R - 1) * 2 * Gp + 8 * h;
+                    const uint16_t* sz = it.SZ16 + (size_t)(nbw * 32 + l32) * 2 * Gp + 8 * h;
+                    for (int ks = 0; ks < Gp / 16; ++ks) {
+                        const bf16x8 xa_hi = *as_global(reinterpret_cast<const bf16x8*>(xs + ks * 16));
+                        const bf16x8 xa_lo = *as_global(reinterpret_cast<const bf16x8*>(xs + Gp + ks * 16));
+                        const bf16x8 zb_hi = *as_global(reinterpret_cast<const bf16x8*>(sz + ks * 16));
+                        const bf16x8 zb_lo = *as_global(reinterpret_cast<const bf16x8*>(sz + Gp + ks * 16));
+                        v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa_lo, zb_hi, v, 0, 0, 0);
+                        v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa_hi, zb_lo, v, 0, 0, 0);
+                        v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa_hi, zb_hi, v, 0, 0, 0);
+                    }
+                }
+                if (!(a.flags & ESSA_BASE_ONLY)) {
+                    // rank-r term U_B u_i: bf16 head+tail operands, lo*hi + hi*lo + hi*hi per 16 rank columns
+                    const unsigned char* up = utile + (size_t)(mb * 32 + l32) * UROW + 16 * h;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        if (ks * 16 < rp) {
+                            const bf16x8 ua_hi = *reinterpret_cast<const bf16x8*>(up + ks * 32);
+                            const bf16x8 ua_lo = *reinterpret_cast<const bf16x8*>(up + 2 * rp + ks * 32);
+                            const bf16x8 ub_hi = __builtin_bit_cast(bf16x8, ubf[ks][0]);
+                            const bf16x8 ub_lo = __builtin_bit_cast(bf16x8, ubf[ks][1]);
+                            v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_lo, ub_hi, v, 0, 0, 0);
+                            v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_hi, ub_lo, v, 0, 0, 0);
+                            v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_hi, ub_hi, v, 0, 0, 0);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int rl = mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+                    unsigned char* dst = smem + (size_t)rl * CROW + ((wave & 3) * 32 + l32) * (YBF16 ? 2 : 4);
+                    if (YBF16) *reinterpret_cast<uint16_t*>(dst) = f32_to_bf16_bits(v[q]);
+                    else *reinterpret_cast<float*>(dst) = v[q];
+                }
+            }
+        }
+        __syncthreads();
+        store_ctile<YBF16, BM>(smem, it, m0, nb0 * 32 + half * 128, (nb0 >> 2) + half, tid, rvp);
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // The same product for prefill-sized row counts.  Tile = 128 rows x 256 channels; the 8 waves form a 2 (rows) x 4
 // (channels) grid and each owns a 64 x 64 patch, i.e. 2 x 2 MFMA blocks per limb with no K split: every activation
 // fragment meets two weight fragments and every weight fragment four activation fragments (both limbs), so a K
@@ -1309,6 +1507,28 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
     }
 }
 
+template <int LIMBS, bool YBF16, int RB>
+hipError_t launch_gemm_q4_wide(hipStream_t st, stream_args& a) {
+    int total = 0;
+    for (int g = 0; g < a.n_items; ++g) {
+        a.tile_start[g] = total;
+        total += ((a.it[g].R + 32 * RB - 1) / (32 * RB)) * ((a.it[g].n_blocks + QW_NB - 1) / QW_NB);
+    }
+    a.tile_start[a.n_items] = total;
+    constexpr size_t smem = q4w_smem_bytes<LIMBS, YBF16, RB>();
+    static_assert(2 * smem <= 160 * 1024, "two workgroups share the LDS of a CU");
+    auto kern = gemm_q4_wide_kernel<LIMBS, YBF16, RB>;
+    static bool attr_done = false;   // one flag per instantiation
+    if (!attr_done && smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    if (tl_ev_start) hipExtLaunchKernelGGL(kern, dim3(total), dim3(NT), (uint32_t)smem, st, tl_ev_start, tl_ev_stop, 0, a);
+    else hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a);
+    return hipGetLastError();
+}
+
 template <int LIMBS, bool YBF16>
 hipError_t launch_gemm_big(hipStream_t st, stream_args& a) {
     int total = 0;
@@ -1382,6 +1602,14 @@ int pick_mb(const stream_args& a) {
     return 1;     // fewer tiles than CUs either way: the 32-row tile gives twice as many workgroups and loads less per K tile
 }
 
+// 4-bit weights: rows per 256-channel tile, 0 = the group is too small for these tiles.  (A 32-row tile of the same
+// width fills the last round of workgroups better on the 72B shapes and runs no faster: 214 us either way.)
+int pick_q4_wide(const stream_args& a) {
+    long long tiles = 0;
+    for (int g = 0; g < a.n_items; ++g) tiles += (long long)((a.it[g].R + 63) / 64) * ((a.it[g].n_blocks + QW_NB - 1) / QW_NB);
+    return tiles >= 256 ? 64 : 0;
+}
+
 // the 128 x 256 tile pays off once it fills the chip a few times over
 bool takes_big(const stream_args& a) {
     long long tiles = 0;
@@ -1421,11 +1649,13 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
     tl_ev_start = ev_start;
     tl_ev_stop = ev_stop;
     hipError_t e;
+    const int q4_rows = items[0].quant == ESSA_QUANT_INT4_G128 ? pick_q4_wide(a) : 0;   // all items of a call share the weight format
     if (items[0].quant != ESSA_QUANT_INT4_G128 && takes_big(a)) {
         if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_big<2, true>(st, a) : launch_gemm_big<2, false>(st, a);
         else e = y_dtype == ESSA_BF16 ? launch_gemm_big<1, true>(st, a) : launch_gemm_big<1, false>(st, a);
-    } else
-    if (items[0].quant == ESSA_QUANT_INT4_G128)   // all items of a call share the weight format
+    } else if (q4_rows == 64)
+        e = y_dtype == ESSA_BF16 ? launch_gemm_q4_wide<2, true, 2>(st, a) : launch_gemm_q4_wide<2, false, 2>(st, a);
+    else if (items[0].quant == ESSA_QUANT_INT4_G128)
         e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true, true>(st, a, mb) : launch_gemm_mb<2, false, true>(st, a, mb);
     else if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true, false>(st, a, mb) : launch_gemm_mb<2, false, false>(st, a, mb);
     else e = y_dtype == ESSA_BF16 ? launch_gemm_mb<1, true, false>(st, a, mb) : launch_gemm_mb<1, false, false>(st, a, mb);
