@@ -503,6 +503,56 @@ def test_forward_large_row_count_tile(essa, ctx):
     gp.close()
 
 
+def test_forward_int4_wide_tile(essa, ctx):
+    """4-bit weights with enough rows and channels for the 64 x 256 tile: ragged rows (the last row tile is partly
+    empty) and channels (the last tile's blocks past d_out), both ranks paddings, both output types, the reward partials
+    of every 128-channel block, the rank-r term and the base alone; and the same rows through the narrow tiles (a single
+    small launch) give the same bits."""
+    d_in, d_out, R = 256, 8232, 500                      # 258 blocks of 32 channels -> 33 column tiles x 8 row tiles
+    for r, K in ((8, 5), (32, 9)):
+        _say("int4 wide tile: d_in=%d d_out=%d R=%d r=%d" % (d_in, d_out, R, r))
+        p = wl.make_projection("t", d_in, d_out, r, "int4", layer=6, proj=r)
+        W, f = oracle_proj(p)
+        gp = gpu_proj(essa, ctx, p)
+        sA, sB = candidate_sigmas(f, K, 0.05)
+        xb, xv = wl.make_x_bf16(R, d_in, x_id=12)
+        r2c = np.random.default_rng(3).integers(0, K, R).astype(np.int32)
+        ref = orc.svdlora_forward(W, f, xv, r2c, sA, sB)
+        Xd, rd, sAd, sBd = bf16_dev(xb), to_dev(r2c), to_dev(sA), to_dev(sB)
+        Y32 = torch.empty(R, d_out, device="cuda")
+        essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32)
+        e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref)
+        _say("  fp32 out: max %.3g rms %.3g" % (e_max, e_rms))
+        assert e_rms <= LIMB_RMS and e_max <= LIMB_MAX
+        Y16 = torch.empty(R, d_out, device="cuda", dtype=torch.bfloat16)
+        v = wl.reward_vector(d_out, 6, 1)
+        nblk = (d_out + essa.REWARD_BLOCK - 1) // essa.REWARD_BLOCK
+        rowpart = torch.full((nblk + 1, R), float("nan"), device="cuda")
+        grp = essa.ForwardGroup([(gp, Xd, rd, sAd, sBd, Y16)], [to_dev(v)])
+        assert essa.essa_svdlora_forward_reward_group(ctx, grp, None, rowpart) == nblk
+        ref16 = orc.round_to_bf16(ref)
+        e_max, e_rms = orc.rel_errors(bf16_host(Y16), ref16)
+        _say("  bf16 out: max %.3g rms %.3g" % (e_max, e_rms))
+        assert e_rms <= BF16_RMS and e_max <= BF16_MAX
+        assert not torch.isnan(rowpart[:nblk]).any() and torch.isnan(rowpart[nblk]).all()
+        F = torch.zeros(K, device="cuda")
+        essa.essa_reward_finish(ctx, rowpart, nblk, rd, F)
+        F_ref = orc.reward_accumulate(np.zeros(K), ref16, v, r2c, K)
+        assert np.all(np.abs(F.cpu().numpy() - F_ref) <= _reward_bound(ref16, v, r2c, K, 2e-3))
+        essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, essa.LORA_ONLY)
+        e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), orc.svdlora_forward(W, f, xv, r2c, sA, sB, lora_only=True))
+        assert e_rms <= 1e-4 and e_max <= 1e-3
+        essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, essa.BASE_ONLY)
+        e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), xv.astype(np.float64) @ W.T)
+        assert e_rms <= LIMB_RMS and e_max <= LIMB_MAX
+        # 40 of the rows alone: too few tiles for the wide kernel, so the 64 x 128 tiles take them -- same bits
+        sub = slice(123, 163)
+        Ysub = torch.empty(40, d_out, device="cuda", dtype=torch.bfloat16)
+        essa.essa_svdlora_forward(ctx, gp, Xd[sub].contiguous(), rd[sub].contiguous(), sAd, sBd, Ysub)
+        assert torch.equal(Ysub, Y16[sub])
+        gp.close()
+
+
 def test_forward_paper_sweep_values_mixed_group(essa, ctx):
     """The population sizes, ranks and alpha of the paper's sweeps (Appendix, hyperparameter study: K in 24..400, r down to
     2, alpha < 1) in ONE grouped launch with mixed ranks and mixed weight formats: candidates sampled from seeds, only the
