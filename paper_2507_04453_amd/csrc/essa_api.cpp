@@ -906,9 +906,13 @@ extern "C" essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uin
         ESSA_TRY(essa_ws_reserve(ctx, off_Z + align256((size_t)mu * n * 4)));
         int32_t* order = (int32_t*)ctx->ws;
         float* Z = (float*)((char*)ctx->ws + off_Z);
-        ESSA_HIP(essa_k::rank_rewards(ctx->stream, rewards, K, order));
+        if (K <= essa_k::kRankInKernelMax) {
+            ESSA_HIP(essa_k::normals_scaled(ctx->stream, seeds, nullptr, mu, n, nullptr, Z, nullptr, rewards, K, order));
+        } else {
+            ESSA_HIP(essa_k::rank_rewards(ctx->stream, rewards, K, order));
+            ESSA_HIP(essa_k::normals_scaled(ctx->stream, seeds, order, mu, n, nullptr, Z, nullptr));
+        }
         if (order_out) ESSA_HIP(hipMemcpyAsync(order_out, order, (size_t)K * 4, hipMemcpyDeviceToDevice, ctx->stream));
-        ESSA_HIP(essa_k::normals_scaled(ctx->stream, seeds, order, mu, n, nullptr, Z, nullptr));
         ESSA_HIP(essa_k::mean_step(ctx->stream, Z, nullptr, 1.0 / mu, mu, n, cma->sc, 1, cma->m));
         return ESSA_OK;
     }
@@ -935,9 +939,11 @@ extern "C" essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uin
     float* S = (float*)((char*)ctx->ws + off_S);
     float* BY = (float*)((char*)ctx->ws + off_BY);
     float* Z = (float*)((char*)ctx->ws + off_Z);
-    ESSA_HIP(essa_k::rank_rewards(ctx->stream, rewards, K, order));
+    // the ranking: inside the kernel that regenerates the normals when the population is small, else a launch of its own
+    const bool rank_inside = K <= essa_k::kRankInKernelMax;
+    if (!rank_inside) ESSA_HIP(essa_k::rank_rewards(ctx->stream, rewards, K, order));
+    ESSA_HIP(essa_k::cma_build_rhs(ctx->stream, seeds, order, rank_inside ? rewards : nullptr, cma->weights, c, cma->D, S, Z));
     if (order_out) ESSA_HIP(hipMemcpyAsync(order_out, order, (size_t)K * 4, hipMemcpyDeviceToDevice, ctx->stream));
-    ESSA_HIP(essa_k::cma_build_rhs(ctx->stream, seeds, order, cma->weights, c, cma->D, S, Z));
     if (cma->kind == ESSA_OPT_SEP_CMA) {
         // B = I: the rows of S are the y_i, z_w and y_w themselves
         ESSA_HIP(essa_k::cma_vectors(ctx->stream, c, cma->weights, S, cma->m, cma->p_sigma, cma->p_c, cma->sc));

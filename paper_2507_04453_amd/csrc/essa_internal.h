@@ -105,8 +105,11 @@ void essa_host_thin_svd(const double* G, int m, int r, double* U, double* s, dou
 namespace essa_k {
 hipError_t philox_words(hipStream_t st, const uint32_t* seeds, int K, int n_blocks, uint32_t* out);
 // S[k, :] = D * z_k (z optionally stored too)
+// rank_F: null, or rank_K <= 256 rewards whose ranking (written to rank_order as well) replaces sel
+constexpr int kRankInKernelMax = 256;
 hipError_t normals_scaled(hipStream_t st, const uint32_t* seeds, const int32_t* sel /*null or [J]*/, int J, int n,
-                          const float* D /*null = 1*/, float* S, float* z_out);
+                          const float* D /*null = 1*/, float* S, float* z_out, const float* rank_F = nullptr, int rank_K = 0,
+                          int32_t* rank_order = nullptr);
 // theta[k, l] = m[l] + s_k sigma (D ? D[l] : 1) z[l];  pairs: candidate k uses seeds[k / 2] and s_k = +1, -1, else seeds[k], +1
 hipError_t sample_diag(hipStream_t st, const uint32_t* seeds, int K, int n, const float* m, const float* D,
                        const essa_cma_scalars* sc, int pairs, float* theta, float* z_out);
@@ -131,7 +134,8 @@ struct cma_consts {
     float w_sum;               // sum of the ny weights (1 without negative weights)
 };
 // S rows 0..ny-1 = D*z_sel, row ny = z_w (the mu positive weights applied), row ny+1 = D*z_w; needs order
-hipError_t cma_build_rhs(hipStream_t st, const uint32_t* seeds, const int32_t* order, const float* w,
+// rewards non-null: the ranking is taken inside (c.K <= kRankInKernelMax) and written to order; else order is read
+hipError_t cma_build_rhs(hipStream_t st, const uint32_t* seeds, int32_t* order, const float* rewards, const float* w,
                          const cma_consts& c, const float* D, float* S, float* Z /*[ny,n] scratch*/);
 hipError_t cma_vectors(hipStream_t st, const cma_consts& c, const float* w, const float* BY /*[ny+2,n]*/,
                        float* m, float* p_sigma, float* p_c, essa_cma_scalars* sc);

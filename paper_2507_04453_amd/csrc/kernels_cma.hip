@@ -257,9 +257,10 @@ hipError_t rank_rewards(hipStream_t st, const float* F, int K, int32_t* order) {
     return hipGetLastError();
 }
 
-hipError_t cma_build_rhs(hipStream_t st, const uint32_t* seeds, const int32_t* order, const float* w, const cma_consts& c,
+hipError_t cma_build_rhs(hipStream_t st, const uint32_t* seeds, int32_t* order, const float* rewards, const float* w, const cma_consts& c,
                          const float* D, float* S, float* Z) {
-    hipError_t e = normals_scaled(st, seeds, order, c.ny, c.n, D, S, Z);
+    hipError_t e = rewards ? normals_scaled(st, seeds, nullptr, c.ny, c.n, D, S, Z, rewards, c.K, order)
+                           : normals_scaled(st, seeds, order, c.ny, c.n, D, S, Z);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(weighted_rowsum_kernel, dim3((c.n + 255) / 256), dim3(256), 0, st, Z, w, D, c.mu, c.n, S + (size_t)c.ny * c.n,
                        S + (size_t)(c.ny + 1) * c.n);

@@ -42,13 +42,38 @@ __global__ void philox_words_kernel(const uint32_t* __restrict__ seeds, int K, i
 }
 
 // S[j, l] = D[l] * z_{cand(j)}[l],  cand(j) = sel ? sel[j] : j ; optional copy of z itself.
-__global__ void normals_scaled_kernel(const uint32_t* __restrict__ seeds, const int32_t* __restrict__ sel, int J, int n,
-                                      const float* __restrict__ D, float* __restrict__ S, float* __restrict__ z_out) {
+// With rank_F the selection is the ranking of rank_K <= 256 rewards (larger first, ties by index, NaN last), which every
+// workgroup works out for itself in LDS -- a few hundred comparisons instead of a kernel launch of its own; the first
+// workgroup also writes it to rank_order.
+__global__ __launch_bounds__(256) void normals_scaled_kernel(const uint32_t* __restrict__ seeds, const int32_t* __restrict__ sel, int J, int n,
+                                                            const float* __restrict__ D, float* __restrict__ S, float* __restrict__ z_out,
+                                                            const float* __restrict__ rank_F, int rank_K, int32_t* __restrict__ rank_order) {
+    __shared__ float key[256];
+    __shared__ int ord[256];
+    if (rank_F) {
+        const int i = threadIdx.x;
+        if (i < rank_K) {
+            const float f = rank_F[i];
+            key[i] = (f != f) ? -INFINITY : f;
+        }
+        __syncthreads();
+        if (i < rank_K) {
+            const float mine = key[i];
+            int better = 0;
+            for (int j = 0; j < rank_K; ++j) {
+                const float o = key[j];
+                better += (o > mine) || (o == mine && j < i);
+            }
+            ord[better] = i;
+            if (blockIdx.x == 0 && rank_order) rank_order[better] = i;
+        }
+        __syncthreads();
+    }
     const int nb = (n + 3) / 4;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long long)J * nb) return;
     const int j = (int)(idx / nb), c = (int)(idx % nb);
-    const int cand = sel ? sel[j] : j;
+    const int cand = rank_F ? ord[j] : (sel ? sel[j] : j);
     const uint4 w = philox4x32_10(make_uint4((uint32_t)c, 0u, 0u, 0u), make_uint2(seeds[cand], 0u));
     float z[4];
     box_muller(w.x, w.y, z[0], z[1]);
@@ -185,9 +210,10 @@ hipError_t philox_words(hipStream_t st, const uint32_t* seeds, int K, int n_bloc
 }
 
 hipError_t normals_scaled(hipStream_t st, const uint32_t* seeds, const int32_t* sel, int J, int n, const float* D, float* S,
-                          float* z_out) {
+                          float* z_out, const float* rank_F, int rank_K, int32_t* rank_order) {
     const long long total = (long long)J * ((n + 3) / 4);
-    hipLaunchKernelGGL(normals_scaled_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, seeds, sel, J, n, D, S, z_out);
+    hipLaunchKernelGGL(normals_scaled_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, seeds, sel, J, n, D, S, z_out, rank_F,
+                       rank_K, rank_order);
     return hipGetLastError();
 }
 
