@@ -31,8 +31,8 @@ def log(*a):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--mode", choices=["w8a16", "w8a8"], default="w8a16", help="w8a16: bf16 activations as two int8 limbs on the int8 MFMA (default path); w8a8: one int8 limb")
     ap.add_argument("--workload", choices=["c2_7b_decode", "c3_32b_prefill", "c4_72b_decode", "c5_7b_es_iter"], default="c2_7b_decode",
                     help="c2 is the configuration the headline metric is quoted on; the others are side measurements")
