@@ -50,6 +50,11 @@ struct stream_args {
     int n_items;
     unsigned flags;
     int limbs;
+    // prep kernel, interleaved order (every item has the same row count and K slices; 0 in per_rb = off): the workgroups
+    // of one block of 32 rows sit side by side in the grid -- per distinct X the 16 that quantise its rows, then per K
+    // slice one per item -- so that a row is fetched from memory once and found in the caches by the others
+    int inter_per_rb, inter_nown, inter_slices;
+    int inter_owner[ESSA_MAX_GROUP];       // the items that quantise
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
@@ -123,20 +128,42 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     static_assert(offsetof(stream_args, lora_start) == offsetof(stream_args, quant_start) + NG * sizeof(int) &&
                   offsetof(stream_args, flags) == offsetof(stream_args, quant_start) + (2 * NG + 1) * sizeof(int) &&
                   offsetof(stream_args, limbs) == offsetof(stream_args, flags) + sizeof(int), "tables and scalars are adjacent");
-    int tab[2 * NG + 3];
+    static_assert(offsetof(stream_args, inter_per_rb) == offsetof(stream_args, limbs) + sizeof(int) &&
+                  offsetof(stream_args, inter_owner) == offsetof(stream_args, limbs) + 4 * sizeof(int), "order fields follow");
+    int tab[2 * NG + 3 + 3 + ESSA_MAX_GROUP];
     fetch_words(a.quant_start, tab);
+    const int a_nitems = tab[2 * NG];
     const unsigned a_flags = (unsigned)tab[2 * NG + 1];
     const int a_limbs = tab[2 * NG + 2];
-    const int n_qblocks = tab[NG - 1];
-    const bool quant_role = b < n_qblocks;
-    const int lb = b - n_qblocks;
-    int g = 0, first = 0;
+    const int per_rb = tab[2 * NG + 3], nown = tab[2 * NG + 4], islices = tab[2 * NG + 5];
+    bool quant_role;
+    int g = 0, first = 0, lb = 0;
+    int rel = 0;          // quant role: index of the row pair inside the item; other role: (row block) * slices + slice
+    if (per_rb > 0) {
+        const int rb = b / per_rb, rem = b % per_rb;
+        quant_role = rem < 16 * nown;
+        if (quant_role) {
+            const int oi = rem >> 4;
 #pragma unroll
-    for (int i = 1; i < ESSA_MAX_GROUP; ++i) {
-        const int start = quant_role ? tab[i] : tab[NG + i];
-        const bool past = (quant_role ? b : lb) >= start;
-        g += past ? 1 : 0;
-        first = past ? start : first;
+            for (int i = 0; i < ESSA_MAX_GROUP; ++i) g = i == oi ? tab[2 * NG + 6 + i] : g;
+            rel = rb * 16 + (rem & 15);
+        } else {
+            const int e = rem - 16 * nown;
+            g = e % a_nitems;
+            rel = rb * islices + e / a_nitems;
+        }
+    } else {
+        const int n_qblocks = tab[NG - 1];
+        quant_role = b < n_qblocks;
+        lb = b - n_qblocks;
+#pragma unroll
+        for (int i = 1; i < ESSA_MAX_GROUP; ++i) {
+            const int start = quant_role ? tab[i] : tab[NG + i];
+            const bool past = (quant_role ? b : lb) >= start;
+            g += past ? 1 : 0;
+            first = past ? start : first;
+        }
+        rel = (quant_role ? b : lb) - first;
     }
     const fwd_item it = fetch_item(a.it[g]);
     if (quant_role) {
@@ -144,7 +171,7 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         PSTAMP(0) PSTAMP(7)
         // ---- (a) row quantisation: this 256-thread group takes row 2*b' + grp of its item ---------------
         const int grp = tid >> 8, t256 = tid & 255;
-        const int i = (b - first) * 2 + grp;
+        const int i = rel * 2 + grp;
         const bool live = i < it.R;
         const int din = it.d_in, dpad = it.d_in_pad;
         const gptr<const u32x4> xrow = as_global(reinterpret_cast<const u32x4*>((const uint16_t*)it.X + (size_t)(live ? i : 0) * din));
@@ -236,7 +263,7 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     const int role_ = 2; (void)role_;
     PSTAMP(0) PSTAMP(7)
     const int S = it.tslices;
-    const int r0 = ((lb - first) / S) * 32, slice = (lb - first) % S;
+    const int r0 = (rel / S) * 32, slice = rel % S;
     const int l32 = lane & 31, h = lane >> 5;
     const int din = it.d_in, rp = it.rp, nbv = rp / 16, R = it.R;
     f32x16 acc0 = {0}, acc1 = {0};
@@ -1618,7 +1645,22 @@ bool takes_big(const stream_args& a) {
     return tiles >= 512;
 }
 
-void fill_prep_tables(stream_args& a) {
+// returns the grid size of the prep kernel
+int fill_prep_tables(stream_args& a) {
+    // interleaved order when every item has the same rows and slices and the rows do not fit the caches as a whole
+    // (at decode sizes the order makes no difference to the traffic, and the plain one is a little faster)
+    bool same = a.n_items > 0 && a.it[0].R >= 2048;
+    int nown = 0;
+    for (int g = 0; g < a.n_items; ++g) {
+        same = same && a.it[g].R == a.it[0].R && a.it[g].tslices == a.it[0].tslices;
+        if (a.it[g].x_owner) a.inter_owner[nown++] = g;
+    }
+    a.inter_per_rb = 0;
+    if (same && a.n_items > 0) {
+        a.inter_nown = nown;
+        a.inter_slices = a.it[0].tslices;
+        a.inter_per_rb = 16 * nown + a.n_items * a.it[0].tslices;
+    }
     int q = 0, l = 0;
     for (int g = 0; g < a.n_items; ++g) {
         a.quant_start[g] = q;
@@ -1630,6 +1672,7 @@ void fill_prep_tables(stream_args& a) {
         a.quant_start[g] = q;
         a.lora_start[g] = l;
     }
+    return a.inter_per_rb > 0 ? ((a.it[0].R + 31) / 32) * a.inter_per_rb : q + l;
 }
 
 }  // namespace
@@ -1643,8 +1686,8 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
     a.n_items = n_items;
     a.flags = flags;
     a.limbs = (flags & ESSA_COMPUTE_W8A8) ? 1 : 2;
-    fill_prep_tables(a);
-    hipLaunchKernelGGL(prep_kernel, dim3(a.quant_start[n_items] + a.lora_start[n_items]), dim3(PREP_NT), 0, st, a);
+    const int prep_blocks = fill_prep_tables(a);
+    hipLaunchKernelGGL(prep_kernel, dim3(prep_blocks), dim3(PREP_NT), 0, st, a);
     const int mb = pick_mb(a);
     tl_ev_start = ev_start;
     tl_ev_stop = ev_stop;
