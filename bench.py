@@ -8,7 +8,8 @@ activations, r=16, 32 candidates x 8 sequences x 1 token = 256 rows; 822 MB of w
 256 MB Infinity Cache) -> synthetic reward -> rank-weighted CMA-ES update.  A candidate-token is one row
 taken through the four projections of one layer, so a step processes 28 * 256 of them.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value, unit, ms_per_step, config, roofline (of the dominant kernel, timed with HIP
+events on the launch stream) and cpu_baseline (the CPU oracle on a bounded sample of the same workload).
 """
 import argparse
 import json

@@ -654,7 +654,7 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
 
 // int8 weights, bf16 activations, 16-byte rows: the int8-limb kernels take the item
 static bool takes_stream(const essa_k::fwd_item& k, int x_dtype, unsigned flags) {
-    // at most 8 K slices of 1024 in the rank-space partial sums
+    // at most 8 K slices in the rank-space partial sums: 512 columns each up to d_in 4096, 1024 beyond
     return k.Wt && x_dtype == ESSA_BF16 && k.d_in % 16 == 0 && k.d_in <= 8192 && !(flags & ESSA_COMPUTE_BF16) && ((uintptr_t)k.X & 15) == 0 &&
            !(k.quant == ESSA_QUANT_INT4_G128 && (flags & ESSA_COMPUTE_W8A8));
 }

@@ -51,8 +51,9 @@ struct stream_args {
     unsigned flags;
     int limbs;
     // prep kernel, interleaved order (every item has the same row count and K slices; 0 in per_rb = off): the workgroups
-    // of one block of 32 rows sit side by side in the grid -- per distinct X the 16 that quantise its rows, then per K
-    // slice one per item -- so that a row is fetched from memory once and found in the caches by the others
+    // of one block of 32 rows sit side by side in the grid -- per distinct X those that quantise its rows (4 of eight
+    // rows each, or 16 of two rows each), then per K slice one per item -- so that a row is fetched from memory once and
+    // found in the caches by the others
     int inter_per_rb, inter_nown, inter_slices;
     int inter_owner[ESSA_MAX_GROUP];       // the items that quantise
 };
@@ -106,7 +107,8 @@ __device__ __forceinline__ void fetch_words(const int* p, int (&out)[N]) {
 
 // ------------------------------------------------------------------------------------------------
 // prep kernel (512 threads): two kinds of workgroups in one launch.
-//  (a) quantise two activation rows into limbs, one row per 256 threads (once per distinct X of the group);
+//  (a) quantise two activation rows into limbs, one row per 256 threads (once per distinct X of the group); at row
+//      counts in the thousands and rows up to 4096 wide, eight rows, one per wave;
 //  (b) for one item, 32 rows and one K slice: the partial t = V_A^T x by bf16 MFMA against the head+tail copy of
 //      V_A; each of the 8 waves takes 64 columns per 512 of the slice and the 8 partial tiles are summed through
 //      LDS in a fixed order.  The GEMM kernel adds the slices up and turns t into u = sB_c * (M (sA_c * t)).
@@ -115,6 +117,82 @@ __device__ __forceinline__ void fetch_words(const int* p, int (&out)[N]) {
 // ------------------------------------------------------------------------------------------------
 constexpr int PREP_NT = 512;
 using essa_k::prep_slice_cols;
+
+// Row quantisation at row counts in the thousands: one wave per row, the whole row in the wave's registers (NK
+// 16-byte chunks per lane, all asked for at once), the row maximum by shuffles alone.  No barrier and no LDS, so a
+// workgroup keeps eight rows in flight instead of two; the arithmetic per element is that of the two-row form.  It pays
+// for rows up to 4096 wide; beyond, with more arithmetic per wave between its loads and its stores, the two-row form is
+// the faster one.
+template <int NK>
+__device__ __forceinline__ void quantise_row_wave(const fwd_item& it, int i, int lane, int a_limbs) {
+    typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+    const int din = it.d_in, dpad = it.d_in_pad;
+    const int nch = din / 8, kd = dpad / 512;             // 16-byte chunks of the row; trips of 64 chunks up to the padded width
+    const gptr<const u32x4> xrow = as_global(reinterpret_cast<const u32x4*>((const uint16_t*)it.X + (size_t)i * din));
+    u32x4 xr[NK];
+#pragma unroll
+    for (int k = 0; k < NK; ++k) xr[k] = xrow[min(64 * k + lane, nch - 1)];     // clamped: no branch between the loads
+    __builtin_amdgcn_sched_barrier(0);
+    float m = 0.f;
+#pragma unroll
+    for (int k = 0; k < NK; ++k) {
+        if (64 * k + lane >= nch) xr[k] = (u32x4){0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            m = fmaxf(m, fabsf(__uint_as_float(xr[k][e] << 16)));
+            m = fmaxf(m, fabsf(__uint_as_float(xr[k][e] & 0xffff0000u)));
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    const float amax = m;
+    const float top = a_limbs == 2 ? 16383.0f : 127.0f;
+    const float inv = amax > 0.f ? top / amax : 0.f;
+    const gptr<u32x2> hrow = as_global_w(reinterpret_cast<u32x2*>(it.Xh + (size_t)i * dpad));
+    const gptr<u32x2> lrow = as_global_w(reinterpret_cast<u32x2*>(it.Xl + (size_t)i * dpad));
+    const gptr<uint16_t> xs16 = as_global_w(it.XS16);
+#pragma unroll
+    for (int k = 0; k < NK; ++k) {
+        if (k >= kd) break;                                // wave-uniform: chunks up to the padded width quantise zeros
+        const int c = 64 * k + lane;
+        uint32_t hi[2] = {0, 0}, lo[2] = {0, 0};
+        int qsum = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float x = (e & 1) ? __uint_as_float(xr[k][e >> 1] & 0xffff0000u) : __uint_as_float(xr[k][e >> 1] << 16);
+            float q = rintf(x * inv);
+            q = fminf(fmaxf(q, -top), top);
+            const int qi = (int)q;
+            qsum += qi;
+            if (a_limbs == 2) {
+                hi[e >> 2] |= (uint32_t)((qi >> 7) & 0xff) << (8 * (e & 3));
+                lo[e >> 2] |= (uint32_t)(qi & 127) << (8 * (e & 3));
+            } else {
+                hi[e >> 2] |= (uint32_t)(qi & 0xff) << (8 * (e & 3));
+            }
+        }
+        hrow[c] = (u32x2){hi[0], hi[1]};
+        if (a_limbs == 2) lrow[c] = (u32x2){lo[0], lo[1]};
+        if (it.quant == ESSA_QUANT_INT4_G128) {
+            int gs = qsum;                                 // a group of 128 columns is 16 consecutive lanes of one trip
+#pragma unroll
+            for (int off = 8; off > 0; off >>= 1) gs += __shfl_xor(gs, off, 64);
+            const int grp16 = c >> 4;
+            if ((lane & 15) == 0 && grp16 < it.Gp) {
+                const float xs = (amax > 0.f ? amax / top : 0.f) * (float)gs;
+                const uint16_t xh = f32_to_bf16_bits(xs);
+                xs16[(size_t)i * 2 * it.Gp + grp16] = xh;
+                xs16[(size_t)i * 2 * it.Gp + it.Gp + grp16] = f32_to_bf16_bits(xs - bf16_bits_to_f32(xh));
+            }
+        }
+    }
+    if (it.quant == ESSA_QUANT_INT4_G128)
+        for (int gq = dpad / 128 + lane; gq < it.Gp; gq += 64) {
+            xs16[(size_t)i * 2 * it.Gp + gq] = 0;
+            xs16[(size_t)i * 2 * it.Gp + it.Gp + gq] = 0;
+        }
+    if (lane == 0) as_global_w(it.xdelta)[i] = amax > 0.f ? amax / top : 0.f;
+}
 
 __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     __shared__ __attribute__((aligned(16))) float part[8][2][16][64];   // lora role: partial tiles of the 8 waves (64 KB)
@@ -136,19 +214,20 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     const unsigned a_flags = (unsigned)tab[2 * NG + 1];
     const int a_limbs = tab[2 * NG + 2];
     const int per_rb = tab[2 * NG + 3], nown = tab[2 * NG + 4], islices = tab[2 * NG + 5];
+    const int qw = per_rb > 0 ? (per_rb - a_nitems * islices) / nown : 0;    // quantising workgroups per owner and block of 32 rows
     bool quant_role;
     int g = 0, first = 0, lb = 0;
     int rel = 0;          // quant role: index of the row pair inside the item; other role: (row block) * slices + slice
     if (per_rb > 0) {
         const int rb = b / per_rb, rem = b % per_rb;
-        quant_role = rem < 16 * nown;
+        quant_role = rem < qw * nown;
         if (quant_role) {
-            const int oi = rem >> 4;
+            const int oi = rem / qw;
 #pragma unroll
             for (int i = 0; i < ESSA_MAX_GROUP; ++i) g = i == oi ? tab[2 * NG + 6 + i] : g;
-            rel = rb * 16 + (rem & 15);
+            rel = rb * qw + rem % qw;                       // 4: eight rows each, one per wave; 16: two rows each
         } else {
-            const int e = rem - 16 * nown;
+            const int e = rem - qw * nown;
             g = e % a_nitems;
             rel = rb * islices + e / a_nitems;
         }
@@ -166,6 +245,11 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
         rel = (quant_role ? b : lb) - first;
     }
     const fwd_item it = fetch_item(a.it[g]);
+    if (quant_role && qw == 4) {
+        const int i = rel * 8 + wave;
+        if (i < it.R) quantise_row_wave<8>(it, i, lane, a_limbs);
+        return;
+    }
     if (quant_role) {
         const int role_ = 1; (void)role_;
         PSTAMP(0) PSTAMP(7)
@@ -552,8 +636,8 @@ __device__ __forceinline__ void load_w(u32x4 (&w)[2], rsrc_t wbase, uint32_t wst
     for (int cc = 0; cc < 2; ++cc) w[cc] = load16(wbase, lane16, (uint32_t)(kt * 4 + 2 * kh + cc) * wstride_b);
 }
 
-// LDS stages of the activation tiles: four where they fit (the tile of K step j sits in stage j % 4 and can be
-// written before the step's barrier), two for the 128-row tile
+// LDS stages of the activation tiles: four for int8 weights (the tile of K step j sits in stage j % 4 and can be
+// written before the step's barrier), two for 4-bit weights
 template <int MB, bool Q4 = false>
 constexpr int gemm_stages() { return (MB <= 2 && !Q4) ? 4 : 2; }     // the 4-bit loop alternates between two stages
 
@@ -883,9 +967,9 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
     //   barrier: tile kt+1 is complete in LDS, and nobody reads tile kt-1's stage any more
     //   second half (K chunk 1): MFMAs interleaved with the fragment reads of tile kt+1; then the loads of weight
     //   tile kt+PD and activation tile kt+4
-    // so no LDS or memory latency sits between two MFMAs of a wave.  With two stages (128-row tile) tile kt+2 is
-    // written after the barrier instead, into the stage tile kt was read from.  Tile indices past the end are
-    // clamped: that data is fetched again and never used.
+    // so no LDS or memory latency sits between two MFMAs of a wave.  (With only two stages tile kt+2 would be
+    // written after the barrier instead, into the stage tile kt was read from; both tile heights have four.)
+    // Tile indices past the end are clamped: that data is fetched again and never used.
     constexpr int NS = gemm_stages<MB, Q4>();
     constexpr bool EARLY = NS == 4;
     constexpr int NF = LIMBS * MB;                      // MFMAs per K chunk
@@ -1659,7 +1743,11 @@ int fill_prep_tables(stream_args& a) {
     if (same && a.n_items > 0) {
         a.inter_nown = nown;
         a.inter_slices = a.it[0].tslices;
-        a.inter_per_rb = 16 * nown + a.n_items * a.it[0].tslices;
+        // rows up to 4096 wide are quantised eight to a workgroup, one wave each (at 3584 columns the prep launch of
+        // 32768 rows takes 388 us instead of 440); wider rows two to a workgroup (5120 columns: 640 us against 855)
+        bool narrow = true;
+        for (int g = 0; g < a.n_items; ++g) narrow = narrow && a.it[g].d_in <= 4096;
+        a.inter_per_rb = (narrow ? 4 : 16) * nown + a.n_items * a.it[0].tslices;
     }
     int q = 0, l = 0;
     for (int g = 0; g < a.n_items; ++g) {

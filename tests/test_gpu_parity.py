@@ -553,6 +553,51 @@ def test_forward_int4_wide_tile(essa, ctx):
         gp.close()
 
 
+@pytest.mark.parametrize("quant,d_in,d_out,r", [
+    ("int8", 592, 72, 8),        # two trips of 64 chunks per row, the second one ragged
+    ("int8", 3600, 40, 16),      # eight trips, two chunks in the last one
+    ("int8", 6160, 40, 32),      # wider than 4096: two rows per workgroup at this row count too
+    ("int4", 640, 264, 8),       # group sums: five real groups, three in the zero padding
+])
+def test_forward_rows_in_thousands_prep(essa, ctx, quant, d_in, d_out, r):
+    """From 2048 rows on, activation rows up to 4096 wide are quantised one wave per row: ragged row count (the last
+    workgroup's waves past the last row do nothing), row widths that end inside a trip of 64 chunks, both weight formats;
+    and a few of the rows alone (quantised two rows per workgroup) give the same bits."""
+    K, R = 6, 2051
+    _say("rows in thousands: %s d_in=%d d_out=%d r=%d R=%d" % (quant, d_in, d_out, r, R))
+    p = wl.make_projection("t", d_in, d_out, r, quant, layer=7, proj=3)
+    W, f = oracle_proj(p)
+    gp = gpu_proj(essa, ctx, p)
+    sA, sB = candidate_sigmas(f, K, 0.05)
+    xb, xv = wl.make_x_bf16(R, d_in, x_id=13)
+    xb[5] = 0                                              # a row of zeros: unit 0, all limbs 0
+    xv[5] = 0
+    r2c = np.random.default_rng(4).integers(0, K, R).astype(np.int32)
+    ref = orc.svdlora_forward(W, f, xv, r2c, sA, sB)
+    Xd, rd, sAd, sBd = bf16_dev(xb), to_dev(r2c), to_dev(sA), to_dev(sB)
+    Y32 = torch.empty(R, d_out, device="cuda")
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32)
+    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref)
+    _say("  fp32 out: max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= LIMB_RMS and e_max <= LIMB_MAX
+    assert torch.count_nonzero(Y32[5]).item() == 0
+    if quant == "int8":
+        essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32, essa.COMPUTE_W8A8)
+        e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), orc.svdlora_forward_w8a8(p.Wq, p.scales, f, xv, r2c, sA, sB))
+        _say("  w8a8: max %.3g rms %.3g" % (e_max, e_rms))
+        assert e_rms <= EXACT_RMS and e_max <= EXACT_MAX
+    Y16 = torch.empty(R, d_out, device="cuda", dtype=torch.bfloat16)
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y16)
+    e_max, e_rms = orc.rel_errors(bf16_host(Y16), orc.round_to_bf16(ref))
+    assert e_rms <= BF16_RMS and e_max <= BF16_MAX
+    for sub in (slice(0, 40), slice(R - 37, R)):
+        n = sub.stop - sub.start
+        Ysub = torch.empty(n, d_out, device="cuda", dtype=torch.bfloat16)
+        essa.essa_svdlora_forward(ctx, gp, Xd[sub].contiguous(), rd[sub].contiguous(), sAd, sBd, Ysub)
+        assert torch.equal(Ysub, Y16[sub])
+    gp.close()
+
+
 def test_forward_paper_sweep_values_mixed_group(essa, ctx):
     """The population sizes, ranks and alpha of the paper's sweeps (Appendix, hyperparameter study: K in 24..400, r down to
     2, alpha < 1) in ONE grouped launch with mixed ranks and mixed weight formats: candidates sampled from seeds, only the
