@@ -39,6 +39,7 @@ def main():
                     help="c2 is the configuration the headline metric is quoted on; the others are side measurements")
     ap.add_argument("--layers", type=int, default=0, help="distinct layers cycled through (default: 28 for c2/c5, 1 for c3, 8 for c4)")
     ap.add_argument("--rows-per-cand", type=int, default=0)
+    ap.add_argument("--population", type=int, default=0, help="candidates K (default: the workload's); with --rows-per-cand it sets the row count of a sweep point")
     ap.add_argument("--forward-only", action="store_true", help="time only the projections (no sampler / reward / update)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--refresh-basis", action="store_true",
@@ -64,12 +65,12 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(2)
     cfg = wl.CONFIGS[args.workload]
-    hidden, kv, r, K = cfg.hidden, cfg.kv, cfg.r, cfg.K
+    hidden, kv, r, K = cfg.hidden, cfg.kv, cfg.r, args.population or cfg.K
     layers = args.layers or {"c2_7b_decode": 28, "c3_32b_prefill": 1, "c4_72b_decode": 8, "c5_7b_es_iter": 28}[args.workload]
     rows_per = args.rows_per_cand or cfg.rows_per_cand
     if args.workload in ("c3_32b_prefill", "c4_72b_decode"):
         args.forward_only = True        # these configurations name the projections only
-    if args.workload != "c2_7b_decode":
+    if args.workload != "c2_7b_decode" or K != cfg.K:
         args.no_cpu_baseline = True
     quant = essa.QUANT_INT8_PERCH if cfg.quant == "int8" else essa.QUANT_INT4_G128
     R = K * rows_per
@@ -257,7 +258,7 @@ def main():
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
     # HBM-side bytes per GEMM launch from rocprofv3 --pmc (profiles/c2_7b_decode_gemm_i8_hbm_traffic.md: reads scaled by the
     # factor a plain 256 MiB copy gives, 2.0; writes 1.0); measured for the default workload and mode only
-    if args.workload == "c2_7b_decode" and args.mode == "w8a16" and rows_per == cfg.rows_per_cand:
+    if args.workload == "c2_7b_decode" and args.mode == "w8a16" and rows_per == cfg.rows_per_cand and K == cfg.K:
         roof["traffic"] = 74.8e6
     # the library takes its 128 x 256 tile once the group fills the chip twice over with such tiles (int8 weights)
     big_tiles = -(-R // 128) * sum(-(-(-(-p.d_out // 32)) // 8) for p in projs[:4])
