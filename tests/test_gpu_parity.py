@@ -345,6 +345,11 @@ def test_forward_c3_prefill_sampled(essa, ctx):
     _layer_case(essa, ctx, wl.CONFIGS["c3_32b_prefill"], layer=0, n_cands_checked=6, rows_per_cand_checked=6)
 
 
+def test_forward_c5_layer_sampled(essa, ctx):
+    _say("c5: one 7B-shaped layer at the 32768 rows of the full iteration, sampled rows of 5 candidates")
+    _layer_case(essa, ctx, wl.CONFIGS["c5_7b_es_iter"], layer=2, n_cands_checked=5, rows_per_cand_checked=6)
+
+
 def test_forward_c4_int4_interleaved_sampled(essa, ctx):
     _say("c4: 72B-shaped int4 decode layer, interleaved rows, sampled candidates")
     _layer_case(essa, ctx, wl.CONFIGS["c4_72b_decode"], layer=0, n_cands_checked=5, rows_per_cand_checked=4)
