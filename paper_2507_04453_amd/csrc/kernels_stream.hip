@@ -1269,6 +1269,7 @@ __global__ __launch_bounds__(NT, 4) void gemm_q4_wide_kernel(stream_args a) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) tot[mb][q] = 0.f;
     const u32x4 m4 = {0x0f0f0f0fu, 0x0f0f0f0fu, 0x0f0f0f0fu, 0x0f0f0f0fu};
+    constexpr int FD = 3;                                 // fragments in flight ahead of their MFMA
     const i32x16 zero = {0};
     // One step: multiply K tile kt (weights in W), refill W with tile kt+2, move activation tile kt+1 (in XS) into the
     // other LDS stage and refill XS with tile kt+3.  Tile indices past the end are clamped: fetched again, never used.
@@ -1277,16 +1278,27 @@ __global__ __launch_bounds__(NT, 4) void gemm_q4_wide_kernel(stream_args a) {
         const int kt_ = (KTI);                                                                                     \
         const i32x4 wq_[4] = {(i32x4)(W[0] & m4), (i32x4)((W[0] >> 4) & m4), (i32x4)(W[1] & m4), (i32x4)((W[1] >> 4) & m4)}; \
         const unsigned char* st_ = smem + (size_t)((kt_ & 1) * LIMBS) * BM * LROW + (size_t)l32 * LROW + 16 * h;    \
-        _Pragma("unroll") for (int mb = 0; mb < RB; ++mb) {                                                         \
-            i32x16 t_ = zero;                                                                                      \
-            _Pragma("unroll") for (int l = 0; l < LIMBS; ++l) {                                                    \
-                if (l == 1) { _Pragma("unroll") for (int q = 0; q < 16; ++q) t_[q] <<= 7; }                        \
-                _Pragma("unroll") for (int c = 0; c < 4; ++c) {                                                    \
-                    const i32x4 fr_ = *reinterpret_cast<const i32x4*>(st_ + (size_t)(l * BM + mb * 32) * LROW + c * 32); \
-                    t_ = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr_, wq_[c], t_, 0, 0, 0);                          \
-                }                                                                                                  \
+        /* the step's fragments in the order of their MFMAs (row block, limb, chunk), read FD ahead of their use */ \
+        constexpr int NFR_ = RB * LIMBS * 4;                                                                       \
+        i32x4 fr_[FD];                                                                                             \
+        _Pragma("unroll") for (int i_ = 0; i_ < FD; ++i_)                                                          \
+            fr_[i_] = *reinterpret_cast<const i32x4*>(st_ + (size_t)(((i_ >> 2) % LIMBS) * BM + (i_ / (4 * LIMBS)) * 32) * LROW + (i_ & 3) * 32); \
+        __builtin_amdgcn_sched_barrier(0);                                                                         \
+        i32x16 t_ = zero;                                                                                          \
+        _Pragma("unroll") for (int i_ = 0; i_ < NFR_; ++i_) {                                                      \
+            const int mb_ = i_ / (4 * LIMBS), l_ = (i_ >> 2) % LIMBS, c_ = i_ & 3;                                 \
+            if (c_ == 0 && l_ == 0) t_ = zero;                                                                     \
+            if (c_ == 0 && l_ == 1) { _Pragma("unroll") for (int q = 0; q < 16; ++q) t_[q] <<= 7; }                \
+            t_ = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr_[i_ % FD], wq_[c_], t_, 0, 0, 0);                        \
+            if (i_ + FD < NFR_) {                                                                                  \
+                const int n_ = i_ + FD;                                                                            \
+                fr_[i_ % FD] = *reinterpret_cast<const i32x4*>(st_ + (size_t)(((n_ >> 2) % LIMBS) * BM + (n_ / (4 * LIMBS)) * 32) * LROW + (n_ & 3) * 32); \
             }                                                                                                      \
-            _Pragma("unroll") for (int q = 0; q < 16; ++q) tot[mb][q] = fmaf(SG, (float)t_[q], tot[mb][q]);        \
+            __builtin_amdgcn_sched_barrier(0);                                                                     \
+            if (c_ == 3 && l_ == LIMBS - 1) {                                                                      \
+                _Pragma("unroll") for (int q = 0; q < 16; ++q) tot[mb_][q] = fmaf(SG, (float)t_[q], tot[mb_][q]);  \
+                __builtin_amdgcn_sched_barrier(0);                                                                 \
+            }                                                                                                      \
         }                                                                                                          \
         fetch_q(W, SG, min(kt_ + 2, nk - 1));                                                                      \
         store_x<LIMBS, BM, XV>(XS, smem, (kt_ + 1) & 1, tid);                                                      \
