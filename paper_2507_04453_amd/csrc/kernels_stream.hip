@@ -56,6 +56,10 @@ struct stream_args {
     // found in the caches by the others
     int inter_per_rb, inter_nown, inter_slices;
     int inter_owner[ESSA_MAX_GROUP];       // the items that quantise
+    // 64 x 256 kernel for 4-bit weights: rows below q4_big_rows go in 64-row tiles (tile_start), the rows from there on in
+    // 32-row tiles (q4_small_start), which come last in the grid
+    int q4_big_rows;
+    int q4_small_start[ESSA_MAX_GROUP + 1];
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
@@ -1198,7 +1202,7 @@ constexpr size_t q4w_smem_bytes() {
 }
 
 template <int LIMBS, bool YBF16, int RB>
-__global__ __launch_bounds__(NT, 4) void gemm_q4_wide_kernel(stream_args a) {
+__device__ __forceinline__ void q4w_tile(const stream_args& a, const fwd_item& it, const int m0, const int nb0) {
     constexpr int BM = 32 * RB;
     constexpr int XV = (LIMBS * BM * 8 + NT - 1) / NT;
     constexpr size_t BIG = q4w_smem_bytes<LIMBS, YBF16, RB>() - BM * 4 - (size_t)BM * UROW;
@@ -1206,16 +1210,7 @@ __global__ __launch_bounds__(NT, 4) void gemm_q4_wide_kernel(stream_args a) {
     float* xd = reinterpret_cast<float*>(smem + BIG);
     unsigned char* utile = smem + BIG + BM * 4;
 
-    int g = 0;
-#pragma unroll
-    for (int i = 1; i < ESSA_MAX_GROUP; ++i) g += (i < a.n_items && (int)blockIdx.x >= a.tile_start[i]) ? 1 : 0;
-    const fwd_item it = fetch_item(a.it[g]);
-    const int ntile = a.tile_start[g + 1] - a.tile_start[g];
-    int tile = blockIdx.x - a.tile_start[g];
-    if ((ntile & 7) == 0 && (a.tile_start[g] & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);   // an XCD takes a contiguous range of tiles
     const int R = it.R, dout = it.d_out, dpad = it.d_in_pad, rp = it.rp;
-    const int tiles_m = (R + BM - 1) / BM;
-    const int m0 = (tile % tiles_m) * BM, nb0 = (tile / tiles_m) * QW_NB;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, h = lane >> 5;
@@ -1382,6 +1377,33 @@ __global__ __launch_bounds__(NT, 4) void gemm_q4_wide_kernel(stream_args a) {
         __syncthreads();
         store_ctile<YBF16, BM>(smem, it, m0, nb0 * 32 + half * 128, (nb0 >> 2) + half, tid, rvp);
         __syncthreads();
+    }
+}
+
+// The grid: the 64-row tiles of all items, then the 32-row tiles of all items.  The launcher gives the rows of a last,
+// sparsely filled round of 64-row tiles to 32-row tiles instead: a round in which one workgroup sits alone on a CU has
+// nobody to overlap its phases with, and twice as many workgroups of half the height finish it in about half the time.
+// A row's result does not depend on the height of its tile.
+template <int LIMBS, bool YBF16>
+__global__ __launch_bounds__(NT, 4) void gemm_q4_wide_kernel(stream_args a) {
+    const int nbig = a.tile_start[a.n_items];
+    const bool small = (int)blockIdx.x >= nbig;
+    const int bb = small ? (int)blockIdx.x - nbig : (int)blockIdx.x;
+    int g = 0;
+#pragma unroll
+    for (int i = 1; i < ESSA_MAX_GROUP; ++i) g += (i < a.n_items && bb >= (small ? a.q4_small_start[i] : a.tile_start[i])) ? 1 : 0;
+    const fwd_item it = fetch_item(a.it[g]);
+    const int start = small ? a.q4_small_start[g] : a.tile_start[g];
+    const int ntile = (small ? a.q4_small_start[g + 1] : a.tile_start[g + 1]) - start;
+    int tile = bb - start;
+    if ((ntile & 7) == 0 && ((start + (small ? nbig : 0)) & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);   // an XCD takes a contiguous range of tiles
+    const int big_rows = min(a.q4_big_rows, (it.R + 63) / 64 * 64);
+    if (!small) {
+        const int tiles_m = big_rows / 64;
+        q4w_tile<LIMBS, YBF16, 2>(a, it, (tile % tiles_m) * 64, (tile / tiles_m) * QW_NB);
+    } else {
+        const int tiles_m = (it.R - big_rows + 31) / 32;
+        q4w_tile<LIMBS, YBF16, 1>(a, it, big_rows + (tile % tiles_m) * 32, (tile / tiles_m) * QW_NB);
     }
 }
 
@@ -1630,25 +1652,50 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
     }
 }
 
-template <int LIMBS, bool YBF16, int RB>
+template <int LIMBS, bool YBF16>
 hipError_t launch_gemm_q4_wide(hipStream_t st, stream_args& a) {
-    int total = 0;
+    // column tiles of the group, and whether all items have the same rows (the split below is one row index for all)
+    int ct = 0;
+    bool same = true;
     for (int g = 0; g < a.n_items; ++g) {
-        a.tile_start[g] = total;
-        total += ((a.it[g].R + 32 * RB - 1) / (32 * RB)) * ((a.it[g].n_blocks + QW_NB - 1) / QW_NB);
+        ct += (a.it[g].n_blocks + QW_NB - 1) / QW_NB;
+        same = same && a.it[g].R == a.it[0].R;
     }
-    a.tile_start[a.n_items] = total;
-    constexpr size_t smem = q4w_smem_bytes<LIMBS, YBF16, RB>();
+    const int R0 = a.it[0].R, nrt = (R0 + 63) / 64;
+    // two workgroups per CU: 512 at a time.  When the 64-row tiles end in a round that is at most a quarter full, the
+    // last row tiles of every column are cut into 32-row tiles, so that the 64-row tiles fill whole rounds only.
+    constexpr int SLOTS = 512;
+    int small_rt = 0;                                   // 64-row tiles per column that are cut in two
+    const long long all = (long long)nrt * ct;
+    if (same && all > SLOTS && all % SLOTS != 0 && all % SLOTS <= SLOTS / 4) {
+        small_rt = (int)((all % SLOTS + ct - 1) / ct);
+        if (small_rt >= nrt) small_rt = 0;
+    }
+    a.q4_big_rows = same ? (nrt - small_rt) * 64 : 0x7fffffc0;
+    int total = 0, total_s = 0;
+    for (int g = 0; g < a.n_items; ++g) {
+        const int cols = (a.it[g].n_blocks + QW_NB - 1) / QW_NB;
+        const int big_rows = std::min(a.q4_big_rows, (a.it[g].R + 63) / 64 * 64);
+        a.tile_start[g] = total;
+        a.q4_small_start[g] = total_s;
+        total += (big_rows / 64) * cols;
+        total_s += ((a.it[g].R - std::min(a.it[g].R, big_rows) + 31) / 32) * cols;
+    }
+    for (int g = a.n_items; g <= ESSA_MAX_GROUP; ++g) {
+        a.tile_start[g] = total;
+        a.q4_small_start[g] = total_s;
+    }
+    constexpr size_t smem = q4w_smem_bytes<LIMBS, YBF16, 2>();
     static_assert(2 * smem <= 160 * 1024, "two workgroups share the LDS of a CU");
-    auto kern = gemm_q4_wide_kernel<LIMBS, YBF16, RB>;
+    auto kern = gemm_q4_wide_kernel<LIMBS, YBF16>;
     static bool attr_done = false;   // one flag per instantiation
     if (!attr_done && smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    if (tl_ev_start) hipExtLaunchKernelGGL(kern, dim3(total), dim3(NT), (uint32_t)smem, st, tl_ev_start, tl_ev_stop, 0, a);
-    else hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a);
+    if (tl_ev_start) hipExtLaunchKernelGGL(kern, dim3(total + total_s), dim3(NT), (uint32_t)smem, st, tl_ev_start, tl_ev_stop, 0, a);
+    else hipLaunchKernelGGL(kern, dim3(total + total_s), dim3(NT), smem, st, a);
     return hipGetLastError();
 }
 
@@ -1725,8 +1772,9 @@ int pick_mb(const stream_args& a) {
     return 1;     // fewer tiles than CUs either way: the 32-row tile gives twice as many workgroups and loads less per K tile
 }
 
-// 4-bit weights: rows per 256-channel tile, 0 = the group is too small for these tiles.  (A 32-row tile of the same
-// width fills the last round of workgroups better on the 72B shapes and runs no faster: 214 us either way.)
+// 4-bit weights: rows per 256-channel tile, 0 = the group is too small for these tiles.  (32-row tiles of the same
+// width throughout fill the last round of workgroups better on the 72B shapes and run no faster, 214 us either way:
+// only the rows of a sparsely filled last round get them, see launch_gemm_q4_wide.)
 int pick_q4_wide(const stream_args& a) {
     long long tiles = 0;
     for (int g = 0; g < a.n_items; ++g) tiles += (long long)((a.it[g].R + 63) / 64) * ((a.it[g].n_blocks + QW_NB - 1) / QW_NB);
@@ -1797,7 +1845,7 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
         if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_big<2, true>(st, a) : launch_gemm_big<2, false>(st, a);
         else e = y_dtype == ESSA_BF16 ? launch_gemm_big<1, true>(st, a) : launch_gemm_big<1, false>(st, a);
     } else if (q4_rows == 64)
-        e = y_dtype == ESSA_BF16 ? launch_gemm_q4_wide<2, true, 2>(st, a) : launch_gemm_q4_wide<2, false, 2>(st, a);
+        e = y_dtype == ESSA_BF16 ? launch_gemm_q4_wide<2, true>(st, a) : launch_gemm_q4_wide<2, false>(st, a);
     else if (items[0].quant == ESSA_QUANT_INT4_G128)
         e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true, true>(st, a, mb) : launch_gemm_mb<2, false, true>(st, a, mb);
     else if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_mb<2, true, false>(st, a, mb) : launch_gemm_mb<2, false, false>(st, a, mb);

@@ -558,6 +558,48 @@ def test_forward_int4_wide_tile(essa, ctx):
         gp.close()
 
 
+def test_forward_int4_wide_tile_mixed_heights(essa, ctx):
+    """4-bit weights, 9 x 58 = 522 tiles of 64 x 256 on 512 places: the last 64 rows of every column go in 32-row tiles
+    instead (ragged: 570 rows, the last 32-row tile holds 26; the last column tile ends inside a 32-channel block).
+    Both outputs, the reward partials, and rows from either kind of tile alone through the narrow tiles: same bits."""
+    d_in, d_out, R, r, K = 256, 14824, 570, 16, 7
+    _say("int4 wide tile, mixed heights: d_in=%d d_out=%d R=%d" % (d_in, d_out, R))
+    p = wl.make_projection("t", d_in, d_out, r, "int4", layer=8, proj=1)
+    W, f = oracle_proj(p)
+    gp = gpu_proj(essa, ctx, p)
+    sA, sB = candidate_sigmas(f, K, 0.05)
+    xb, xv = wl.make_x_bf16(R, d_in, x_id=14)
+    r2c = np.random.default_rng(5).integers(0, K, R).astype(np.int32)
+    ref = orc.svdlora_forward(W, f, xv, r2c, sA, sB)
+    Xd, rd, sAd, sBd = bf16_dev(xb), to_dev(r2c), to_dev(sA), to_dev(sB)
+    Y32 = torch.empty(R, d_out, device="cuda")
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, Y32)
+    e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref)
+    _say("  fp32 out: max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= LIMB_RMS and e_max <= LIMB_MAX
+    Y16 = torch.empty(R, d_out, device="cuda", dtype=torch.bfloat16)
+    v = wl.reward_vector(d_out, 8, 1)
+    nblk = (d_out + essa.REWARD_BLOCK - 1) // essa.REWARD_BLOCK
+    rowpart = torch.full((nblk + 1, R), float("nan"), device="cuda")
+    grp = essa.ForwardGroup([(gp, Xd, rd, sAd, sBd, Y16)], [to_dev(v)])
+    assert essa.essa_svdlora_forward_reward_group(ctx, grp, None, rowpart) == nblk
+    ref16 = orc.round_to_bf16(ref)
+    e_max, e_rms = orc.rel_errors(bf16_host(Y16), ref16)
+    _say("  bf16 out: max %.3g rms %.3g" % (e_max, e_rms))
+    assert e_rms <= BF16_RMS and e_max <= BF16_MAX
+    assert not torch.isnan(rowpart[:nblk]).any() and torch.isnan(rowpart[nblk]).all()
+    F = torch.zeros(K, device="cuda")
+    essa.essa_reward_finish(ctx, rowpart, nblk, rd, F)
+    F_ref = orc.reward_accumulate(np.zeros(K), ref16, v, r2c, K)
+    assert np.all(np.abs(F.cpu().numpy() - F_ref) <= _reward_bound(ref16, v, r2c, K, 2e-3))
+    for sub in (slice(100, 140), slice(500, 540), slice(R - 30, R)):      # 64-row tiles, both kinds, 32-row tiles
+        n = sub.stop - sub.start
+        Ysub = torch.empty(n, d_out, device="cuda", dtype=torch.bfloat16)
+        essa.essa_svdlora_forward(ctx, gp, Xd[sub].contiguous(), rd[sub].contiguous(), sAd, sBd, Ysub)
+        assert torch.equal(Ysub, Y16[sub])
+    gp.close()
+
+
 @pytest.mark.parametrize("quant,d_in,d_out,r", [
     ("int8", 592, 72, 8),        # two trips of 64 chunks per row, the second one ragged
     ("int8", 3600, 40, 16),      # eight trips, two chunks in the last one
