@@ -175,8 +175,8 @@ __device__ __forceinline__ void quantise_row_wave(const fwd_item& it, int i, int
                 hi[e >> 2] |= (uint32_t)(qi & 0xff) << (8 * (e & 3));
             }
         }
-        hrow[c] = (u32x2){hi[0], hi[1]};
-        if (a_limbs == 2) lrow[c] = (u32x2){lo[0], lo[1]};
+        __builtin_nontemporal_store((u32x2){hi[0], hi[1]}, hrow + c);        // streaming stores, as in the two-row form
+        if (a_limbs == 2) __builtin_nontemporal_store((u32x2){lo[0], lo[1]}, lrow + c);
         if (it.quant == ESSA_QUANT_INT4_G128) {
             int gs = qsum;                                 // a group of 128 columns is 16 consecutive lanes of one trip
 #pragma unroll
@@ -316,8 +316,9 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
                     hi[e >> 2] |= (uint32_t)(qi & 0xff) << (8 * (e & 3));
                 }
             }
-            hrow[c] = (u32x2){hi[0], hi[1]};
-            if (a_limbs == 2) lrow[c] = (u32x2){lo[0], lo[1]};
+            // streaming stores: the limbs are read by the next launch, from behind other L2s than this one
+            __builtin_nontemporal_store((u32x2){hi[0], hi[1]}, hrow + c);
+            if (a_limbs == 2) __builtin_nontemporal_store((u32x2){lo[0], lo[1]}, lrow + c);
             if (it.quant == ESSA_QUANT_INT4_G128) {
                 // sum of the row's fixed-point activations over each group of 128 columns (16 consecutive lanes),
                 // times delta: what the zero-points of the 4-bit format multiply.  Kept as bf16 head + tail.
@@ -785,7 +786,9 @@ __device__ __forceinline__ void store_ctile(const unsigned char* ctile, const fw
         const u32x4 val = *reinterpret_cast<const u32x4*>(src);
         if (valid) {
             if (vec_ok && o + EPV <= dout) {
-                *reinterpret_cast<gptr<u32x4>>(Yb + ((size_t)i * dout + o) * ESZ) = val;
+                // streaming store: the output is not read again by this launch, and lines left dirty in the L2 are written
+                // back when the kernel ends, before the next one may start
+                __builtin_nontemporal_store(val, reinterpret_cast<gptr<u32x4>>(Yb + ((size_t)i * dout + o) * ESZ));
             } else {
                 for (int e = 0; e < EPV && o + e < dout; ++e) {
                     if (YBF16) reinterpret_cast<gptr<uint16_t>>(Yb)[(size_t)i * dout + o + e] = reinterpret_cast<const uint16_t*>(src)[e];
