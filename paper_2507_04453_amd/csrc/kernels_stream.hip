@@ -60,6 +60,10 @@ struct stream_args {
     // 32-row tiles (q4_small_start), which come last in the grid
     int q4_big_rows;
     int q4_small_start[ESSA_MAX_GROUP + 1];
+    // prep kernel, interleaved order only: one workgroup per item and block of 32 rows walks all K slices and leaves the
+    // finished u_i = sB_c * (M (sA_c * V_A^T x_i)) in U16 (bf16 head and tail) instead of the slices' shares in Tpart;
+    // the 128 x 256 kernel then copies its tile of u instead of adding the shares up once per column tile
+    int u_ready;
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
@@ -120,6 +124,7 @@ __device__ __forceinline__ void fetch_words(const int* p, int (&out)[N]) {
 // role are bound by what one CU can load, and twice as many of them with half the columns each halve that time.
 // ------------------------------------------------------------------------------------------------
 constexpr int PREP_NT = 512;
+constexpr int UTP = 36;            // LDS pitch (floats) of the two small matrices (rank-space vectors t, core M)
 using essa_k::prep_slice_cols;
 
 // Row quantisation at row counts in the thousands: one wave per row, the whole row in the wave's registers (NK
@@ -198,7 +203,11 @@ __device__ __forceinline__ void quantise_row_wave(const fwd_item& it, int i, int
     if (lane == 0) as_global_w(it.xdelta)[i] = amax > 0.f ? amax / top : 0.f;
 }
 
-__global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
+// FULLK: the form for row counts in the thousands on their way to the 128 x 256 kernel (role (b) walks all K slices and
+// finishes u); a separate instantiation, capped at 128 registers for two workgroups per CU, so that the decode form
+// keeps its own register allocation.
+template <bool FULLK>
+__global__ __launch_bounds__(PREP_NT, FULLK ? 4 : 1) void prep_kernel(stream_args a) {
     __shared__ __attribute__((aligned(16))) float part[8][2][16][64];   // lora role: partial tiles of the 8 waves (64 KB)
     __shared__ float wred[8];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -351,11 +360,12 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
     // ---- (b) partial t = V_A^T x for 32 rows of one item over one K slice --------------------------------
     const int role_ = 2; (void)role_;
     PSTAMP(0) PSTAMP(7)
+    constexpr int full_k = FULLK ? 1 : 0;                   // this workgroup walks all K slices and finishes u
     const int S = it.tslices;
-    const int r0 = (rel / S) * 32, slice = rel % S;
+    const int r0 = full_k ? rel * 32 : (rel / S) * 32;
+    const int slice_begin = full_k ? 0 : rel % S, slice_end = full_k ? S : slice_begin + 1;
     const int l32 = lane & 31, h = lane >> 5;
     const int din = it.d_in, rp = it.rp, nbv = rp / 16, R = it.R;
-    f32x16 acc0 = {0}, acc1 = {0};
     const int ksteps = din / 16;
     const int scols = prep_slice_cols(din);
     // The candidate's singular values for the (row, j) elements this thread finishes at the end (one for rank 16, two
@@ -376,8 +386,11 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) my_c[i] = as_global(it.row2cand)[min(r0 + e_row[i], R - 1)];
     };
+    float tsum[2] = {0.f, 0.f};                             // full_k: this thread's elements of sA_c * (V_A^T x), slices added in ascending order
+    for (int slice = slice_begin; slice < slice_end; ++slice) {
+    f32x16 acc0 = {0}, acc1 = {0};
     if (a_flags & ESSA_BASE_ONLY) {
-        ask_candidates();
+        if (slice == slice_begin) ask_candidates();
     } else {
         // wave w takes, of every 512 columns of the slice, the four consecutive steps 4w + u, i.e. 64 columns = 128 bytes
         // of each of the 32 rows.  x: four coalesced loads (instruction i: rows 8i..8i+7, whole 128-byte lines), turned
@@ -406,7 +419,7 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
                 for (int u = 0; u < 4; ++u) v1[u] = vt[((size_t)(ks0 + u < ksteps ? ks0 + u : 0) * 2 + 1) * 64];
             }
             __builtin_amdgcn_sched_barrier(0);
-            if (c0 == 0) ask_candidates();
+            if (c0 == 0 && slice == slice_begin) ask_candidates();
             __builtin_amdgcn_sched_barrier(0);              // all loads are out before anything waits for one of them
             if (kbase + ch * 8 >= din) {
 #pragma unroll
@@ -438,11 +451,13 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     }
+    if (slice == slice_begin) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const size_t at = (size_t)my_c[i] * it.sigma_stride + min(e_j[i], it.r - 1);
-        my_sa[i] = as_global(it.sigmaA)[at];
-        my_sb[i] = as_global(it.sigmaB)[at];
+        for (int i = 0; i < 2; ++i) {
+            const size_t at = (size_t)my_c[i] * it.sigma_stride + min(e_j[i], it.r - 1);
+            my_sa[i] = as_global(it.sigmaA)[at];
+            my_sb[i] = as_global(it.sigmaB)[at];
+        }
     }
     lds_barrier();            // the staging patches become the reduction buffer
     PSTAMP(1)
@@ -471,15 +486,59 @@ __global__ __launch_bounds__(PREP_NT) void prep_kernel(stream_args a) {
             }
             // the eight slice slots of an element sit side by side (two 16-byte loads for the GEMM kernel); the slice-0
             // workgroup clears the slots no slice fills
-            const gptr<float> slot = as_global_w(it.Tpart) + ((size_t)(r0 + row) * rp + j) * 8;
-            slot[slice] = (j < it.r ? my_sa[i] : 0.f) * (th[0] + th[1]);
-            if (slice == 0) {
-                for (int sl = S; sl < 8; ++sl) slot[sl] = 0.f;
-                if (r0 + row < R) as_global_w(it.SBrow)[(size_t)(r0 + row) * rp + j] = j < it.r ? my_sb[i] : 0.f;
+            const float share = (j < it.r ? my_sa[i] : 0.f) * (th[0] + th[1]);
+            if (full_k) {
+                tsum[i] = slice == 0 ? share : tsum[i] + share;
+            } else {
+                const gptr<float> slot = as_global_w(it.Tpart) + ((size_t)(r0 + row) * rp + j) * 8;
+                slot[slice] = share;
+                if (slice == 0) {
+                    for (int sl = S; sl < 8; ++sl) slot[sl] = 0.f;
+                    if (r0 + row < R) as_global_w(it.SBrow)[(size_t)(r0 + row) * rp + j] = j < it.r ? my_sb[i] : 0.f;
+                }
             }
         }
     }
+    if (full_k) lds_barrier();     // the partial tiles are read: the memory goes back to the staging patches, or to the finish below
+    }
     PSTAMP(3)
+    if (!full_k) return;
+    // ---- u_i = sB_c * (M t_i) for the 32 rows, with the operations (and their order) of the GEMM kernels' own prologue
+    float* tvec = &part[0][0][0][0];                        // [32][UTP]
+    float* Ms = tvec + 32 * UTP;                            // [rp][UTP]
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int e = tid + PREP_NT * i;
+        if (e < rp * rp) Ms[(e >> rsh) * UTP + (e & (rp - 1))] = as_global(it.M)[e];
+        if (e < 32 * rp) tvec[e_row[i] * UTP + e_j[i]] = tsum[i];
+    }
+    lds_barrier();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        if (tid + PREP_NT * i < 32 * rp) {
+            const int row = e_row[i], j = e_j[i];
+            float u = 0.f;
+            if (!(a_flags & ESSA_BASE_ONLY)) {
+                for (int l0 = 0; l0 < rp; l0 += 16) {
+                    f32x4 mv[4], tv[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        mv[q] = *reinterpret_cast<const f32x4*>(Ms + j * UTP + l0 + 4 * q);
+                        tv[q] = *reinterpret_cast<const f32x4*>(tvec + row * UTP + l0 + 4 * q);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) u = fmaf(mv[q >> 2][q & 3], tv[q >> 2][q & 3], u);
+                }
+                u *= j < it.r ? my_sb[i] : 0.f;
+            }
+            if (r0 + row < R) {
+                const uint16_t hi = f32_to_bf16_bits(u);
+                const gptr<uint16_t> urow = as_global_w(it.U16) + (size_t)(r0 + row) * 2 * rp;
+                urow[j] = hi;
+                urow[rp + j] = f32_to_bf16_bits(u - bf16_bits_to_f32(hi));
+            }
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -661,7 +720,6 @@ constexpr size_t gemm_smem_bytes() {
 // The tile of rank-space vectors u_i = sB_c * (M t_i), t_i = sum over the K slices (ascending) of the prep kernel's
 // sA_c * (V_A^T x_i) shares, kept in LDS as bf16 head+tail rows of UROW bytes.  Two parts, so that a caller can put
 // other loads between them: the global loads, then the arithmetic (which contains one workgroup barrier).
-constexpr int UTP = 36;            // LDS pitch (floats) of the two small matrices
 template <int BM, int EU>
 __device__ __forceinline__ void u_tile_loads(const fwd_item& it, int m0, int tid, f32x4 (&tp)[EU][2], float (&sb)[EU], float (&mreg)[2]) {
     const int R = it.R, rp = it.rp, rpad = (R + 31) / 32 * 32;
@@ -1512,7 +1570,25 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
     float* tvec = reinterpret_cast<float*>(smem + 3 * STAGE);
     float* Ms = tvec + BM * UTP;
     constexpr int EU = (BM * 32 + NT - 1) / NT;
-    {
+    if (a.u_ready) {
+        // the prep kernel has left the finished rows of u (bf16 head, then tail: 4 rp bytes per row): a plain copy
+        const int ppr = rp / 4;                                      // 16-byte pieces per row
+        u32x4 up[2];
+        const gptr<const u32x4> usrc = as_global(reinterpret_cast<const u32x4*>(it.U16));
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int p_ = min(tid + NT * i, BM * ppr - 1), row = p_ / ppr, pc = p_ % ppr;
+            up[i] = usrc[(size_t)min(m0 + row, R - 1) * ppr + pc];
+        }
+        const float xdreg = as_global(it.xdelta)[min(m0 + min(tid, BM - 1), R - 1)];
+        load_tile(xs0, ws0, 0);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int p_ = tid + NT * i;
+            if (p_ < BM * ppr) *reinterpret_cast<u32x4*>(utile + (size_t)(p_ / ppr) * UROW + (p_ % ppr) * 16) = up[i];
+        }
+        if (tid < BM) xd[tid] = xdreg;
+    } else {
         f32x4 tp[EU][2];
         float sbv[EU], mreg[2];
         u_tile_loads<BM, EU>(it, m0, tid, tp, sbv, mreg);
@@ -1793,7 +1869,7 @@ bool takes_big(const stream_args& a) {
 }
 
 // returns the grid size of the prep kernel
-int fill_prep_tables(stream_args& a) {
+int fill_prep_tables(stream_args& a, bool finish_u) {
     // interleaved order when every item has the same rows and slices and the rows do not fit the caches as a whole
     // (at decode sizes the order makes no difference to the traffic, and the plain one is a little faster)
     bool same = a.n_items > 0 && a.it[0].R >= 2048;
@@ -1803,14 +1879,16 @@ int fill_prep_tables(stream_args& a) {
         if (a.it[g].x_owner) a.inter_owner[nown++] = g;
     }
     a.inter_per_rb = 0;
+    a.u_ready = 0;
     if (same && a.n_items > 0) {
+        a.u_ready = finish_u ? 1 : 0;                   // one workgroup per item and row block for all K slices
         a.inter_nown = nown;
-        a.inter_slices = a.it[0].tslices;
+        a.inter_slices = finish_u ? 1 : a.it[0].tslices;
         // rows up to 4096 wide are quantised eight to a workgroup, one wave each (at 3584 columns the prep launch of
         // 32768 rows takes 388 us instead of 440); wider rows two to a workgroup (5120 columns: 640 us against 855)
         bool narrow = true;
         for (int g = 0; g < a.n_items; ++g) narrow = narrow && a.it[g].d_in <= 4096;
-        a.inter_per_rb = (narrow ? 4 : 16) * nown + a.n_items * a.it[0].tslices;
+        a.inter_per_rb = (narrow ? 4 : 16) * nown + a.n_items * a.inter_slices;
     }
     int q = 0, l = 0;
     for (int g = 0; g < a.n_items; ++g) {
@@ -1837,14 +1915,17 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
     a.n_items = n_items;
     a.flags = flags;
     a.limbs = (flags & ESSA_COMPUTE_W8A8) ? 1 : 2;
-    const int prep_blocks = fill_prep_tables(a);
-    hipLaunchKernelGGL(prep_kernel, dim3(prep_blocks), dim3(PREP_NT), 0, st, a);
+    // rows in the thousands on their way to the 128 x 256 kernel: the prep kernel finishes u itself
+    const bool to_big = items[0].quant != ESSA_QUANT_INT4_G128 && takes_big(a);
+    const int prep_blocks = fill_prep_tables(a, to_big);
+    if (a.u_ready) hipLaunchKernelGGL(prep_kernel<true>, dim3(prep_blocks), dim3(PREP_NT), 0, st, a);
+    else hipLaunchKernelGGL(prep_kernel<false>, dim3(prep_blocks), dim3(PREP_NT), 0, st, a);
     const int mb = pick_mb(a);
     tl_ev_start = ev_start;
     tl_ev_stop = ev_stop;
     hipError_t e;
     const int q4_rows = items[0].quant == ESSA_QUANT_INT4_G128 ? pick_q4_wide(a) : 0;   // all items of a call share the weight format
-    if (items[0].quant != ESSA_QUANT_INT4_G128 && takes_big(a)) {
+    if (to_big) {
         if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_big<2, true>(st, a) : launch_gemm_big<2, false>(st, a);
         else e = y_dtype == ESSA_BF16 ? launch_gemm_big<1, true>(st, a) : launch_gemm_big<1, false>(st, a);
     } else if (q4_rows == 64)
@@ -1865,7 +1946,7 @@ hipError_t w8a8_accumulators_stream(hipStream_t st, const fwd_item& it, int32_t*
     a.flags = ESSA_BASE_ONLY | ESSA_COMPUTE_W8A8;
     a.limbs = 1;
     for (int g = 1; g <= ESSA_MAX_GROUP; ++g) a.quant_start[g] = (it.R + 1) / 2;      // quantise only: no rank-space work (lora_start stays zero)
-    hipLaunchKernelGGL(prep_kernel, dim3(a.quant_start[1]), dim3(PREP_NT), 0, st, a);
+    hipLaunchKernelGGL(prep_kernel<false>, dim3(a.quant_start[1]), dim3(PREP_NT), 0, st, a);
     return launch_gemm<2, 1, false, true>(st, a, acc_out);
 }
 
