@@ -271,3 +271,52 @@ def test_ars_follows_the_gradient_of_a_linear_reward():
     new, _ = orc.ars_update(m, seeds, (theta @ g).astype(np.float32), alpha=0.05, b=N)
     step = new - m
     assert step @ g / (np.linalg.norm(step) * np.linalg.norm(g)) > 0.97
+
+
+# ---------------------------------------------------------------- stalled step (h_sigma = 0) of the two other CMA kinds
+def test_active_update_stalled_branch_keeps_the_rank_one_mass():
+    # as for the positive-weight update: with C = p_c p_c^T and h_sigma = 0 the c_1 terms cancel,
+    # C' = (1 - c_mu sum w) C + c_mu sum_i w~_i y_i y_i^T, negative weights rescaled by n / |z_i|^2
+    n, lam = 3, 8
+    rng = np.random.default_rng(31)
+    st = orc.cma_state_init(n, 0.32, rng.standard_normal(n))
+    st.p_c = rng.standard_normal(n)
+    st.C = np.outer(st.p_c, st.p_c)
+    st.p_sigma = np.array([90.0, 0.0, 0.0])
+    st.t = 4
+    seeds = list(range(60, 60 + lam))
+    F = rng.standard_normal(lam)
+    new, order = orc.cma_update_active(st, seeds, F)
+    c = orc.active_cma_constants(n, lam)
+    assert new.extra["h_sigma"] == 0.0
+    np.testing.assert_allclose(new.p_c, (1.0 - c.c_c) * st.p_c, rtol=1e-15)
+    Z = np.stack([orc.normals_from_seed(s, n) for s in seeds]).astype(np.float64)
+    ranked = sorted(range(lam), key=lambda i: -F[i])
+    expect = (1.0 - c.c_mu * c.weights.sum()) * st.C
+    for i, k in enumerate(ranked):
+        w = c.weights[i] if i < c.mu else c.weights[i] * n / float(Z[k] @ Z[k])
+        expect += c.c_mu * w * np.outer(Z[k], Z[k])
+    np.testing.assert_allclose(new.C, expect, rtol=1e-12, atol=1e-15)
+
+
+def test_sep_update_stalled_branch_keeps_the_rank_one_mass():
+    n, lam = 5, 6
+    rng = np.random.default_rng(32)
+    st = orc.sep_cma_init(n, 0.32, rng.standard_normal(n))
+    st.p_c = rng.standard_normal(n)
+    st.c_diag = st.p_c ** 2
+    st.p_sigma = np.zeros(n)
+    st.p_sigma[1] = 200.0
+    st.t = 7
+    seeds = list(range(70, 70 + lam))
+    F = rng.standard_normal(lam)
+    new, order = orc.sep_cma_update(st, seeds, F)
+    c, c_1, c_mu = orc.sep_cma_constants(n, lam)
+    assert new.extra["h_sigma"] == 0.0
+    np.testing.assert_allclose(new.p_c, (1.0 - c.c_c) * st.p_c, rtol=1e-15)
+    Z = np.stack([orc.normals_from_seed(s, n) for s in seeds]).astype(np.float64)
+    ranked = sorted(range(lam), key=lambda i: -F[i])
+    expect = (1.0 - c_mu) * st.c_diag
+    for i in range(c.mu):
+        expect += c_mu * c.weights[i] * st.c_diag * Z[ranked[i]] ** 2          # y = sqrt(c_diag) z
+    np.testing.assert_allclose(new.c_diag, expect, rtol=1e-12)

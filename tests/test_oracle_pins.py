@@ -428,3 +428,133 @@ def test_refresh_basis_keeps_the_sampling_distribution():
     np.testing.assert_allclose(T @ T.T, C, atol=1e-12)
     th, z = orc.sample_candidates(np.zeros(n), 1.0, B, D, [5])
     np.testing.assert_allclose(th[0], T @ z[0], atol=1e-5)
+
+
+# ---------------------------------------------------------------- W8A8 composition, stalled CMA-ES update
+def test_w8a8_forward_hand_worked_case():
+    # One row x = (1, -0.3, 0.26): amax = 1, codes rint(127 x) = (127, -38, 33) worked by hand.  Wq = [[1, 2, 3],
+    # [-4, 5, -6]] gives the integer sums 127 - 76 + 99 = 150 and -508 - 190 - 198 = -896; with channel scales
+    # (0.5, 0.25) the base term is (150 / 127 * 0.5, -896 / 127 * 0.25).  The rank-1 update A = (0, 10, 0),
+    # B = (1, 2)^T at its own singular values adds B A x = 10 * (-0.3) * (1, 2) on the UNQUANTISED x (on the codes it
+    # would be 10 * (-38 / 127) * (1, 2), 0.008 away).
+    Wq = np.array([[1, 2, 3], [-4, 5, -6]], np.int8)
+    ws = np.array([0.5, 0.25], np.float32)
+    A = np.array([[0.0, 10.0, 0.0]])
+    B = np.array([[1.0], [2.0]])
+    f = orc.thin_svd_factors(A, B)
+    assert f["S_A"][0] == pytest.approx(10.0) and f["S_B"][0] == pytest.approx(math.sqrt(5.0))
+    X = np.array([[1.0, -0.3, 0.26]], np.float32)
+    y = orc.svdlora_forward_w8a8(Wq, ws, f, X, np.zeros(1, np.int32), f["S_A"][None], f["S_B"][None])
+    expect = np.array([150.0 / 127.0 * 0.5 - 3.0, -896.0 / 127.0 * 0.25 - 6.0])
+    np.testing.assert_allclose(y[0], expect, rtol=1e-6)
+    assert np.abs(y[0] - (expect + 10 * (0.3 - 38 / 127) * np.array([1.0, 2.0]))).max() > 5e-3   # not the LoRA-on-codes reading
+    # sigma = 0 leaves the base term alone
+    y0 = orc.svdlora_forward_w8a8(Wq, ws, f, X, np.zeros(1, np.int32), np.zeros((1, 1)), f["S_B"][None])
+    np.testing.assert_allclose(y0[0], expect + np.array([3.0, 6.0]), rtol=1e-6)
+
+
+def test_w8a8_forward_within_the_quantisation_bound_of_the_exact_forward():
+    # |x^ - x| <= s_i / 2 per entry, so the W8A8 output sits within (s_i / 2) sum_j |W_deq[o, j]| of the exact forward,
+    # element by element; and it is not the exact forward (the rounding is really there).  A dropped channel scale,
+    # a dropped row scale or a transposed operand leaves the bound by orders of magnitude.
+    p = wl.make_projection("t", 96, 40, 4, "int8", layer=2)
+    W = orc.dequant_int8(p.Wq, p.scales)
+    f = orc.thin_svd_factors(p.A, p.B)
+    K, R = 3, 17
+    g = np.random.default_rng(8)
+    sA = (f["S_A"][None] + 0.05 * g.standard_normal((K, 4))).astype(np.float32)
+    sB = (f["S_B"][None] + 0.05 * g.standard_normal((K, 4))).astype(np.float32)
+    _, xv = wl.make_x_bf16(R, 96, x_id=33)
+    r2c = g.integers(0, K, R).astype(np.int32)
+    y8 = orc.svdlora_forward_w8a8(p.Wq, p.scales, f, xv, r2c, sA, sB)
+    y = orc.svdlora_forward(W, f, xv, r2c, sA, sB)
+    s = np.abs(xv).max(axis=1).astype(np.float64) / 127.0
+    bound = 0.5 * s[:, None] * np.abs(W).sum(axis=1)[None, :]
+    assert np.all(np.abs(y8 - y) <= bound * (1 + 1e-6) + 1e-12)
+    assert np.abs(y8 - y).max() > 1e-3 * bound.max()
+    # statistically the error is that of uniform rounding noise: rms about s sqrt(sum_j W^2 / 12)
+    pred = s[:, None] * np.sqrt((W * W).sum(axis=1) / 12.0)[None, :]
+    ratio = np.sqrt(np.mean((y8 - y) ** 2)) / np.sqrt(np.mean(pred ** 2))
+    assert 0.7 < ratio < 1.3
+
+
+def _stalled_state(n, rng, t=5):
+    """C = p_c p_c^T, B = D = I, |p_sigma| far above the stall threshold (1.4 + 2 / (n + 1)) chi_n."""
+    st = orc.cma_state_init(n, 0.32, rng.standard_normal(n))
+    st.p_c = rng.standard_normal(n)
+    st.C = np.outer(st.p_c, st.p_c)
+    st.p_sigma = np.zeros(n)
+    st.p_sigma[0] = 50.0 * math.sqrt(n)
+    st.t = t
+    return st
+
+
+def test_cma_update_stalled_branch_closed_form():
+    # Tutorial, Eqs. (45)-(47): when |p_sigma| is too long, h_sigma = 0 drops the y_w term from p_c, and the factor of
+    # C gains c_1 c_c (2 - c_c).  Because (1 - c_c)^2 + c_c (2 - c_c) = 1, a state with C = p_c p_c^T then keeps all its
+    # rank-one mass: C' = (1 - c_mu) C + c_mu sum_i w_i y_i y_i^T, with no c_1 in it.  A wrong sign or factor in the
+    # stall term, or a p_c that still takes y_w, breaks the identity.
+    n, lam = 3, 8
+    rng = np.random.default_rng(21)
+    st = _stalled_state(n, rng)
+    seeds = list(range(40, 40 + lam))
+    F = rng.standard_normal(lam)
+    new, order = orc.cma_update(st, seeds, F)
+    c = orc.cma_constants(n, lam)
+    assert new.extra["h_sigma"] == 0.0
+    np.testing.assert_allclose(new.p_c, (1.0 - c.c_c) * st.p_c, rtol=1e-15)
+    Z = np.stack([orc.normals_from_seed(s, n) for s in seeds]).astype(np.float64)       # B = D = I: y = z
+    best = sorted(range(lam), key=lambda i: -F[i])[:c.mu]
+    expect = (1.0 - c.c_mu) * st.C
+    for i in range(c.mu):
+        for a in range(n):
+            for b in range(n):
+                expect[a, b] += c.c_mu * c.weights[i] * Z[best[i], a] * Z[best[i], b]
+    np.testing.assert_allclose(new.C, expect, rtol=1e-12, atol=1e-15)
+    # the same step written out term by term with loops (decay, rank one, rank mu)
+    decay = 1.0 - c.c_1 - c.c_mu + c.c_1 * c.c_c * (2.0 - c.c_c)
+    loops = np.zeros((n, n))
+    for a in range(n):
+        for b in range(n):
+            loops[a, b] = decay * st.C[a, b] + c.c_1 * (1 - c.c_c) ** 2 * st.p_c[a] * st.p_c[b]
+            for i in range(c.mu):
+                loops[a, b] += c.c_mu * c.weights[i] * Z[best[i], a] * Z[best[i], b]
+    np.testing.assert_allclose(new.C, loops, rtol=1e-12, atol=1e-15)
+    # mean and step size do not look at the flag
+    z_w = sum(c.weights[i] * Z[best[i]] for i in range(c.mu))
+    np.testing.assert_allclose(new.m, st.m + 0.32 * z_w, rtol=1e-13)
+    ps = (1 - c.c_sigma) * st.p_sigma + math.sqrt(c.c_sigma * (2 - c.c_sigma) * c.mu_eff) * z_w
+    assert new.sigma == pytest.approx(0.32 * math.exp(c.c_sigma / c.d_sigma * (np.linalg.norm(ps) / c.chi_n - 1)), rel=1e-13)
+    assert new.sigma > 0.32                                       # a long path lengthens the step
+    # with the path just short enough the flag is 1 again and p_c takes y_w
+    st.p_sigma[0] = 0.5
+    alive, _ = orc.cma_update(st, seeds, F)
+    assert alive.extra["h_sigma"] == 1.0
+    np.testing.assert_allclose(alive.p_c, (1 - c.c_c) * st.p_c + math.sqrt(c.c_c * (2 - c.c_c) * c.mu_eff) * z_w, rtol=1e-13)
+
+
+def test_cma_stall_threshold_from_the_hand_evaluated_constants():
+    # n = 16, lambda = 4 with the golden constants: the flag flips where |p_sigma| / sqrt(1 - (1 - c_sigma)^(2 (t + 1)))
+    # crosses (1.4 + 2 / 17) chi_n.  p_sigma is chosen so that the NEW path has a given length: with all rewards equal and
+    # the old path along e_0, p_sigma' = (1 - c_sigma) p_sigma + const z_w.
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "cma_constants.txt")) if l.strip() and not l.startswith("#")]
+    row = [r for r in rows if r[0] == "16" and r[1] == "4"][0]
+    c_sigma, chi_n = float(row[6]), float(row[11])
+    n, lam, t = 16, 4, 2
+    thr = (1.4 + 2.0 / 17.0) * chi_n * math.sqrt(1.0 - (1.0 - c_sigma) ** (2 * (t + 1)))
+    seeds = [3, 4, 5, 6]
+    F = np.array([4.0, 3.0, 2.0, 1.0])
+    st = orc.cma_state_init(n, 0.32)
+    st.t = t
+    base, _ = orc.cma_update(st, seeds, F)                        # p_sigma = 0: the new path is the z_w term alone
+    step = base.p_sigma
+    for target, flag in ((0.98 * thr, 1.0), (1.02 * thr, 0.0)):
+        # |(1 - c_sigma) a e_0 + step| = target  ->  a from the quadratic
+        q = 1.0 - c_sigma
+        bq, cq = 2 * q * step[0], float(step @ step) - target ** 2
+        a = (-bq + math.sqrt(bq * bq - 4 * q * q * cq)) / (2 * q * q)
+        st.p_sigma = np.zeros(n)
+        st.p_sigma[0] = a
+        new, _ = orc.cma_update(st, seeds, F)
+        assert new.extra["ps_norm"] == pytest.approx(target, rel=1e-5)
+        assert new.extra["h_sigma"] == flag
