@@ -52,6 +52,8 @@ typedef enum {
 #define ESSA_LORA_ONLY 0x2u    /* test hook: Y = B_k A_k x only                                       */
 #define ESSA_BASE_ONLY 0x4u    /* test hook: Y = W_deq x only                                         */
 #define ESSA_COMPUTE_BF16 0x8u /* exact bf16 products on the bf16 MFMA instead of the default int8-limb path   */
+#define ESSA_VALIDATE 0x10u    /* debug aid: copy every item's row2cand to the host first (one blocking copy per item)
+                                  and fail with ESSA_ERR_INVALID_ARG, before any launch, if an entry is not in [0, K) */
 
 /* ---------------------------------------------------------------------------------------------
  * Context
@@ -76,6 +78,12 @@ essa_status essa_synchronize(essa_ctx* ctx);
  * the same sequence once, unrecorded, first.  The recorded launches keep their pointer arguments: the replay
  * reads and writes the same buffers, with whatever they hold then (new seeds, the updated search state).
  * The context must have been created on a stream of the caller's, not the default stream.
+ * Lifetime: a graph's launches point into the context's scratch and into every object its calls used.  While a graph
+ * of a context is alive, a call on that context that would have to grow the scratch (a larger problem than any before),
+ * or an update with another population size than the state has seen last, fails with ESSA_ERR_STATE instead of moving
+ * memory under the graph: destroy the graph first, or run the largest problem once before recording.  Projections and
+ * search states used while recording must outlive the graph.  Destroying the context invalidates its graphs:
+ * essa_graph_launch then fails with ESSA_ERR_STATE, essa_graph_destroy is still to be called.
  * ------------------------------------------------------------------------------------------- */
 typedef struct essa_graph essa_graph;
 essa_status essa_graph_begin(essa_ctx* ctx);
@@ -85,8 +93,10 @@ essa_status essa_graph_launch(essa_graph* graph);
 void essa_graph_destroy(essa_graph* graph);
 
 /* Measurement aid: while enabled, every launch of the forward's GEMM kernel is bracketed by HIP
- * events on the context's stream.  essa_profile_read synchronises the stream, returns the summed
- * kernel time in milliseconds and the number of launches since the last read, and resets both. */
+ * events on the context's stream (a call whose items split between the int8, the 4-bit and the generic kernels
+ * launches one GEMM per kind, each with its own pair; the prep kernel in front of a GEMM is not timed).
+ * essa_profile_read synchronises the stream, returns the summed kernel time in milliseconds and the number of
+ * launches since the last read, and resets both. */
 essa_status essa_profile_enable(essa_ctx* ctx, int on);
 essa_status essa_profile_read(essa_ctx* ctx, double* total_ms, int* launches);
 
@@ -120,8 +130,9 @@ essa_status essa_proj_spectrum(const essa_proj* proj, float* sA_host, float* sB_
  * Search distribution  (paper: Method, "Evolutionary optimization": N(m, sigma^2 C))
  *
  * C = B D^2 B^T with orthonormal columns in B and axis lengths D.  A new object has C = B = I,
- * D = 1, both evolution paths 0, t = 0.  The eigendecomposition that refreshes (B, D) from C is not
- * part of this library: the caller supplies it through essa_cma_set_basis.
+ * D = 1, both evolution paths 0, t = 0.  The update moves C only; (B, D) change when the caller asks:
+ * essa_cma_refresh_basis takes the eigendecomposition of the current C on the device, essa_cma_set_basis
+ * installs a factorisation computed elsewhere.
  * ------------------------------------------------------------------------------------------- */
 essa_status essa_cma_create(essa_ctx* ctx, int n, float sigma0, const float* m0_host /* [n] or NULL = 0 */,
                             essa_cma** out);
@@ -211,17 +222,20 @@ essa_status essa_theta_to_sigma(essa_ctx* ctx, int P, int r, int n_top, const fl
  * For every row i:  Y[i,:] = W_deq x_i + U_B ( sB_c * ( (V_B^T U_A) ( sA_c * (V_A^T x_i) ) ) ),
  * c = row2cand[i] -- the candidate's dense W' is never formed.
  *   X          DEVICE [R, d_in], x_dtype (bf16 = upper half of an fp32)
- *   row2cand   DEVICE int32 [R], values in [0, K) (not checked on the device)
+ *   row2cand   DEVICE int32 [R], values in [0, K) (trusted: an entry outside reads sigma out of bounds; the flag
+ *              ESSA_VALIDATE checks them on the host first)
  *   sigmaA/B   DEVICE float, candidate k's r values at sigmaX + k * sigma_stride (absolute singular
  *              values, not offsets)
  *   Y          DEVICE [R, d_out], y_dtype, written in full
  * Arithmetic: fp32 X -> fp32 throughout.  bf16 X with int8 weights (default): each row of x is put in
- * 15-bit fixed point relative to its largest entry (x ~ delta_i (128 hi + lo), two int8 limbs, error at most
- * amax_i / 32766 per entry) and the base term runs on the int8 MFMA with exact int32 accumulation, one pass per
- * limb (4-bit weights likewise, their nibbles unpacked in registers, each group of 128 rescaled in fp32 and the
+ * 16-bit fixed point relative to its largest entry (x ~ delta_i (256 hi + lo), two signed int8 limbs, delta_i =
+ * amax_i / 32639, error at most delta_i / 2 per entry) and the base term runs on the int8 MFMA with exact int32
+ * accumulation, one pass per limb (4-bit weights likewise, their nibbles unpacked in registers, each group of 128 rescaled in fp32 and the
  * zero-point term added as a low-rank product); ESSA_COMPUTE_BF16 selects exact bf16 products on the bf16 MFMA
  * (fp32 accumulation) instead.  With ESSA_COMPUTE_W8A8 the base term uses x quantised per row to one int8
  * (amax/127, round to nearest even).  The LoRA term always sees the unquantised x.
+ * A row of X that holds an Inf or a NaN gives a row of NaN (W_deq x + B_k A_k x is then non-finite in every element: NaN,
+ * or an infinity of either sign).  A row whose largest magnitude is at most 2^-100 counts as zero in the base term.
  * R = 0 is a no-op.
  * ------------------------------------------------------------------------------------------- */
 essa_status essa_svdlora_forward(essa_ctx* ctx, const essa_proj* proj, const void* X, int x_dtype, int R,

@@ -48,6 +48,14 @@ extern "C" void essa_destroy(essa_ctx* ctx) {
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
+    // graphs recorded on this context hold pointers into its scratch: they die with it (launching one afterwards fails)
+    for (essa_graph* g : ctx->graphs) {
+        if (g->exec) (void)hipGraphExecDestroy(g->exec);
+        if (g->graph) (void)hipGraphDestroy(g->graph);
+        g->exec = nullptr;
+        g->graph = nullptr;
+        g->ctx = nullptr;
+    }
     if (ctx->ws) (void)hipFree(ctx->ws);
     for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
     delete ctx;
@@ -89,6 +97,8 @@ extern "C" essa_status essa_graph_end(essa_ctx* ctx, essa_graph** out) {
         return essa_fail(ESSA_ERR_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
     }
     auto* g = new essa_graph();
+    g->ctx = ctx;
+    ctx->graphs.push_back(g);
     g->device = ctx->device;
     g->stream = ctx->stream;
     g->graph = graph;
@@ -99,6 +109,7 @@ extern "C" essa_status essa_graph_end(essa_ctx* ctx, essa_graph** out) {
 
 extern "C" essa_status essa_graph_launch(essa_graph* g) {
     if (!g) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_graph_launch: graph is NULL");
+    if (!g->ctx || !g->exec) return essa_fail(ESSA_ERR_STATE, "essa_graph_launch: the context this graph was recorded on has been destroyed");
     ESSA_HIP(hipSetDevice(g->device));
     ESSA_HIP(hipGraphLaunch(g->exec, g->stream));
     return ESSA_OK;
@@ -107,7 +118,12 @@ extern "C" essa_status essa_graph_launch(essa_graph* g) {
 extern "C" void essa_graph_destroy(essa_graph* g) {
     if (!g) return;
     (void)hipSetDevice(g->device);
-    (void)hipStreamSynchronize(g->stream);
+    if (g->ctx) {
+        (void)hipStreamSynchronize(g->stream);
+        auto& v = g->ctx->graphs;
+        for (size_t i = 0; i < v.size(); ++i)
+            if (v[i] == g) { v.erase(v.begin() + i); break; }
+    }
     if (g->exec) (void)hipGraphExecDestroy(g->exec);
     if (g->graph) (void)hipGraphDestroy(g->graph);
     delete g;
@@ -158,6 +174,8 @@ essa_status essa_ws_reserve(essa_ctx* ctx, size_t bytes) {
     if (bytes <= ctx->ws_bytes) return ESSA_OK;
     if (ctx->capturing)
         return essa_fail(ESSA_ERR_STATE, "scratch would have to grow to %zu bytes while a graph is being recorded: run the same calls once before essa_graph_begin", bytes);
+    if (!ctx->graphs.empty())
+        return essa_fail(ESSA_ERR_STATE, "scratch would have to grow to %zu bytes, but %zu recorded graph(s) of this context still point into the current one: destroy them first (or run the largest problem once before recording)", bytes, ctx->graphs.size());
     ESSA_HIP(hipStreamSynchronize(ctx->stream));
     if (ctx->ws) ESSA_HIP(hipFree(ctx->ws));
     ctx->ws = nullptr;
@@ -571,16 +589,37 @@ extern "C" essa_status essa_theta_to_sigma(essa_ctx* ctx, int P, int r, int n_to
 // ---------------------------------------------------------------------------------------------
 // hot path: forward
 // ---------------------------------------------------------------------------------------------
+// The items of one call, planned: fixed-size, so that planning itself allocates nothing.
+struct item_list {
+    essa_k::fwd_item it[ESSA_MAX_GROUP];
+    int n = 0;
+    void push(const essa_k::fwd_item& k) { it[n++] = k; }
+};
+
+// With ESSA_VALIDATE: every entry of the item's row -> candidate map is checked on the host (one blocking copy).
+static essa_status validate_row2cand(essa_ctx* ctx, const essa_fwd_item& it, int index, const char* who) {
+    if (ctx->capturing) return essa_fail(ESSA_ERR_STATE, "%s: ESSA_VALIDATE copies the map to the host and cannot be recorded", who);
+    std::vector<int32_t> host((size_t)it.R);
+    ESSA_HIP(hipStreamSynchronize(ctx->stream));
+    ESSA_HIP(hipMemcpy(host.data(), it.row2cand, (size_t)it.R * sizeof(int32_t), hipMemcpyDeviceToHost));
+    for (int i = 0; i < it.R; ++i)
+        if (host[i] < 0 || host[i] >= it.K)
+            return essa_fail(ESSA_ERR_INVALID_ARG, "%s: item %d, row2cand[%d] = %d is not in [0, %d)", who, index, i, host[i], it.K);
+    return ESSA_OK;
+}
+
+// Checks the items and lays their scratch out.  scratch == nullptr: the context's own buffer, grown when it has to be;
+// otherwise the caller's buffer of scratch_bytes, which is never exceeded (ESSA_ERR_SHAPE says how much was needed).
 static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_items, int x_dtype, int y_dtype,
-                              unsigned flags, std::vector<essa_k::fwd_item>& out, const char* who,
-                              const float* const* rv = nullptr, float* rowpart = nullptr) {
+                              unsigned flags, item_list& out, const char* who,
+                              const float* const* rv = nullptr, float* rowpart = nullptr, void* scratch = nullptr, size_t scratch_bytes = 0) {
     if (x_dtype != ESSA_F32 && x_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: x_dtype %d", who, x_dtype);
     if (y_dtype != ESSA_F32 && y_dtype != ESSA_BF16) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: y_dtype %d", who, y_dtype);
-    if (flags & ~(ESSA_COMPUTE_W8A8 | ESSA_LORA_ONLY | ESSA_BASE_ONLY | ESSA_COMPUTE_BF16)) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: unknown flag bits 0x%x", who, flags);
+    if (flags & ~(ESSA_COMPUTE_W8A8 | ESSA_LORA_ONLY | ESSA_BASE_ONLY | ESSA_COMPUTE_BF16 | ESSA_VALIDATE)) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: unknown flag bits 0x%x", who, flags);
     if ((flags & ESSA_LORA_ONLY) && (flags & ESSA_BASE_ONLY)) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: LORA_ONLY and BASE_ONLY exclude each other", who);
     size_t total = 0;
     size_t block0 = 0;       // fused reward: first 128-channel block of the item within the call's range
-    out.clear();
+    out.n = 0;
     for (int i = 0; i < n_items; ++i) {
         const essa_fwd_item& it = items[i];
         if (!it.proj) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: item %d has no projection", who, i);
@@ -596,6 +635,7 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
         if ((flags & ESSA_COMPUTE_W8A8) && x_dtype != ESSA_BF16)
             return essa_fail(ESSA_ERR_UNSUPPORTED, "%s: W8A8 takes bf16 activations", who);
         if (it.R == 0) continue;
+        if (flags & ESSA_VALIDATE) ESSA_TRY(validate_row2cand(ctx, it, i, who));
         essa_k::fwd_item k{};
         k.X = it.X; k.row2cand = it.row2cand; k.sigmaA = it.sigmaA; k.sigmaB = it.sigmaB; k.Y = it.Y;
         k.sigma_stride = it.sigma_stride; k.R = it.R; k.K = it.K;
@@ -609,16 +649,24 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
             k.rowpart = rowpart + block0 * (size_t)it.R;
             block0 += (size_t)(p->d_out + ESSA_REWARD_BLOCK - 1) / ESSA_REWARD_BLOCK;
         }
-        out.push_back(k);
+        out.push(k);
         const size_t R = it.R;
         total += align256(R * p->rp * 4) + align256(R * p->rp * 4) + align256(R * (p->groups > 0 ? p->groups : 1) * 4);
         if (flags & ESSA_COMPUTE_W8A8) total += align256(R * (size_t)p->d_in) + align256(R * 4);
         if (p->Wt) total += 2 * align256((R + 255) / 256 * 256 * (size_t)p->d_in_pad) + align256(R * 4) + align256(R * 2 * (size_t)(p->Gp + 16) * 2) +
                             align256((size_t)((R + 31) / 32 * 32) * p->rp * 8 * 4);
     }
-    ESSA_TRY(essa_ws_reserve(ctx, total));
-    char* w = (char*)ctx->ws;
-    for (auto& k : out) {
+    char* w;
+    if (scratch) {
+        if (total > scratch_bytes)
+            return essa_fail(ESSA_ERR_SHAPE, "%s: this problem needs %zu bytes of scratch, the fixed buffer holds %zu", who, total, scratch_bytes);
+        w = (char*)scratch;
+    } else {
+        ESSA_TRY(essa_ws_reserve(ctx, total));
+        w = (char*)ctx->ws;
+    }
+    for (int ki = 0; ki < out.n; ++ki) {
+        essa_k::fwd_item& k = out.it[ki];
         const size_t R = k.R;
         k.U32 = (float*)w; w += align256(R * k.rp * 4);
         k.SBrow = k.U32;                      // the int8-limb path keeps the gathered sigma_B where the generic path keeps u
@@ -633,8 +681,8 @@ static essa_status plan_items(essa_ctx* ctx, const essa_fwd_item* items, int n_i
             k.Tpart = (float*)w; w += align256((size_t)((R + 31) / 32 * 32) * k.rp * 8 * 4);
             // items reading the same X share one set of limbs; the first of them quantises
             const essa_k::fwd_item* first = nullptr;
-            for (auto& o : out) {
-                if (&o == &k) break;
+            for (int oi = 0; oi < ki; ++oi) {
+                const essa_k::fwd_item& o = out.it[oi];
                 if (o.Wt && o.X == k.X && o.R == k.R && o.d_in == k.d_in && o.quant == k.quant) { first = &o; break; }
             }
             if (first) {
@@ -659,39 +707,45 @@ static bool takes_stream(const essa_k::fwd_item& k, int x_dtype, unsigned flags)
            !(k.quant == ESSA_QUANT_INT4_G128 && (flags & ESSA_COMPUTE_W8A8));
 }
 
-static essa_status run_items(essa_ctx* ctx, std::vector<essa_k::fwd_item>& ks, int x_dtype, int y_dtype, unsigned flags) {
-    std::vector<essa_k::fwd_item> fast, rest;
-    for (auto& k : ks) (takes_stream(k, x_dtype, flags) ? fast : rest).push_back(k);
-    // an item whose limbs were to be produced by an item that went the other way quantises for itself
-    for (size_t i = 0; i < fast.size(); ++i) {
-        if (fast[i].x_owner) continue;
-        bool found = false;
-        for (size_t j = 0; j < i; ++j) found = found || (fast[j].x_owner && fast[j].Xh == fast[i].Xh);
-        if (!found) fast[i].x_owner = 1;
+static essa_status run_items(essa_ctx* ctx, item_list& ks, int x_dtype, int y_dtype, unsigned flags) {
+    // three launch groups: int8 and 4-bit items on the int8-limb kernels (different instantiations of the GEMM), and the
+    // rest on the generic kernels
+    item_list f8, f4, rest;
+    for (int i = 0; i < ks.n; ++i) {
+        const essa_k::fwd_item& k = ks.it[i];
+        if (!takes_stream(k, x_dtype, flags)) rest.push(k);
+        else (k.quant == ESSA_QUANT_INT8_PERCH ? f8 : f4).push(k);
     }
-    hipEvent_t e0, e1;
-    ESSA_TRY(next_events(ctx, &e0, &e1));
-    const unsigned kflags = flags & ~ESSA_COMPUTE_BF16;
-    // int8 and 4-bit items of one group go to different instantiations of the GEMM
-    std::vector<essa_k::fwd_item> f8, f4;
-    for (auto& k : fast) (k.quant == ESSA_QUANT_INT8_PERCH ? f8 : f4).push_back(k);
-    for (auto* grp : {&f8, &f4}) {
-        for (size_t i = 0; i < grp->size(); ++i) {          // every set of limbs needs exactly one producer in its launch
+    const unsigned kflags = flags & ~(ESSA_COMPUTE_BF16 | ESSA_VALIDATE);
+    // while profiling, every GEMM launch of the call gets its own pair of events
+    for (item_list* grp : {&f8, &f4}) {
+        if (grp->n == 0) continue;
+        for (int i = 0; i < grp->n; ++i) {                  // every set of limbs needs exactly one producer in its launch
             bool found = false;
-            for (size_t j = 0; j < i; ++j) found = found || ((*grp)[j].x_owner && (*grp)[j].Xh == (*grp)[i].Xh);
-            (*grp)[i].x_owner = found ? 0 : 1;
+            for (int j = 0; j < i; ++j) found = found || (grp->it[j].x_owner && grp->it[j].Xh == grp->it[i].Xh);
+            grp->it[i].x_owner = found ? 0 : 1;
         }
-        if (!grp->empty()) {
-            ESSA_HIP(essa_k::forward_stream(ctx->stream, grp->data(), (int)grp->size(), y_dtype, kflags, e0, e1));
-            e0 = e1 = nullptr;
-        }
+        hipEvent_t e0, e1;
+        ESSA_TRY(next_events(ctx, &e0, &e1));
+        ESSA_HIP(essa_k::forward_stream(ctx->stream, grp->it, grp->n, y_dtype, kflags, e0, e1));
     }
-    if (!rest.empty()) {
-        ESSA_HIP(essa_k::forward_group(ctx->stream, rest.data(), (int)rest.size(), x_dtype, y_dtype, kflags,
-                                       fast.empty() ? e0 : nullptr, fast.empty() ? e1 : nullptr));
-        ESSA_HIP(essa_k::rowdot_blocks(ctx->stream, rest.data(), (int)rest.size(), y_dtype));   // no-op without reward vectors
+    if (rest.n > 0) {
+        hipEvent_t e0, e1;
+        ESSA_TRY(next_events(ctx, &e0, &e1));
+        ESSA_HIP(essa_k::forward_group(ctx->stream, rest.it, rest.n, x_dtype, y_dtype, kflags, e0, e1));
+        ESSA_HIP(essa_k::rowdot_blocks(ctx->stream, rest.it, rest.n, y_dtype));   // no-op without reward vectors
     }
     return ESSA_OK;
+}
+
+essa_status essa_forward_on_scratch(essa_ctx* ctx, const essa_fwd_item* item, int x_dtype, int y_dtype, unsigned flags, void* scratch,
+                                    size_t scratch_bytes, const char* who) {
+    if (flags & ESSA_VALIDATE) return essa_fail(ESSA_ERR_INVALID_ARG, "%s: ESSA_VALIDATE allocates and waits; use the ordinary entry point for it", who);
+    if (ctx->profiling && !ctx->capturing) return essa_fail(ESSA_ERR_STATE, "%s: profiling creates events; switch it off for this entry point", who);
+    item_list ks;
+    ESSA_TRY(plan_items(ctx, item, 1, x_dtype, y_dtype, flags, ks, who, nullptr, nullptr, scratch, scratch_bytes));
+    if (ks.n == 0) return ESSA_OK;
+    return run_items(ctx, ks, x_dtype, y_dtype, flags);
 }
 
 extern "C" essa_status essa_svdlora_forward_group(essa_ctx* ctx, const essa_fwd_item* items, int n_items, int x_dtype,
@@ -699,9 +753,9 @@ extern "C" essa_status essa_svdlora_forward_group(essa_ctx* ctx, const essa_fwd_
     if (!ctx || !items) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_svdlora_forward_group: NULL argument");
     if (n_items < 1 || n_items > ESSA_MAX_GROUP) return essa_fail(ESSA_ERR_SHAPE, "essa_svdlora_forward_group: %d items, at most %d", n_items, ESSA_MAX_GROUP);
     ESSA_HIP(hipSetDevice(ctx->device));
-    std::vector<essa_k::fwd_item> ks;
+    item_list ks;
     ESSA_TRY(plan_items(ctx, items, n_items, x_dtype, y_dtype, flags, ks, "essa_svdlora_forward_group"));
-    if (ks.empty()) return ESSA_OK;
+    if (ks.n == 0) return ESSA_OK;
     return run_items(ctx, ks, x_dtype, y_dtype, flags);
 }
 
@@ -720,9 +774,9 @@ extern "C" essa_status essa_svdlora_forward_reward_group(essa_ctx* ctx, const es
     if (block0 < 0 || block0 + blocks > block_capacity)
         return essa_fail(ESSA_ERR_SHAPE, "%s: blocks %lld..%lld do not fit a buffer of %lld", who, (long long)block0, (long long)(block0 + blocks), (long long)block_capacity);
     ESSA_HIP(hipSetDevice(ctx->device));
-    std::vector<essa_k::fwd_item> ks;
+    item_list ks;
     ESSA_TRY(plan_items(ctx, items, n_items, x_dtype, y_dtype, flags, ks, who, v, rowpart + (size_t)block0 * (size_t)items[0].R));
-    if (ks.empty()) return ESSA_OK;
+    if (ks.n == 0) return ESSA_OK;
     return run_items(ctx, ks, x_dtype, y_dtype, flags);
 }
 
@@ -741,10 +795,10 @@ extern "C" essa_status essa_svdlora_forward(essa_ctx* ctx, const essa_proj* proj
                                             int64_t sigma_stride, int K, void* Y, int y_dtype, uint32_t flags) {
     if (!ctx) return essa_fail(ESSA_ERR_INVALID_ARG, "essa_svdlora_forward: ctx is NULL");
     essa_fwd_item it{proj, X, row2cand, sigmaA, sigmaB, Y, sigma_stride, R, K};
-    std::vector<essa_k::fwd_item> ks;
+    item_list ks;
     ESSA_HIP(hipSetDevice(ctx->device));
     ESSA_TRY(plan_items(ctx, &it, 1, x_dtype, y_dtype, flags, ks, "essa_svdlora_forward"));
-    if (ks.empty()) return ESSA_OK;
+    if (ks.n == 0) return ESSA_OK;
     return run_items(ctx, ks, x_dtype, y_dtype, flags);
 }
 
@@ -922,6 +976,8 @@ extern "C" essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uin
     if (cma->weights_K != K) {
         if (ctx->capturing)
             return essa_fail(ESSA_ERR_STATE, "essa_cmaes_update: the weights for K=%d are not on the device yet: run the update once before essa_graph_begin", K);
+        if (!ctx->graphs.empty() && cma->weights)
+            return essa_fail(ESSA_ERR_STATE, "essa_cmaes_update: K changed from %d to %d while %zu recorded graph(s) of this context may still read the old weights: destroy them first", cma->weights_K, K, ctx->graphs.size());
         ESSA_HIP(hipStreamSynchronize(ctx->stream));
         if (cma->weights) ESSA_HIP(hipFree(cma->weights));
         cma->weights = nullptr;

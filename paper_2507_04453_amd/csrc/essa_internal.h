@@ -34,14 +34,20 @@ struct essa_ctx {
     std::vector<hipEvent_t> ev;   // pairs (start, stop)
     size_t ev_used = 0;
     bool capturing = false;    // between essa_graph_begin and essa_graph_end: no allocation, no synchronisation, no events
+    std::vector<struct essa_graph*> graphs;   // recorded graphs that are still alive: their launches hold pointers into ws
 };
 struct essa_graph {
+    essa_ctx* ctx = nullptr;   // null once the context is gone: the graph can then only be destroyed
     int device = 0;
     hipStream_t stream = nullptr;
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
 };
 essa_status essa_ws_reserve(essa_ctx* ctx, size_t bytes);
+// One projection's forward on a scratch buffer the caller brings (no allocation of any kind): the body of the entry
+// point for callers that cannot allocate.
+essa_status essa_forward_on_scratch(essa_ctx* ctx, const essa_fwd_item* item, int x_dtype, int y_dtype, unsigned flags, void* scratch,
+                                    size_t scratch_bytes, const char* who);
 
 struct essa_proj {
     essa_ctx* ctx = nullptr;   // identity check only; never dereferenced after creation

@@ -678,6 +678,8 @@ hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int
         if (ev_stop) (void)hipEventRecord(ev_stop, st);
     }
     if (ag.n_items) {
+        const bool time_this = !am.n_items;               // a call's one pair of events brackets its first GEMM launch
+        if (time_this && ev_start) (void)hipEventRecord(ev_start, st);
         int total = 0;
         for (int g = 0; g < ag.n_items; ++g) {
             ag.tile_start[g] = total;
@@ -689,6 +691,7 @@ hipError_t forward_group(hipStream_t st, const fwd_item* items, int n_items, int
         else if (xb) hipLaunchKernelGGL((gemm_f32_kernel<true, false>), dim3(total), dim3(256), 0, st, ag);
         else if (yb) hipLaunchKernelGGL((gemm_f32_kernel<false, true>), dim3(total), dim3(256), 0, st, ag);
         else hipLaunchKernelGGL((gemm_f32_kernel<false, false>), dim3(total), dim3(256), 0, st, ag);
+        if (time_this && ev_stop) (void)hipEventRecord(ev_stop, st);
     }
     return hipGetLastError();
 }

@@ -127,6 +127,24 @@ constexpr int PREP_NT = 512;
 constexpr int UTP = 36;            // LDS pitch (floats) of the two small matrices (rank-space vectors t, core M)
 using essa_k::prep_slice_cols;
 
+// The two limbs of the default path: x ~ unit * (256 hi + lo) with hi and lo both signed int8, i.e. 16-bit fixed point
+// relative to the row's largest entry.  LIMB_TOP = 127 * 256 + 127 is the largest magnitude whose high limb still fits.
+constexpr float LIMB_TOP = 32639.0f;
+// A row whose largest magnitude is at most this (2^-100) counts as a row of zeros in the base term: LIMB_TOP / amax
+// would overflow long before amax reaches the smallest fp32.
+constexpr float LIMB_TINY = 0x1p-100f;
+
+// Largest magnitude of a row from the bit patterns of its bf16 entries (two per 32-bit word).  With the sign bit gone
+// the patterns of finite values order like the values, and those of Inf and NaN lie above all of them: the integer
+// maximum is the row's amax when the row is finite and says so when it is not (fmaxf would drop a NaN).  The low
+// halves are compared shifted left by 17 (sign shifted out), the high halves masked: two operations per entry, as
+// many as shift + fmaxf(|.|).
+__device__ __forceinline__ void amax_accumulate(uint32_t& mlo, uint32_t& mhi, uint32_t two_bf16) {
+    mlo = max(mlo, two_bf16 << 17);
+    mhi = max(mhi, two_bf16 & 0x7fff0000u);
+}
+__device__ __forceinline__ uint32_t amax_join(uint32_t mlo, uint32_t mhi) { return max(mlo >> 1, mhi); }   // bits of amax as an fp32
+
 // Row quantisation at row counts in the thousands: one wave per row, the whole row in the wave's registers (NK
 // 16-byte chunks per lane, all asked for at once), the row maximum by shuffles alone.  No barrier and no LDS, so a
 // workgroup keeps eight rows in flight instead of two; the arithmetic per element is that of the two-row form.  It pays
@@ -142,21 +160,22 @@ __device__ __forceinline__ void quantise_row_wave(const fwd_item& it, int i, int
 #pragma unroll
     for (int k = 0; k < NK; ++k) xr[k] = xrow[min(64 * k + lane, nch - 1)];     // clamped: no branch between the loads
     __builtin_amdgcn_sched_barrier(0);
-    float m = 0.f;
+    uint32_t mlo = 0, mhi = 0;                             // see amax_accumulate
 #pragma unroll
     for (int k = 0; k < NK; ++k) {
         if (64 * k + lane >= nch) xr[k] = (u32x4){0, 0, 0, 0};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            m = fmaxf(m, fabsf(__uint_as_float(xr[k][e] << 16)));
-            m = fmaxf(m, fabsf(__uint_as_float(xr[k][e] & 0xffff0000u)));
-        }
+        for (int e = 0; e < 4; ++e) amax_accumulate(mlo, mhi, xr[k][e]);
     }
+    uint32_t mi = amax_join(mlo, mhi);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-    const float amax = m;
-    const float top = a_limbs == 2 ? 16383.0f : 127.0f;
-    const float inv = amax > 0.f ? top / amax : 0.f;
+    for (int off = 32; off > 0; off >>= 1) mi = max(mi, (uint32_t)__shfl_xor((int)mi, off, 64));
+    const bool finite = mi < 0x7f800000u;                  // an Inf or NaN anywhere in the row: the whole output row is NaN
+    const float amax = __uint_as_float(mi);
+    const float top = a_limbs == 2 ? LIMB_TOP : 127.0f;
+    const bool usable = finite && amax > (a_limbs == 2 ? LIMB_TINY : 0.f);
+    const float inv = usable ? top / amax : 0.f;
+    const float unit = !finite ? __builtin_nanf("") : (usable ? amax / top : 0.f);
     const gptr<u32x2> hrow = as_global_w(reinterpret_cast<u32x2*>(it.Xh + (size_t)i * dpad));
     const gptr<u32x2> lrow = as_global_w(reinterpret_cast<u32x2*>(it.Xl + (size_t)i * dpad));
     const gptr<uint16_t> xs16 = as_global_w(it.XS16);
@@ -174,8 +193,9 @@ __device__ __forceinline__ void quantise_row_wave(const fwd_item& it, int i, int
             const int qi = (int)q;
             qsum += qi;
             if (a_limbs == 2) {
-                hi[e >> 2] |= (uint32_t)((qi >> 7) & 0xff) << (8 * (e & 3));
-                lo[e >> 2] |= (uint32_t)(qi & 127) << (8 * (e & 3));
+                const int qh = (qi + 128) >> 8;            // see the two-row form below
+                hi[e >> 2] |= (uint32_t)(qh & 0xff) << (8 * (e & 3));
+                lo[e >> 2] |= (uint32_t)((qi - (qh << 8)) & 0xff) << (8 * (e & 3));
             } else {
                 hi[e >> 2] |= (uint32_t)(qi & 0xff) << (8 * (e & 3));
             }
@@ -188,7 +208,7 @@ __device__ __forceinline__ void quantise_row_wave(const fwd_item& it, int i, int
             for (int off = 8; off > 0; off >>= 1) gs += __shfl_xor(gs, off, 64);
             const int grp16 = c >> 4;
             if ((lane & 15) == 0 && grp16 < it.Gp) {
-                const float xs = (amax > 0.f ? amax / top : 0.f) * (float)gs;
+                const float xs = unit * (float)gs;
                 const uint16_t xh = f32_to_bf16_bits(xs);
                 xs16[(size_t)i * 2 * it.Gp + grp16] = xh;
                 xs16[(size_t)i * 2 * it.Gp + it.Gp + grp16] = f32_to_bf16_bits(xs - bf16_bits_to_f32(xh));
@@ -200,7 +220,7 @@ __device__ __forceinline__ void quantise_row_wave(const fwd_item& it, int i, int
             xs16[(size_t)i * 2 * it.Gp + gq] = 0;
             xs16[(size_t)i * 2 * it.Gp + it.Gp + gq] = 0;
         }
-    if (lane == 0) as_global_w(it.xdelta)[i] = amax > 0.f ? amax / top : 0.f;
+    if (lane == 0) as_global_w(it.xdelta)[i] = unit;
 }
 
 // FULLK: the form for row counts in the thousands on their way to the 128 x 256 kernel (role (b) walks all K slices and
@@ -209,7 +229,7 @@ __device__ __forceinline__ void quantise_row_wave(const fwd_item& it, int i, int
 template <bool FULLK>
 __global__ __launch_bounds__(PREP_NT, FULLK ? 4 : 1) void prep_kernel(stream_args a) {
     __shared__ __attribute__((aligned(16))) float part[8][2][16][64];   // lora role: partial tiles of the 8 waves (64 KB)
-    __shared__ float wred[8];
+    __shared__ uint32_t wred[8];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
     // Two dependent fetches from the kernel arguments stand between the start of the kernel and its first load from
@@ -276,32 +296,31 @@ __global__ __launch_bounds__(PREP_NT, FULLK ? 4 : 1) void prep_kernel(stream_arg
         // the row is read once: the first four chunks of every thread (rows up to 8192 wide) wait in registers
         // between the two passes
         u32x4 xr[4];
-        float m = 0.f;
+        uint32_t mlo = 0, mhi = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int c = t256 + 256 * k;
             xr[k] = c < nch ? xrow[c] : (u32x4){0, 0, 0, 0};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                m = fmaxf(m, fabsf(__uint_as_float(xr[k][e] << 16)));
-                m = fmaxf(m, fabsf(__uint_as_float(xr[k][e] & 0xffff0000u)));
-            }
+            for (int e = 0; e < 4; ++e) amax_accumulate(mlo, mhi, xr[k][e]);
         }
         for (int c = t256 + 1024; c < nch; c += 256) {
             const u32x4 v = xrow[c];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                m = fmaxf(m, fabsf(__uint_as_float(v[e] << 16)));
-                m = fmaxf(m, fabsf(__uint_as_float(v[e] & 0xffff0000u)));
-            }
+            for (int e = 0; e < 4; ++e) amax_accumulate(mlo, mhi, v[e]);
         }
+        uint32_t mi = amax_join(mlo, mhi);
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-        if (lane == 0) wred[wave] = m;
+        for (int off = 32; off > 0; off >>= 1) mi = max(mi, (uint32_t)__shfl_xor((int)mi, off, 64));
+        if (lane == 0) wred[wave] = mi;
         __syncthreads();
-        const float amax = fmaxf(fmaxf(wred[4 * grp], wred[4 * grp + 1]), fmaxf(wred[4 * grp + 2], wred[4 * grp + 3]));
-        const float top = a_limbs == 2 ? 16383.0f : 127.0f;
-        const float inv = amax > 0.f ? top / amax : 0.f;
+        mi = max(max(wred[4 * grp], wred[4 * grp + 1]), max(wred[4 * grp + 2], wred[4 * grp + 3]));
+        const bool finite = mi < 0x7f800000u;             // an Inf or NaN anywhere in the row: the whole output row is NaN
+        const float amax = __uint_as_float(mi);
+        const float top = a_limbs == 2 ? LIMB_TOP : 127.0f;
+        const bool usable = finite && amax > (a_limbs == 2 ? LIMB_TINY : 0.f);
+        const float inv = usable ? top / amax : 0.f;
+        const float unit = !finite ? __builtin_nanf("") : (usable ? amax / top : 0.f);
         PSTAMP(1)
         if (!live) return;
         typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
@@ -319,8 +338,9 @@ __global__ __launch_bounds__(PREP_NT, FULLK ? 4 : 1) void prep_kernel(stream_arg
                 const int qi = (int)q;
                 qsum += qi;
                 if (a_limbs == 2) {
-                    hi[e >> 2] |= (uint32_t)((qi >> 7) & 0xff) << (8 * (e & 3));   // arithmetic shift: hi in [-128,127]
-                    lo[e >> 2] |= (uint32_t)(qi & 127) << (8 * (e & 3));           // lo in [0,127]
+                    const int qh = (qi + 128) >> 8;                                // arithmetic shift: hi in [-127,127]
+                    hi[e >> 2] |= (uint32_t)(qh & 0xff) << (8 * (e & 3));
+                    lo[e >> 2] |= (uint32_t)((qi - (qh << 8)) & 0xff) << (8 * (e & 3));   // lo in [-128,127]
                 } else {
                     hi[e >> 2] |= (uint32_t)(qi & 0xff) << (8 * (e & 3));
                 }
@@ -336,7 +356,7 @@ __global__ __launch_bounds__(PREP_NT, FULLK ? 4 : 1) void prep_kernel(stream_arg
                 for (int off = 8; off > 0; off >>= 1) gs += __shfl_xor(gs, off, 64);
                 const int grp16 = c >> 4;
                 if ((lane & 15) == 0 && grp16 < it.Gp) {
-                    const float xs = (amax > 0.f ? amax / top : 0.f) * (float)gs;
+                    const float xs = unit * (float)gs;
                     const uint16_t xh = f32_to_bf16_bits(xs);
                     xs16[(size_t)i * 2 * it.Gp + grp16] = xh;
                     xs16[(size_t)i * 2 * it.Gp + it.Gp + grp16] = f32_to_bf16_bits(xs - bf16_bits_to_f32(xh));
@@ -353,7 +373,7 @@ __global__ __launch_bounds__(PREP_NT, FULLK ? 4 : 1) void prep_kernel(stream_arg
                 xs16[(size_t)i * 2 * it.Gp + gq] = 0;
                 xs16[(size_t)i * 2 * it.Gp + it.Gp + gq] = 0;
             }
-        if (t256 == 0) as_global_w(it.xdelta)[i] = amax > 0.f ? amax / top : 0.f;
+        if (t256 == 0) as_global_w(it.xdelta)[i] = unit;
         PSTAMP(2)
         return;
     }
@@ -690,7 +710,7 @@ __device__ __forceinline__ void compute_tile_q4_rows(f32x16& tot, const u32x4 (&
     }
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-        const int comb = LIMBS == 2 ? (t[0][q] << 7) + t[LIMBS - 1][q] : t[0][q];   // |t| <= 2^17 per tile: no overflow
+        const int comb = LIMBS == 2 ? (t[0][q] << 8) + t[LIMBS - 1][q] : t[0][q];   // |t| < 2^18 per tile: no overflow
         tot[q] = fmaf(sg, (float)comb, tot[q]);
     }
 }
@@ -1109,7 +1129,7 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int q = 0; q < 16; ++q) {
-                if (!Q4) tot[mb][q] = fmaf(128.0f, (float)acc[0][mb][q], (float)acc[LIMBS - 1][mb][q]);
+                if (!Q4) tot[mb][q] = fmaf(256.0f, (float)acc[0][mb][q], (float)acc[LIMBS - 1][mb][q]);
                 acc[0][mb][q] = (int)__float_as_uint(tot[mb][q]);
             }
     }
@@ -1344,7 +1364,7 @@ __device__ __forceinline__ void q4w_tile(const stream_args& a, const fwd_item& i
         _Pragma("unroll") for (int i_ = 0; i_ < NFR_; ++i_) {                                                      \
             const int mb_ = i_ / (4 * LIMBS), l_ = (i_ >> 2) % LIMBS, c_ = i_ & 3;                                 \
             if (c_ == 0 && l_ == 0) t_ = zero;                                                                     \
-            if (c_ == 0 && l_ == 1) { _Pragma("unroll") for (int q = 0; q < 16; ++q) t_[q] <<= 7; }                \
+            if (c_ == 0 && l_ == 1) { _Pragma("unroll") for (int q = 0; q < 16; ++q) t_[q] <<= 8; }                \
             t_ = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr_[i_ % FD], wq_[c_], t_, 0, 0, 0);                        \
             if (i_ + FD < NFR_) {                                                                                  \
                 const int n_ = i_ + FD;                                                                            \
@@ -1501,8 +1521,8 @@ constexpr size_t big_smem_bytes() {
     return big + BIG_BM * 4 + (size_t)BIG_BM * UROW;
 }
 
-template <int LIMBS, bool YBF16>
-__global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
+template <int LIMBS, bool YBF16, bool DUMP = false>
+__global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a, int32_t* __restrict__ acc_out) {
     constexpr int BM = BIG_BM;
     constexpr size_t STAGE = big_stage_bytes<LIMBS>();
     constexpr size_t WOFF = (size_t)LIMBS * BM * BXROW;                // weight blocks inside a stage
@@ -1570,7 +1590,9 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
     float* tvec = reinterpret_cast<float*>(smem + 3 * STAGE);
     float* Ms = tvec + BM * UTP;
     constexpr int EU = (BM * 32 + NT - 1) / NT;
-    if (a.u_ready) {
+    if constexpr (DUMP) {
+        load_tile(xs0, ws0, 0);                             // accumulator dump: no rank-space work, no scales
+    } else if (a.u_ready) {
         // the prep kernel has left the finished rows of u (bf16 head, then tail: 4 rp bytes per row): a plain copy
         const int ppr = rp / 4;                                      // 16-byte pieces per row
         u32x4 up[2];
@@ -1668,6 +1690,21 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
 #undef BIG_READ_A
 #undef BIG_READ_B
 
+    if constexpr (DUMP) {
+        // test hook: the raw int32 sums of the (single) limb, element (row, channel) of this lane's accumulators
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const int o = (nb0 + wc * 2 + nb) * 32 + l32;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int i = m0 + wr * 64 + mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+                    if (i < R && o < dout) acc_out[(size_t)i * dout + o] = acc[0][mb][nb][q];
+                }
+            }
+        return;
+    }
     // ---- epilogue, one half of the tile (128 channels) at a time: scale, rank-r term, LDS output tile, store
     constexpr int CROW = 128 * (YBF16 ? 2 : 4) + 16;
 #pragma unroll 1
@@ -1695,7 +1732,7 @@ __global__ __launch_bounds__(NT) void gemm_i8_big_kernel(stream_args a) {
                     for (int q = 0; q < 16; ++q) {
                         const int rl = wr * 64 + mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
                         const float sc = xd[rl] * wscale;
-                        if (LIMBS == 2) v[q] = fmaf(128.0f, (float)acc[0][mb][nb][q], (float)acc[LIMBS - 1][mb][nb][q]) * sc;
+                        if (LIMBS == 2) v[q] = fmaf(256.0f, (float)acc[0][mb][nb][q], (float)acc[LIMBS - 1][mb][nb][q]) * sc;
                         else v[q] = (float)acc[0][mb][nb][q] * sc;
                         if (a.flags & ESSA_LORA_ONLY) v[q] = 0.f;
                     }
@@ -1778,8 +1815,8 @@ hipError_t launch_gemm_q4_wide(hipStream_t st, stream_args& a) {
     return hipGetLastError();
 }
 
-template <int LIMBS, bool YBF16>
-hipError_t launch_gemm_big(hipStream_t st, stream_args& a) {
+template <int LIMBS, bool YBF16, bool DUMP = false>
+hipError_t launch_gemm_big(hipStream_t st, stream_args& a, int32_t* acc_out = nullptr) {
     int total = 0;
     for (int g = 0; g < a.n_items; ++g) {
         a.tile_start[g] = total;
@@ -1788,15 +1825,15 @@ hipError_t launch_gemm_big(hipStream_t st, stream_args& a) {
     a.tile_start[a.n_items] = total;
     constexpr size_t smem = big_smem_bytes<LIMBS, YBF16>();
     static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
-    auto kern = gemm_i8_big_kernel<LIMBS, YBF16>;
+    auto kern = gemm_i8_big_kernel<LIMBS, YBF16, DUMP>;
     static bool attr_done = false;   // one flag per instantiation
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    if (tl_ev_start) hipExtLaunchKernelGGL(kern, dim3(total), dim3(NT), (uint32_t)smem, st, tl_ev_start, tl_ev_stop, 0, a);
-    else hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a);
+    if (tl_ev_start) hipExtLaunchKernelGGL(kern, dim3(total), dim3(NT), (uint32_t)smem, st, tl_ev_start, tl_ev_stop, 0, a, acc_out);
+    else hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a, acc_out);
     return hipGetLastError();
 }
 
@@ -1947,6 +1984,8 @@ hipError_t w8a8_accumulators_stream(hipStream_t st, const fwd_item& it, int32_t*
     a.limbs = 1;
     for (int g = 1; g <= ESSA_MAX_GROUP; ++g) a.quant_start[g] = (it.R + 1) / 2;      // quantise only: no rank-space work (lora_start stays zero)
     hipLaunchKernelGGL(prep_kernel<false>, dim3(a.quant_start[1]), dim3(PREP_NT), 0, st, a);
+    // the kernel the forward itself would take at this size dumps its sums: the 128 x 256 tile once it fills the chip
+    if (takes_big(a)) return launch_gemm_big<1, false, true>(st, a, acc_out);
     return launch_gemm<2, 1, false, true>(st, a, acc_out);
 }
 

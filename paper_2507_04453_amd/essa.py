@@ -16,13 +16,14 @@ __all__ = [
     "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards", "essa_version", "EXPORTED_SYMBOLS",
     "ForwardGroup", "REWARD_BLOCK", "essa_svdlora_forward_reward_group", "essa_reward_finish",
     "essa_cma_create_opt", "OPT_CMA", "OPT_ACTIVE_CMA", "OPT_SEP_CMA", "OPT_ES", "OPT_ARS",
+    "VALIDATE",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libessa.so")
 
 F32, BF16 = 0, 1
 QUANT_INT8_PERCH, QUANT_INT4_G128 = 0, 1
-COMPUTE_W8A8, LORA_ONLY, BASE_ONLY, COMPUTE_BF16 = 1, 2, 4, 8
+COMPUTE_W8A8, LORA_ONLY, BASE_ONLY, COMPUTE_BF16, VALIDATE = 1, 2, 4, 8, 16
 MAX_GROUP = 8
 REWARD_BLOCK = 128
 OPT_CMA, OPT_ACTIVE_CMA, OPT_SEP_CMA, OPT_ES, OPT_ARS = 0, 1, 2, 3, 4
