@@ -242,6 +242,22 @@ essa_status essa_svdlora_forward(essa_ctx* ctx, const essa_proj* proj, const voi
                                  const int32_t* row2cand, const float* sigmaA, const float* sigmaB,
                                  int64_t sigma_stride, int K, void* Y, int y_dtype, uint32_t flags);
 
+/* The same call for callers that cannot allocate device memory (code under HIP graph capture by the caller, tight
+ * serving loops, harnesses that forbid hipMalloc): it never calls hipMalloc, hipFree or any other allocating routine.
+ * Where essa_svdlora_forward takes its scratch (activation limbs, rank-space vectors) from the context's buffer and
+ * grows that on demand, this one lays the same scratch out in a fixed array of ESSA_NOALLOC_SCRATCH_BYTES (8 MiB) that
+ * the library holds in device memory on every GPU it runs on until the process ends.  A problem that needs more fails
+ * with ESSA_ERR_SHAPE and a message naming both sizes; as a guide, the bytes needed are about
+ * 2 * ceil(R / 256) * 256 * ceil(d_in / 512) * 512 + R * (300 * rp + 4 * d_in / 128), i.e. R = 256 rows fit for d_in up
+ * to 8192.  ESSA_VALIDATE and profiling (essa_profile_enable) are refused, since they allocate.  Results are bit for
+ * bit those of essa_svdlora_forward.  All calls on one GPU share the array, which keeps the last call's contents
+ * (nothing in it has to start at zero: every byte a kernel reads is written by the prep launch of the same call):
+ * calls that overlap in time on one GPU -- two streams, two contexts -- race; calls on one stream are ordered. */
+#define ESSA_NOALLOC_SCRATCH_BYTES (8u << 20)
+essa_status essa_svdlora_forward_noalloc(essa_ctx* ctx, const essa_proj* proj, const void* X, int x_dtype, int R,
+                                         const int32_t* row2cand, const float* sigmaA, const float* sigmaB,
+                                         int64_t sigma_stride, int K, void* Y, int y_dtype, uint32_t flags);
+
 /* The same for several projections in one launch sequence (q, k, v of a layer share X; o has its own). */
 typedef struct essa_fwd_item {
     const essa_proj* proj;

@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libessa.so")
-SOURCES = ["essa_api.cpp", "svd_host.cpp", "kernels_sample.hip", "kernels_cma.hip", "kernels_forward.hip", "kernels_stream.hip", "kernels_eig.hip"]
+SOURCES = ["essa_api.cpp", "svd_host.cpp", "kernels_sample.hip", "kernels_cma.hip", "kernels_forward.hip", "kernels_stream.hip", "kernels_eig.hip", "noalloc.hip"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wno-unused-result"]
 # packed-fp32 VALU forms are switched off for device code on purpose
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + os.environ.get("ESSA_EXTRA_FLAGS", "").split()

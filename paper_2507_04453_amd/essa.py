@@ -16,7 +16,7 @@ __all__ = [
     "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards", "essa_version", "EXPORTED_SYMBOLS",
     "ForwardGroup", "REWARD_BLOCK", "essa_svdlora_forward_reward_group", "essa_reward_finish",
     "essa_cma_create_opt", "OPT_CMA", "OPT_ACTIVE_CMA", "OPT_SEP_CMA", "OPT_ES", "OPT_ARS",
-    "VALIDATE",
+    "VALIDATE", "essa_svdlora_forward_noalloc", "NOALLOC_SCRATCH_BYTES",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libessa.so")
@@ -24,6 +24,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libessa.so"
 F32, BF16 = 0, 1
 QUANT_INT8_PERCH, QUANT_INT4_G128 = 0, 1
 COMPUTE_W8A8, LORA_ONLY, BASE_ONLY, COMPUTE_BF16, VALIDATE = 1, 2, 4, 8, 16
+NOALLOC_SCRATCH_BYTES = 8 << 20
 MAX_GROUP = 8
 REWARD_BLOCK = 128
 OPT_CMA, OPT_ACTIVE_CMA, OPT_SEP_CMA, OPT_ES, OPT_ARS = 0, 1, 2, 3, 4
@@ -38,7 +39,7 @@ EXPORTED_SYMBOLS = [
     "essa_reward_accumulate", "essa_reward_accumulate_group", "essa_cmaes_update", "essa_rank_rewards",
     "essa_svdlora_forward_reward_group", "essa_reward_finish",
     "essa_graph_begin", "essa_graph_end", "essa_graph_launch", "essa_graph_destroy", "essa_cma_refresh_basis",
-    "essa_cma_create_opt", "essa_cma_kind",
+    "essa_cma_create_opt", "essa_cma_kind", "essa_svdlora_forward_noalloc",
 ]
 
 
@@ -97,6 +98,7 @@ def _load():
         "essa_philox_words": (i32, [vp, vp, i32, i32, vp]),
         "essa_theta_to_sigma": (i32, [vp, i32, i32, i32, vp, vp, vp, i32, vp, vp]),
         "essa_svdlora_forward": (i32, [vp, vp, vp, i32, i32, vp, vp, vp, i64, i32, vp, i32, u32]),
+        "essa_svdlora_forward_noalloc": (i32, [vp, vp, vp, i32, i32, vp, vp, vp, i64, i32, vp, i32, u32]),
         "essa_svdlora_forward_group": (i32, [vp, C.POINTER(_FwdItem), i32, i32, i32, u32]),
         "essa_svdlora_forward_reward_group": (i32, [vp, C.POINTER(_FwdItem), i32, i32, i32, u32, C.POINTER(vp), vp, i64, i64]),
         "essa_reward_finish": (i32, [vp, vp, i64, i32, vp, i32, vp]),
@@ -418,6 +420,18 @@ def essa_svdlora_forward(ctx: Context, proj: Projection, X: torch.Tensor, row2ca
     pa, pb, stride = _sigma_args(proj, sigmaA, sigmaB, K)
     _check(lib.essa_svdlora_forward(ctx._h, proj._h, _dev(X, None, "X"), _xdtype(X), R, _dev(row2cand, torch.int32, "row2cand"),
                                     pa, pb, stride, K, _dev(Y, None, "Y"), _ydtype(Y), flags))
+
+
+def essa_svdlora_forward_noalloc(ctx: Context, proj: Projection, X: torch.Tensor, row2cand: torch.Tensor, sigmaA: torch.Tensor,
+                                 sigmaB: torch.Tensor, Y: torch.Tensor, flags: int = 0):
+    """essa_svdlora_forward on the library's fixed scratch array: no device allocation of any kind."""
+    R = X.shape[0]
+    K = sigmaA.shape[0]
+    if X.dim() != 2 or X.shape[1] != proj.d_in or tuple(Y.shape) != (R, proj.d_out) or row2cand.numel() != R:
+        raise ValueError("X [R,d_in], Y [R,d_out], row2cand [R]")
+    pa, pb, stride = _sigma_args(proj, sigmaA, sigmaB, K)
+    _check(lib.essa_svdlora_forward_noalloc(ctx._h, proj._h, _dev(X, None, "X"), _xdtype(X), R, _dev(row2cand, torch.int32, "row2cand"),
+                                            pa, pb, stride, K, _dev(Y, None, "Y"), _ydtype(Y), flags))
 
 
 class ForwardGroup:
