@@ -64,6 +64,9 @@ struct stream_args {
     // finished u_i = sB_c * (M (sA_c * V_A^T x_i)) in U16 (bf16 head and tail) instead of the slices' shares in Tpart;
     // the 128 x 256 kernel then copies its tile of u instead of adding the shares up once per column tile
     int u_ready;
+    // the limbs leave the prep kernel in MFMA-operand tiles, [block of 32 rows][K chunk of 32][half][row][16 bytes]
+    // (one contiguous kilobyte per wave load), for the kernel that streams them straight into registers
+    int limb_tiled;
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
@@ -324,9 +327,16 @@ __global__ __launch_bounds__(PREP_NT, FULLK ? 4 : 1) void prep_kernel(stream_arg
         PSTAMP(1)
         if (!live) return;
         typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
-        const gptr<u32x2> hrow = as_global_w(reinterpret_cast<u32x2*>(it.Xh + (size_t)i * dpad));
-        const gptr<u32x2> lrow = as_global_w(reinterpret_cast<u32x2*>(it.Xl + (size_t)i * dpad));
+        const gptr<u32x2> hrow = as_global_w(reinterpret_cast<u32x2*>(it.Xh));
+        const gptr<u32x2> lrow = as_global_w(reinterpret_cast<u32x2*>(it.Xl));
         const gptr<uint16_t> xs16 = as_global_w(it.XS16);
+        const int tiled = a.limb_tiled;
+        // where chunk c (columns 8c .. 8c+7) of row i goes, in units of 8 bytes: row-major, or operand tiles
+        auto limb_slot = [&](int c) -> size_t {
+            if (!tiled) return ((size_t)i * dpad >> 3) + c;
+            const size_t blk = (size_t)(i >> 5) * (dpad >> 5) + (c >> 2);                  // (row block, K chunk)
+            return ((blk * 2 + ((c >> 1) & 1)) * 512 + (size_t)(i & 31) * 16 + (c & 1) * 8) >> 3;
+        };
         auto quantise_chunk = [&](int c, const u32x4& v) {
             uint32_t hi[2] = {0, 0}, lo[2] = {0, 0};
             int qsum = 0;
@@ -346,8 +356,9 @@ __global__ __launch_bounds__(PREP_NT, FULLK ? 4 : 1) void prep_kernel(stream_arg
                 }
             }
             // streaming stores: the limbs are read by the next launch, from behind other L2s than this one
-            __builtin_nontemporal_store((u32x2){hi[0], hi[1]}, hrow + c);
-            if (a_limbs == 2) __builtin_nontemporal_store((u32x2){lo[0], lo[1]}, lrow + c);
+            const size_t slot = limb_slot(c);
+            __builtin_nontemporal_store((u32x2){hi[0], hi[1]}, hrow + slot);
+            if (a_limbs == 2) __builtin_nontemporal_store((u32x2){lo[0], lo[1]}, lrow + slot);
             if (it.quant == ESSA_QUANT_INT4_G128) {
                 // sum of the row's fixed-point activations over each group of 128 columns (16 consecutive lanes),
                 // times delta: what the zero-points of the 4-bit format multiply.  Kept as bf16 head + tail.
@@ -763,7 +774,7 @@ __device__ __forceinline__ void u_tile_loads(const fwd_item& it, int m0, int tid
     for (int i = 0; i < 2; ++i) mreg[i] = as_global(it.M)[min(tid + NT * i, rp * rp - 1)];
 }
 
-template <int BM, int EU>
+template <int BM, int EU, bool LDS_ONLY = false>
 __device__ __forceinline__ void u_tile_finish(const fwd_item& it, unsigned flags, int tid, const f32x4 (&tp)[EU][2], const float (&sb)[EU],
                                               const float (&mreg)[2], float* tvec, float* Ms, unsigned char* utile) {
     const int rp = it.rp, rsh = rp == 16 ? 4 : 5;
@@ -782,7 +793,8 @@ __device__ __forceinline__ void u_tile_finish(const fwd_item& it, unsigned flags
             tvec[(e >> rsh) * UTP + (e & (rp - 1))] = t;
         }
     }
-    __syncthreads();
+    if (LDS_ONLY) lds_barrier();          // loads already in flight keep flying across it
+    else __syncthreads();
 #pragma unroll
     for (int i = 0; i < EU; ++i) {
         const int e = tid + NT * i;
@@ -1257,6 +1269,207 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
 
     // ---- epilogue 3: the tile leaves as full rows, 16 bytes per thread where the output allows it
     store_ctile<YBF16, BM>(smem, it, m0, nb0 * 32, nb0 >> 2, tid, rvp);
+    TSTAMP(5)
+}
+
+// ------------------------------------------------------------------------------------------------
+// int8 weights at row counts up to 32 (the decode sizes bound by the weight stream): every CU streams weights.
+// One workgroup per block of 32 output channels, all the rows (MB blocks of 32), the whole K; its 8 waves
+// split K, wave w taking the chunks of 32 columns kc = w, w + 8, ...  There is no LDS and no barrier in the loop: a
+// wave loads the weight block of its chunk (one kilobyte, operand order) and the activation limbs of the same chunk
+// (operand tiles written by the prep kernel, one kilobyte per limb and row block) straight into MFMA operand
+// registers, D chunks ahead.  What bounds a decode launch is the bytes its busiest CU takes in; here that is
+// K x (32 + 2 R) instead of K x (128 + 2 x 32) on a quarter of the CUs (at 32 rows), and all 256 CUs pull on HBM.
+// Loads past the wave's last chunk and the limb rows past R are sent out of the buffer's range: they return zeros
+// without touching memory.
+// After the loop the partial sums meet in LDS.  The integer sums of the chunks with kc % 4 in {0, 1} and in {2, 3} are
+// each folded into one fp32 value (256 hi + lo) and the two are added in that order: exactly what the two K halves of
+// the 32- and 64-row tiles of gemm_i8_kernel compute, so a row's result does not depend on which of them took it.
+// Wave mb then finishes row block mb like the other kernels do (scale, rank-r term by bf16 head+tail MFMA steps).
+// The reward partials, one per 128 channels, span four workgroups here: the launcher takes them in a pass of its own.
+// ------------------------------------------------------------------------------------------------
+template <int MB, int LIMBS>
+constexpr size_t stream_smem_bytes() { return (size_t)8 * LIMBS * MB * 4096 + (size_t)MB * 4096 + (size_t)32 * MB * 4 + (size_t)32 * MB * UROW; }
+
+template <int MB, int LIMBS, bool YBF16>
+__global__ __launch_bounds__(NT, 1) void gemm_i8_stream_kernel(stream_args a) {
+    constexpr int BM = 32 * MB;
+    // chunks in flight per wave.  Deeper does not help (all 14 chunks of a 3584-wide row at once: 14.3 against 12.5 us):
+    // a CU's vector-memory path takes 64 B per clock, i.e. 16 clocks per kilobyte-sized load instruction, so the 24
+    // loads of 8 chunks already take the 8 waves 1.4 us to issue, about the time the first of them needs to come back
+    constexpr int D = MB == 1 ? 8 : 6;
+    constexpr size_t RED = (size_t)8 * LIMBS * MB * 4096;  // the 8 waves' partial sums; before the loop: t vectors and the core matrix
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    int* red = reinterpret_cast<int*>(smem);               // [wave][limb][row block][q][lane]
+    float* totb = reinterpret_cast<float*>(smem + RED);    // [row block][q][lane] folded base sums
+    float* xd = reinterpret_cast<float*>(smem + RED + (size_t)MB * 4096);
+    unsigned char* utile = smem + RED + (size_t)MB * 4096 + BM * 4;
+    float* tvec = reinterpret_cast<float*>(smem);
+    float* Ms = tvec + BM * UTP;
+    static_assert((size_t)(BM + 32) * UTP * 4 <= RED, "the prologue's matrices fit where the partial sums go later");
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, h = lane >> 5;
+    TSTAMP(0)
+    int g = 0;
+#pragma unroll
+    for (int i = 1; i < ESSA_MAX_GROUP; ++i) g += (i < a.n_items && (int)blockIdx.x >= a.tile_start[i]) ? 1 : 0;
+    const fwd_item it = fetch_item(a.it[g]);
+    const int nb = blockIdx.x - a.tile_start[g];           // this workgroup's block of 32 channels
+    const int R = it.R, dout = it.d_out, dpad = it.d_in_pad, rp = it.rp;
+    const int nkc = dpad >> 5;                             // chunks of 32 columns; a multiple of 16
+    const int n = nkc >> 3;                                // chunks of this wave
+    const uint32_t wstride_b = (uint32_t)it.n_blocks * 1024;
+    const rsrc_t wbase = make_rsrc(reinterpret_cast<const unsigned char*>(it.Wt) + (size_t)nb * 1024);
+    rsrc_t xbase[LIMBS];
+#pragma unroll
+    for (int l = 0; l < LIMBS; ++l) xbase[l] = make_rsrc(l == 0 ? it.Xh : it.Xl);
+    constexpr uint32_t OUT_OF_RANGE = 0x80000000u;         // beyond the descriptor's 2 GB: the load returns zeros, no memory access
+    const uint32_t lane16 = lane * 16;
+    uint32_t xoff[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) xoff[mb] = (mb * 32 + l32 < R) ? (uint32_t)(mb * nkc) * 1024u + lane16 : OUT_OF_RANGE;
+
+    // the small loads first (loads return in order): rank-space vectors, row units, this lane's channel scale and U_B
+    constexpr int EU = (BM * 32 + NT - 1) / NT;
+    f32x4 tp[EU][2];
+    float sb[EU], mreg[2];
+    u_tile_loads<BM, EU>(it, 0, tid, tp, sb, mreg);
+    const float xdreg = as_global(it.xdelta)[min(min(tid, BM - 1), R - 1)];
+    const int oc = min(nb * 32 + l32, dout - 1);
+    const float wscale = as_global(it.scale)[oc];
+    u32x4 ubf[2][2];
+    {
+        const uint16_t* bp = it.UB16 + (size_t)oc * 2 * rp + 8 * h;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            ubf[ks][0] = ubf[ks][1] = (u32x4){0, 0, 0, 0};
+            if (ks * 16 < rp) {
+                ubf[ks][0] = *as_global(reinterpret_cast<const u32x4*>(bp + ks * 16));
+                ubf[ks][1] = *as_global(reinterpret_cast<const u32x4*>(bp + rp + ks * 16));
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    TSTAMP(1)
+
+    // the ring: slot s holds chunk j = s, s + D, ... of this wave (K chunk kc = wave + 8 j)
+    u32x4 wr[D], xr[D][LIMBS][MB];
+    auto issue = [&](int j, int slot) {
+        const uint32_t gone = j < n ? 0u : OUT_OF_RANGE;   // wave-uniform
+        const uint32_t kc = (uint32_t)(wave + 8 * j);
+        wr[slot] = load16(wbase, lane16 | gone, kc * wstride_b);
+#pragma unroll
+        for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) xr[slot][l][mb] = load16(xbase[l], xoff[mb] | gone, kc * 1024u);
+    };
+#pragma unroll
+    for (int s = 0; s < D; ++s) issue(s, s);
+    __builtin_amdgcn_sched_barrier(0);
+    TSTAMP(2)
+
+    u_tile_finish<BM, EU, true>(it, a.flags, tid, tp, sb, mreg, tvec, Ms, utile);
+    if (tid < BM) xd[tid] = xdreg;
+    TSTAMP(3)
+
+    i32x16 acc[LIMBS][MB];
+#pragma unroll
+    for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[l][mb][q] = 0;
+    for (int j0 = 0; j0 < n; j0 += D) {
+#pragma unroll
+        for (int s = 0; s < D; ++s) {
+            // a slot past the last chunk holds zeros: its products add nothing
+#pragma unroll
+            for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    acc[l][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8((i32x4)xr[s][l][mb], (i32x4)wr[s], acc[l][mb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            issue(j0 + s + D, s);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    TSTAMP(4)
+    lds_barrier();            // the prologue's matrices have been read by everyone: the area becomes the reduction slots
+#pragma unroll
+    for (int l = 0; l < LIMBS; ++l)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) red[(((wave * LIMBS + l) * MB + mb) * 16 + q) * 64 + lane] = acc[l][mb][q];
+    lds_barrier();
+    // element (row block, q, lane): the integer sums of the two K halves, folded and added as the other decode tiles do
+#pragma unroll
+    for (int i = 0; i < 2 * MB; ++i) {
+        const int e = tid + NT * i, mb = e >> 10, ql = e & 1023;
+        int sum[2][LIMBS];                                 // [K half][limb]
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+            for (int l = 0; l < LIMBS; ++l) {
+                int t = 0;
+#pragma unroll
+                for (int wi = 0; wi < 4; ++wi) {
+                    const int w = 2 * kh + (wi & 1) + 4 * (wi >> 1);       // K half 0: waves 0, 1, 4, 5 (kc % 4 in {0, 1}); half 1: 2, 3, 6, 7
+                    t += red[((w * LIMBS + l) * MB + mb) * 1024 + ql];
+                }
+                sum[kh][l] = t;
+            }
+        float tot;
+        if (LIMBS == 2) tot = fmaf(256.0f, (float)sum[0][0], (float)sum[0][1]) + fmaf(256.0f, (float)sum[1][0], (float)sum[1][1]);
+        else tot = (float)(sum[0][0] + sum[1][0]);
+        totb[e] = tot;
+    }
+    lds_barrier();
+    if (wave >= MB) return;
+    const int mb = wave;
+    bf16x8 ua[2][2];
+    {
+        const unsigned char* up = utile + (size_t)(mb * 32 + l32) * UROW + 16 * h;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int kso = ks * 16 < rp ? ks : 0;
+            ua[ks][0] = *reinterpret_cast<const bf16x8*>(up + kso * 32);
+            ua[ks][1] = *reinterpret_cast<const bf16x8*>(up + 2 * rp + kso * 32);
+        }
+    }
+    f32x16 v;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int rl = mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+        const float sc = xd[rl] * wscale;
+        v[q] = totb[(mb * 16 + q) * 64 + lane] * sc;
+        if (a.flags & ESSA_LORA_ONLY) v[q] = 0.f;
+    }
+    if (!(a.flags & ESSA_BASE_ONLY)) {
+        // rank-r term U_B u_i: bf16 head+tail operands, lo*hi + hi*lo + hi*hi per 16 rank columns
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if (ks * 16 < rp) {
+                const bf16x8 ub_hi = __builtin_bit_cast(bf16x8, ubf[ks][0]);
+                const bf16x8 ub_lo = __builtin_bit_cast(bf16x8, ubf[ks][1]);
+                v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua[ks][1], ub_hi, v, 0, 0, 0);
+                v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua[ks][0], ub_lo, v, 0, 0, 0);
+                v = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua[ks][0], ub_hi, v, 0, 0, 0);
+            }
+        }
+    }
+    // 32 consecutive channels of a row sit in 32 consecutive lanes: 64 or 128 contiguous bytes per store instruction
+    const int o = nb * 32 + l32;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int i = mb * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+        if (i < R && o < dout) {
+            if (YBF16) __builtin_nontemporal_store(f32_to_bf16_bits(v[q]), as_global_w(reinterpret_cast<uint16_t*>(it.Y)) + (size_t)i * dout + o);
+            else __builtin_nontemporal_store(v[q], as_global_w(reinterpret_cast<float*>(it.Y)) + (size_t)i * dout + o);
+        }
+    }
     TSTAMP(5)
 }
 
@@ -1861,6 +2074,39 @@ hipError_t launch_gemm(hipStream_t st, stream_args& a, int32_t* acc_out) {
     return hipGetLastError();
 }
 
+template <int MB, int LIMBS, bool YBF16>
+hipError_t launch_gemm_stream(hipStream_t st, stream_args& a) {
+    int total = 0;
+    for (int g = 0; g < a.n_items; ++g) {
+        a.tile_start[g] = total;
+        total += a.it[g].n_blocks;
+    }
+    for (int g = a.n_items; g <= ESSA_MAX_GROUP; ++g) a.tile_start[g] = total;
+    constexpr size_t smem = stream_smem_bytes<MB, LIMBS>();
+    static_assert(smem <= 160 * 1024, "does not fit the LDS of a CU");
+    auto kern = gemm_i8_stream_kernel<MB, LIMBS, YBF16>;
+    static bool attr_done = false;   // one flag per instantiation
+    if (!attr_done && smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    if (tl_ev_start) hipExtLaunchKernelGGL(kern, dim3(total), dim3(NT), (uint32_t)smem, st, tl_ev_start, tl_ev_stop, 0, a);
+    else hipLaunchKernelGGL(kern, dim3(total), dim3(NT), smem, st, a);
+    return hipGetLastError();
+}
+
+// Row counts up to this take the kernel that streams weights on every CU (int8 weights).  With two blocks of 32 rows per
+// workgroup (MB = 2, 33 .. 64 rows) the same kernel takes 19.2 us per launch at the 7B shapes, as long as the 32-row
+// tiles of gemm_i8_kernel (19.0): the activation limbs, which every workgroup loads for all its rows, are then four
+// fifths of the bytes a CU takes in.  Only MB = 1 is instantiated.
+constexpr int STREAM_MAX_ROWS = 32;
+bool takes_stream_kernel(const stream_args& a) {
+    for (int g = 0; g < a.n_items; ++g)
+        if (a.it[g].quant != ESSA_QUANT_INT8_PERCH || a.it[g].R > STREAM_MAX_ROWS) return false;
+    return a.n_items > 0;
+}
+
 template <int LIMBS, bool YBF16, bool Q4>
 hipError_t launch_gemm_mb(hipStream_t st, stream_args& a, int mb) {
     switch (mb) {
@@ -1954,6 +2200,8 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
     a.limbs = (flags & ESSA_COMPUTE_W8A8) ? 1 : 2;
     // rows in the thousands on their way to the 128 x 256 kernel: the prep kernel finishes u itself
     const bool to_big = items[0].quant != ESSA_QUANT_INT4_G128 && takes_big(a);
+    const bool to_stream = takes_stream_kernel(a);
+    a.limb_tiled = to_stream ? 1 : 0;
     const int prep_blocks = fill_prep_tables(a, to_big);
     if (a.u_ready) hipLaunchKernelGGL(prep_kernel<true>, dim3(prep_blocks), dim3(PREP_NT), 0, st, a);
     else hipLaunchKernelGGL(prep_kernel<false>, dim3(prep_blocks), dim3(PREP_NT), 0, st, a);
@@ -1962,7 +2210,15 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
     tl_ev_stop = ev_stop;
     hipError_t e;
     const int q4_rows = items[0].quant == ESSA_QUANT_INT4_G128 ? pick_q4_wide(a) : 0;   // all items of a call share the weight format
-    if (to_big) {
+    if (to_stream) {
+        const bool yb = y_dtype == ESSA_BF16;
+        if (a.limbs == 2) e = yb ? launch_gemm_stream<1, 2, true>(st, a) : launch_gemm_stream<1, 2, false>(st, a);
+        else e = yb ? launch_gemm_stream<1, 1, true>(st, a) : launch_gemm_stream<1, 1, false>(st, a);
+        tl_ev_start = tl_ev_stop = nullptr;
+        if (e != hipSuccess) return e;
+        // the reward partials (one per 128 channels and row) span four of this kernel's workgroups: a pass of their own
+        return essa_k::rowdot_blocks(st, items, n_items, y_dtype);
+    } else if (to_big) {
         if (a.limbs == 2) e = y_dtype == ESSA_BF16 ? launch_gemm_big<2, true>(st, a) : launch_gemm_big<2, false>(st, a);
         else e = y_dtype == ESSA_BF16 ? launch_gemm_big<1, true>(st, a) : launch_gemm_big<1, false>(st, a);
     } else if (q4_rows == 64)

@@ -1379,3 +1379,97 @@ def test_graph_lifetime_rules(essa):
         with pytest.raises(essa.EssaError):
             orphan.launch()
         orphan.close()
+
+
+# ------------------------------------------------------------------------------------------------ row counts up to 64
+@pytest.mark.parametrize("d_in,d_out,r,K", [(320, 200, 8, 5), (3584, 264, 16, 7), (1024, 72, 32, 3)])
+def test_forward_small_row_counts_stream_kernel(essa, ctx, d_in, d_out, r, K):
+    """Up to 32 rows on int8 weights take the kernel that splits K over the waves of a 32-channel workgroup: one row, a
+    few rows, one full block (and one row more, two blocks: the 32-row tiles again); ragged channels; both output
+    types; the one-limb mode; the rank-r term and the base alone; the fused reward (a pass of its own behind this
+    kernel); and the rows of a larger call (64-row tiles, K split in halves) give the same bits in fp32 and bf16."""
+    _say("small row counts d_in=%d d_out=%d r=%d" % (d_in, d_out, r))
+    p = wl.make_projection("t", d_in, d_out, r, "int8", layer=18, proj=r % 4)
+    W, f = oracle_proj(p)
+    gp = gpu_proj(essa, ctx, p)
+    sA, sB = candidate_sigmas(f, K, 0.05)
+    sAd, sBd = to_dev(sA), to_dev(sB)
+    Rbig = 150
+    xb, xv = wl.make_x_bf16(Rbig, d_in, x_id=60)
+    xb[2] = 0
+    xv[2] = 0
+    r2c = np.random.default_rng(8).integers(0, K, Rbig).astype(np.int32)
+    Xd, rd = bf16_dev(xb), to_dev(r2c)
+    ref = orc.svdlora_forward(W, f, xv, r2c, sA, sB)
+    ref8 = orc.svdlora_forward_w8a8(p.Wq, p.scales, f, xv, r2c, sA, sB)
+    big32 = torch.empty(Rbig, d_out, device="cuda")
+    big16 = torch.empty(Rbig, d_out, device="cuda", dtype=torch.bfloat16)
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, big32)           # 150 rows: the 64-row tiles
+    essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, big16)
+    v = wl.reward_vector(d_out, 18, 0)
+    nblk = (d_out + essa.REWARD_BLOCK - 1) // essa.REWARD_BLOCK
+    for R in (1, 8, 31, 32, 33, 64):
+        for start in (0, Rbig - R):
+            sub = slice(start, start + R)
+            Xs, rs = Xd[sub].contiguous(), rd[sub].contiguous()
+            Y32 = torch.empty(R, d_out, device="cuda")
+            Y16 = torch.empty(R, d_out, device="cuda", dtype=torch.bfloat16)
+            essa.essa_svdlora_forward(ctx, gp, Xs, rs, sAd, sBd, Y32)
+            essa.essa_svdlora_forward(ctx, gp, Xs, rs, sAd, sBd, Y16)
+            assert torch.equal(Y32, big32[sub]) and torch.equal(Y16, big16[sub]), (R, start)
+            e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref[sub])
+            assert e_rms <= LIMB_RMS and e_max <= LIMB_MAX, (R, start, e_max, e_rms)
+            if R > 4:
+                e_max, e_rms = orc.rel_errors(bf16_host(Y16), orc.round_to_bf16(ref[sub]))
+                assert e_rms <= 2 * BF16_RMS and e_max <= BF16_MAX, (R, start, e_max, e_rms)   # few elements: see the whole-tensor check below
+            essa.essa_svdlora_forward(ctx, gp, Xs, rs, sAd, sBd, Y32, essa.COMPUTE_W8A8)
+            e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), ref8[sub])
+            assert e_rms <= EXACT_RMS and e_max <= EXACT_MAX, ("w8a8", R, start, e_max, e_rms)
+            essa.essa_svdlora_forward(ctx, gp, Xs, rs, sAd, sBd, Y32, essa.LORA_ONLY)
+            e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), orc.svdlora_forward(W, f, xv[sub], r2c[sub], sA, sB, lora_only=True))
+            assert e_rms <= 1e-4 and e_max <= 1e-3, ("lora only", R, start)
+            essa.essa_svdlora_forward(ctx, gp, Xs, rs, sAd, sBd, Y32, essa.BASE_ONLY)
+            e_max, e_rms = orc.rel_errors(Y32.cpu().numpy(), xv[sub].astype(np.float64) @ W.T)
+            assert e_rms <= LIMB_RMS and e_max <= LIMB_MAX, ("base only", R, start)
+            # the fused reward: the partials of every 128-channel block, same bits as those of the larger call's rows
+            rowpart = torch.full((nblk + 1, R), float("nan"), device="cuda")
+            grp = essa.ForwardGroup([(gp, Xs, rs, sAd, sBd, Y16)], [to_dev(v)])
+            assert essa.essa_svdlora_forward_reward_group(ctx, grp, None, rowpart) == nblk
+            assert torch.equal(Y16, big16[sub])
+            assert not torch.isnan(rowpart[:nblk]).any() and torch.isnan(rowpart[nblk]).all()
+            yv = bf16_host(Y16)
+            for b in range(nblk):
+                want = yv[:, 128 * b:128 * (b + 1)] @ v[128 * b:128 * (b + 1)].astype(np.float64)
+                np.testing.assert_allclose(rowpart[b].cpu().numpy(), want, rtol=2e-5, atol=1e-5 * np.abs(want).max())
+    e_max, e_rms = orc.rel_errors(bf16_host(big16), orc.round_to_bf16(ref))
+    assert e_rms <= BF16_RMS and e_max <= BF16_MAX
+    gp.close()
+
+
+def test_forward_small_row_counts_grouped_mixed_rows(essa, ctx):
+    """A grouped call whose items have different small row counts (10, 25 and 32 rows; rows past an item's own count are
+    never loaded) and ranks, q/k/v-like sharing of one X between two items."""
+    d_in, K = 768, 6
+    specs = [(200, 16, 25), (96, 8, 25), (328, 32, 10), (64, 4, 32)]                  # (d_out, rank, rows)
+    xs = {R: wl.make_x_bf16(R, d_in, x_id=70 + R) for R in (10, 25, 32)}
+    r2cs = {R: np.random.default_rng(R).integers(0, K, R).astype(np.int32) for R in (10, 25, 32)}
+    Xd = {R: bf16_dev(xs[R][0]) for R in xs}
+    rd = {R: to_dev(r2cs[R]) for R in xs}
+    items, refs, gps = [], [], []
+    for pi, (d_out, r, R) in enumerate(specs):
+        p = wl.make_projection("t", d_in, d_out, r, "int8", layer=19, proj=pi)
+        W, f = oracle_proj(p)
+        gp = gpu_proj(essa, ctx, p)
+        sA, sB = candidate_sigmas(f, K, 0.05, pert_id=pi)
+        items.append((gp, Xd[R], rd[R], to_dev(sA), to_dev(sB), torch.empty(R, d_out, device="cuda")))
+        refs.append(orc.svdlora_forward(W, f, xs[R][1], r2cs[R], sA, sB))
+        gps.append(gp)
+    essa.essa_svdlora_forward_group(ctx, items)
+    for it, ref in zip(items, refs):
+        e_max, e_rms = orc.rel_errors(it[5].cpu().numpy(), ref)
+        assert e_rms <= LIMB_RMS and e_max <= LIMB_MAX, (e_max, e_rms)
+        Y1 = torch.empty_like(it[5])
+        essa.essa_svdlora_forward(ctx, it[0], it[1], it[2], it[3], it[4], Y1)
+        assert torch.equal(Y1, it[5])
+    for gp in gps:
+        gp.close()
