@@ -31,7 +31,10 @@ published algorithm; moment / range checks of the normals; closed-form CMA-ES
 constants; forward invariants (own singular values give W + B A from the
 unfactored factors, zero singular values give the base layer, brute-force
 dense products on tiny shapes, linearity, row permutation); CMA-ES invariants
-and convergence on sphere / ellipsoid; the eigendecomposition against closed forms (2 x 2, diagonal,
+and convergence on sphere / ellipsoid; the stalled step (h_sigma = 0) against a closed form
+(with C = p_c p_c^T the update is (1 - c_mu) C + c_mu sum w_i y_i y_i^T) and the threshold that
+decides it; the W8A8 composition against a hand-worked 2 x 3 case and within its quantisation bound
+of the fp64 forward; the eigendecomposition against closed forms (2 x 2, diagonal,
 known spectrum) and its defining identities.  The exact CMA-ES variant the paper ran
 (an external library's defaults) cannot be checked here: against that library
 the update is PARITY UNPINNED; it is pinned to the tutorial's equations only.

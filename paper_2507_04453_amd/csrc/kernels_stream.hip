@@ -916,16 +916,22 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
     unsigned char* utile = smem + BIG + BM * 4;                        // [BM][UROW] bf16 head+tail of u_i
 
     QSTAMP(0)
+    // Blocks go round-robin over the 8 XCDs, each with an L2 of its own.  XCD x takes the contiguous range
+    // [x T/8, (x+1) T/8) of the group's T tiles (row tile fastest, then column tile, then item): the row tiles that share a
+    // weight tile sit behind one L2 and start together, no weight tile is read behind two L2s, and an XCD whose range lies
+    // inside the items that read one X (q, k, v) never touches the limbs of the other (o).
+    const int total = a.tile_start[ESSA_MAX_GROUP];
+    int b = blockIdx.x;
+    const bool by_group = (total & 7) == 0;
+    if (by_group) b = (b & 7) * (total >> 3) + (b >> 3);
     // which item this tile belongs to: the whole table comes in with one scalar load, the count is branch-free
     int g = 0;
 #pragma unroll
-    for (int i = 1; i < ESSA_MAX_GROUP; ++i) g += (i < a.n_items && (int)blockIdx.x >= a.tile_start[i]) ? 1 : 0;
+    for (int i = 1; i < ESSA_MAX_GROUP; ++i) g += (i < a.n_items && b >= a.tile_start[i]) ? 1 : 0;
     const fwd_item it = fetch_item(a.it[g]);
-    // blocks go round-robin over the 8 XCDs; give each XCD a contiguous range of tiles so that the row
-    // tiles sharing a weight tile sit behind the same L2
     const int ntile = a.tile_start[g + 1] - a.tile_start[g];
-    int tile = blockIdx.x - a.tile_start[g];
-    if ((ntile & 7) == 0 && (a.tile_start[g] & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);
+    int tile = b - a.tile_start[g];
+    if (!by_group && (ntile & 7) == 0 && (a.tile_start[g] & 7) == 0) tile = (tile & 7) * (ntile >> 3) + (tile >> 3);   // per item, where that works
     const int tiles_m = (it.R + BM - 1) / BM;
     const int m0 = (tile % tiles_m) * BM, nb0 = (tile / tiles_m) * 4;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -2057,7 +2063,7 @@ hipError_t launch_gemm(hipStream_t st, stream_args& a, int32_t* acc_out) {
         a.tile_start[g] = total;
         total += ((a.it[g].R + 32 * MB - 1) / (32 * MB)) * ((a.it[g].n_blocks + 3) / 4);
     }
-    a.tile_start[a.n_items] = total;
+    for (int g = a.n_items; g <= ESSA_MAX_GROUP; ++g) a.tile_start[g] = total;   // the last entry is the grid size
     constexpr size_t smem = gemm_smem_bytes<MB, LIMBS, YBF16, Q4>();
     static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
     auto kern = gemm_i8_kernel<MB, LIMBS, YBF16, DUMP, Q4>;
