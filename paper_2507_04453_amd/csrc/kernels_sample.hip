@@ -136,6 +136,8 @@ __global__ void theta_to_sigma_kernel(int P, int r, int n_top, const float* __re
 // loads four consecutive floats of its row, which feed four MFMA steps) and their partial tiles are summed
 // through LDS in a fixed order (bit-reproducible).  B is read exactly once when J <= 16 * JB.
 constexpr int SG_WAVES = 8;
+constexpr int SG_BUNCH = 14;         // chunks of B a wave asks for at once (n = 3584: 28 chunks per wave, two bunches)
+constexpr int SG_AHEAD = 4;          // chunks of S in flight ahead of their MFMAs
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 template <bool ALIGNED, int JB>
 __global__ __launch_bounds__(SG_WAVES * 64) void skinny_gemm_nt_kernel(const float* __restrict__ S, int J, const float* __restrict__ B,
@@ -164,22 +166,73 @@ __global__ __launch_bounds__(SG_WAVES * 64) void skinny_gemm_nt_kernel(const flo
         }
         return v;
     };
-    for (int ch0 = wave; ch0 < nchunks; ch0 += 2 * SG_WAVES) {
-        // two chunks per trip: all their loads are issued before the first MFMA
-        f32x4 a[2], sv[2][JB];
+    // A wave walks its chunks (wave, wave + 8, ...) in ascending order.
+    if constexpr (ALIGNED) {
+        // Buffer loads: a row or a chunk past the end is an offset outside the descriptor and comes back as zeros, so there
+        // is no branch around any load and the compiler can count them.  The B fragments of SG_BUNCH chunks are asked for
+        // together and the S fragments then stream past them a few chunks ahead of their MFMAs: a CU's loads complete in
+        // order, B comes from HBM and S out of the L2, and S loads spread evenly between B loads would all move at HBM
+        // latency.  (n <= 16384 on this path: both matrices stay below the descriptor's 2 GB.)
+        typedef __amdgpu_buffer_rsrc_t rsrc_t;
+        constexpr uint32_t OUT_OF_RANGE = 0x80000000u;
+        const rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(B), 0, (uint32_t)n * (uint32_t)n * 4u, 0x00020000);
+        const rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(S), 0, (uint32_t)J * (uint32_t)n * 4u, 0x00020000);
+        const uint32_t brow = (uint32_t)i * (uint32_t)n * 4u;                    // i >= n: beyond the descriptor
+        uint32_t srow[JB];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int l = (ch0 + u * SG_WAVES) * 16 + 4 * kq;      // past the end: l >= n, everything loads as zero
-            a[u] = load4(B, i, n, l);
+        for (int jb = 0; jb < JB; ++jb) srow[jb] = (uint32_t)(j0 + 16 * jb + l16) * (uint32_t)n * 4u;
+        auto ld = [&](rsrc_t r, uint32_t row_off, int chunk) {
+            const int l = chunk * 16 + 4 * kq;
+            const uint32_t off = l < n ? row_off + (uint32_t)l * 4u : OUT_OF_RANGE;
+            const auto v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+            f32x4 f;
+            __builtin_memcpy(&f, &v, 16);
+            return f;
+        };
+        for (int base = wave; base < nchunks; base += SG_BUNCH * SG_WAVES) {
+            f32x4 a[SG_BUNCH], sv[SG_AHEAD][JB];
 #pragma unroll
-            for (int jb = 0; jb < JB; ++jb) sv[u][jb] = load4(S, j0 + 16 * jb + l16, J, l);
+            for (int u = 0; u < SG_BUNCH; ++u) a[u] = ld(rb, brow, base + u * SG_WAVES);
+            __builtin_amdgcn_sched_barrier(0);              // left alone, the compiler moves every load down to its first use
+#pragma unroll
+            for (int u = 0; u < SG_AHEAD; ++u)
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) sv[u][jb] = ld(rs, srow[jb], base + u * SG_WAVES);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < SG_BUNCH; ++u) {
+                f32x4 cur[JB];
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) cur[jb] = sv[u % SG_AHEAD][jb];
+                if (u + SG_AHEAD < SG_BUNCH) {
+#pragma unroll
+                    for (int jb = 0; jb < JB; ++jb) sv[u % SG_AHEAD][jb] = ld(rs, srow[jb], base + (u + SG_AHEAD) * SG_WAVES);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int jb = 0; jb < JB; ++jb) acc[jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][e], cur[jb][e], acc[jb], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
+    } else {
+        for (int ch0 = wave; ch0 < nchunks; ch0 += 2 * SG_WAVES) {
+            // two chunks per trip: all their loads are issued before the first MFMA
+            f32x4 a[2], sv[2][JB];
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+            for (int u = 0; u < 2; ++u) {
+                const int l = (ch0 + u * SG_WAVES) * 16 + 4 * kq;      // past the end: l >= n, everything loads as zero
+                a[u] = load4(B, i, n, l);
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
+                for (int jb = 0; jb < JB; ++jb) sv[u][jb] = load4(S, j0 + 16 * jb + l16, J, l);
+            }
 #pragma unroll
-                for (int jb = 0; jb < JB; ++jb) acc[jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][e], sv[u][jb][e], acc[jb], 0, 0, 0);
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int jb = 0; jb < JB; ++jb) acc[jb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][e], sv[u][jb][e], acc[jb], 0, 0, 0);
+        }
     }
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb)
