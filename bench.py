@@ -290,7 +290,7 @@ class Bench:
         if self.cfg.quant == "int8":
             if -(-R // 128) * col256 >= 512:
                 return "gemm_i8_big_kernel"
-            return "gemm_i8_stream_kernel" if R <= 32 else "gemm_i8_kernel"
+            return "gemm_i8_stream_kernel" if R <= 64 else "gemm_i8_kernel"
         return "gemm_q4_wide_kernel" if -(-R // 64) * col256 >= 256 else "gemm_i8_kernel<Q4>"
 
     def config(self):

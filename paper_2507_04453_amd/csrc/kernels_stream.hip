@@ -1300,10 +1300,11 @@ constexpr size_t stream_smem_bytes() { return (size_t)8 * LIMBS * MB * 4096 + (s
 template <int MB, int LIMBS, bool YBF16>
 __global__ __launch_bounds__(NT, 1) void gemm_i8_stream_kernel(stream_args a) {
     constexpr int BM = 32 * MB;
-    // chunks in flight per wave.  Deeper does not help (all 14 chunks of a 3584-wide row at once: 14.3 against 12.5 us):
-    // a CU's vector-memory path takes 64 B per clock, i.e. 16 clocks per kilobyte-sized load instruction, so the 24
-    // loads of 8 chunks already take the 8 waves 1.4 us to issue, about the time the first of them needs to come back
-    constexpr int D = MB == 1 ? 8 : 6;
+    // A wave asks for the weights of NW of its chunks at once and then lets the activation limbs of those chunks stream past,
+    // DX chunks ahead of their MFMAs.  A CU's loads complete in order: weights come from HBM, limbs out of the L2, and limb
+    // loads issued between weight loads would each wait for the weight load in front of them.
+    constexpr int NW = 16;                                 // 16 chunks per wave = 4096 columns: one bunch at the 7B and 8B shapes
+    constexpr int DX = 4;
     constexpr size_t RED = (size_t)8 * LIMBS * MB * 4096;  // the 8 waves' partial sums; before the loop: t vectors and the core matrix
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int* red = reinterpret_cast<int*>(smem);               // [wave][limb][row block][q][lane]
@@ -1360,19 +1361,25 @@ __global__ __launch_bounds__(NT, 1) void gemm_i8_stream_kernel(stream_args a) {
     __builtin_amdgcn_sched_barrier(0);
     TSTAMP(1)
 
-    // the ring: slot s holds chunk j = s, s + D, ... of this wave (K chunk kc = wave + 8 j)
-    u32x4 wr[D], xr[D][LIMBS][MB];
-    auto issue = [&](int j, int slot) {
+    // chunk j of this wave is K chunk kc = wave + 8 j; a chunk past the last one is asked for outside the descriptor (zeros,
+    // no memory access), and its products add nothing
+    u32x4 wr[NW], xr[DX][LIMBS][MB];
+    auto issue_w = [&](int j, int slot) {
         const uint32_t gone = j < n ? 0u : OUT_OF_RANGE;   // wave-uniform
-        const uint32_t kc = (uint32_t)(wave + 8 * j);
-        wr[slot] = load16(wbase, lane16 | gone, kc * wstride_b);
+        wr[slot] = load16(wbase, lane16 | gone, (uint32_t)(wave + 8 * j) * wstride_b);
+    };
+    auto issue_x = [&](int j, int slot) {
+        const uint32_t gone = j < n ? 0u : OUT_OF_RANGE;
 #pragma unroll
         for (int l = 0; l < LIMBS; ++l)
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) xr[slot][l][mb] = load16(xbase[l], xoff[mb] | gone, kc * 1024u);
+            for (int mb = 0; mb < MB; ++mb) xr[slot][l][mb] = load16(xbase[l], xoff[mb] | gone, (uint32_t)(wave + 8 * j) * 1024u);
     };
 #pragma unroll
-    for (int s = 0; s < D; ++s) issue(s, s);
+    for (int s = 0; s < NW; ++s) issue_w(s, s);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < DX; ++s) issue_x(s, s);
     __builtin_amdgcn_sched_barrier(0);
     TSTAMP(2)
 
@@ -1387,17 +1394,24 @@ __global__ __launch_bounds__(NT, 1) void gemm_i8_stream_kernel(stream_args a) {
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[l][mb][q] = 0;
-    for (int j0 = 0; j0 < n; j0 += D) {
+    for (int j0 = 0; j0 < n; j0 += NW) {
+        if (j0 > 0) {                                      // rows wider than 4096: the next bunch of weights, then its first limbs
 #pragma unroll
-        for (int s = 0; s < D; ++s) {
-            // a slot past the last chunk holds zeros: its products add nothing
+            for (int s = 0; s < NW; ++s) issue_w(j0 + s, s);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < DX; ++s) issue_x(j0 + s, s);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int s = 0; s < NW; ++s) {
 #pragma unroll
             for (int l = 0; l < LIMBS; ++l)
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
-                    acc[l][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8((i32x4)xr[s][l][mb], (i32x4)wr[s], acc[l][mb], 0, 0, 0);
+                    acc[l][mb] = __builtin_amdgcn_mfma_i32_32x32x32_i8((i32x4)xr[s % DX][l][mb], (i32x4)wr[s], acc[l][mb], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            issue(j0 + s + D, s);
+            if (s + DX < NW) issue_x(j0 + s + DX, s % DX);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -2102,15 +2116,20 @@ hipError_t launch_gemm_stream(hipStream_t st, stream_args& a) {
     return hipGetLastError();
 }
 
-// Row counts up to this take the kernel that streams weights on every CU (int8 weights).  With two blocks of 32 rows per
-// workgroup (MB = 2, 33 .. 64 rows) the same kernel takes 19.2 us per launch at the 7B shapes, as long as the 32-row
-// tiles of gemm_i8_kernel (19.0): the activation limbs, which every workgroup loads for all its rows, are then four
-// fifths of the bytes a CU takes in.  Only MB = 1 is instantiated.
-constexpr int STREAM_MAX_ROWS = 32;
+// Row counts up to this take the kernel that streams weights on every CU (int8 weights), with one block of 32 rows per
+// workgroup or two.  At the 7B shapes two row blocks take 17.3 us per launch at 64 rows against 18.7 for the 32-row tiles of
+// gemm_i8_kernel; the activation limbs, which every workgroup loads for all its rows, are then four fifths of the bytes a
+// CU takes in, and four row blocks (128 rows) would need more registers than a wave has.
+constexpr int STREAM_MAX_ROWS = 64;
 bool takes_stream_kernel(const stream_args& a) {
     for (int g = 0; g < a.n_items; ++g)
         if (a.it[g].quant != ESSA_QUANT_INT8_PERCH || a.it[g].R > STREAM_MAX_ROWS) return false;
     return a.n_items > 0;
+}
+int stream_row_blocks(const stream_args& a) {
+    int r = 0;
+    for (int g = 0; g < a.n_items; ++g) r = std::max(r, a.it[g].R);
+    return r > 32 ? 2 : 1;
 }
 
 template <int LIMBS, bool YBF16, bool Q4>
@@ -2218,7 +2237,10 @@ hipError_t forward_stream(hipStream_t st, const fwd_item* items, int n_items, in
     const int q4_rows = items[0].quant == ESSA_QUANT_INT4_G128 ? pick_q4_wide(a) : 0;   // all items of a call share the weight format
     if (to_stream) {
         const bool yb = y_dtype == ESSA_BF16;
-        if (a.limbs == 2) e = yb ? launch_gemm_stream<1, 2, true>(st, a) : launch_gemm_stream<1, 2, false>(st, a);
+        if (stream_row_blocks(a) == 2) {
+            if (a.limbs == 2) e = yb ? launch_gemm_stream<2, 2, true>(st, a) : launch_gemm_stream<2, 2, false>(st, a);
+            else e = yb ? launch_gemm_stream<2, 1, true>(st, a) : launch_gemm_stream<2, 1, false>(st, a);
+        } else if (a.limbs == 2) e = yb ? launch_gemm_stream<1, 2, true>(st, a) : launch_gemm_stream<1, 2, false>(st, a);
         else e = yb ? launch_gemm_stream<1, 1, true>(st, a) : launch_gemm_stream<1, 1, false>(st, a);
         tl_ev_start = tl_ev_stop = nullptr;
         if (e != hipSuccess) return e;

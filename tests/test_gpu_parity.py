@@ -1384,10 +1384,11 @@ def test_graph_lifetime_rules(essa):
 # ------------------------------------------------------------------------------------------------ row counts up to 64
 @pytest.mark.parametrize("d_in,d_out,r,K", [(320, 200, 8, 5), (3584, 264, 16, 7), (1024, 72, 32, 3)])
 def test_forward_small_row_counts_stream_kernel(essa, ctx, d_in, d_out, r, K):
-    """Up to 32 rows on int8 weights take the kernel that splits K over the waves of a 32-channel workgroup: one row, a
-    few rows, one full block (and one row more, two blocks: the 32-row tiles again); ragged channels; both output
-    types; the one-limb mode; the rank-r term and the base alone; the fused reward (a pass of its own behind this
-    kernel); and the rows of a larger call (64-row tiles, K split in halves) give the same bits in fp32 and bf16."""
+    """Up to 64 rows on int8 weights take the kernel that splits K over the waves of a 32-channel workgroup, with one
+    block of 32 rows or two: one row, a few rows, one full block, one row more (two blocks), two full blocks, and one row
+    more (the 32-row tiles again); ragged channels; both output types; the one-limb mode; the rank-r term and the base
+    alone; the fused reward (a pass of its own behind this kernel); and the rows of a larger call (64-row tiles, K split in
+    halves) give the same bits in fp32 and bf16."""
     _say("small row counts d_in=%d d_out=%d r=%d" % (d_in, d_out, r))
     p = wl.make_projection("t", d_in, d_out, r, "int8", layer=18, proj=r % 4)
     W, f = oracle_proj(p)
@@ -1408,7 +1409,7 @@ def test_forward_small_row_counts_stream_kernel(essa, ctx, d_in, d_out, r, K):
     essa.essa_svdlora_forward(ctx, gp, Xd, rd, sAd, sBd, big16)
     v = wl.reward_vector(d_out, 18, 0)
     nblk = (d_out + essa.REWARD_BLOCK - 1) // essa.REWARD_BLOCK
-    for R in (1, 8, 31, 32, 33, 64):
+    for R in (1, 8, 31, 32, 33, 48, 64, 65):
         for start in (0, Rbig - R):
             sub = slice(start, start + R)
             Xs, rs = Xd[sub].contiguous(), rd[sub].contiguous()
@@ -1446,13 +1447,16 @@ def test_forward_small_row_counts_stream_kernel(essa, ctx, d_in, d_out, r, K):
     gp.close()
 
 
-def test_forward_small_row_counts_grouped_mixed_rows(essa, ctx):
-    """A grouped call whose items have different small row counts (10, 25 and 32 rows; rows past an item's own count are
-    never loaded) and ranks, q/k/v-like sharing of one X between two items."""
+@pytest.mark.parametrize("specs", [[(200, 16, 25), (96, 8, 25), (328, 32, 10), (64, 4, 32)],
+                                   [(200, 16, 25), (96, 8, 25), (328, 32, 50), (64, 4, 64)]], ids=["one_row_block", "two_row_blocks"])
+def test_forward_small_row_counts_grouped_mixed_rows(essa, ctx, specs):
+    """A grouped call whose items ((d_out, rank, rows)) have different small row counts and ranks, q/k/v-like sharing of one
+    X between two items: rows past an item's own count are never loaded, also when the group as a whole takes two row
+    blocks per workgroup and an item fills only the first; each item alone gives the same bits."""
     d_in, K = 768, 6
-    specs = [(200, 16, 25), (96, 8, 25), (328, 32, 10), (64, 4, 32)]                  # (d_out, rank, rows)
-    xs = {R: wl.make_x_bf16(R, d_in, x_id=70 + R) for R in (10, 25, 32)}
-    r2cs = {R: np.random.default_rng(R).integers(0, K, R).astype(np.int32) for R in (10, 25, 32)}
+    rows = sorted({R for _, _, R in specs})
+    xs = {R: wl.make_x_bf16(R, d_in, x_id=70 + R) for R in rows}
+    r2cs = {R: np.random.default_rng(R).integers(0, K, R).astype(np.int32) for R in rows}
     Xd = {R: bf16_dev(xs[R][0]) for R in xs}
     rd = {R: to_dev(r2cs[R]) for R in xs}
     items, refs, gps = [], [], []
