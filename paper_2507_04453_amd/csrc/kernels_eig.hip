@@ -17,6 +17,7 @@ constexpr int EB = 32;             // columns per block
 constexpr int EP = 2 * EB;         // columns per panel
 constexpr int ER = 64;             // rows per LDS chunk
 constexpr int EPITCH = ER + 1;     // LDS pitch (doubles)
+typedef __attribute__((ext_vector_type(4))) double f64x4;
 
 // round-robin tournament over nblk players (nblk even): the p-th pair of round `round`
 __device__ __forceinline__ void pair_of(int nblk, int round, int p, int& I, int& J) {
@@ -81,12 +82,15 @@ __global__ __launch_bounds__(256) void eig_gram_kernel(const double* __restrict_
     const int pair = blockIdx.x, slice = blockIdx.y, S = gridDim.y, tid = threadIdx.x;
     int I, J;
     pair_of(nblk, round, pair, I, J);
-    const int ta = tid >> 4, tb = tid & 15;
-    double acc[4][4];
+    // fp64 MFMA 16x16x4: wave w owns rows 16w .. 16w+15 of G (all four 16-column blocks).  Operand element (i, k) and (k, j)
+    // sit in lane i + 16 k resp. j + 16 k; with A[i][k] = P[r0 + k][16w + i] and B[k][j] = P[r0 + k][16jb + j] both operands
+    // are T[column][row] read at [16 x + lane % 16][rr + lane / 16].  Accumulator element v of a lane is G[16w + 4 v +
+    // lane / 16][16jb + lane % 16] (the fp64 form's own order: not that of the fp32 16x16x4).  (The vector and the matrix unit have the same fp64 rate on this chip; the MFMA needs a sixth of
+    // the LDS reads per product.)
+    const int wave = tid >> 6, lane = tid & 63, l16 = lane & 15, kq = lane >> 4;
+    f64x4 acc[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+    for (int jb = 0; jb < 4; ++jb) acc[jb] = (f64x4){0.0, 0.0, 0.0, 0.0};
     for (int ch = 0; ch < chunks_per_slice; ++ch) {
         const int r0 = (slice * chunks_per_slice + ch) * ER;
         if (r0 >= n) break;                                    // uniform for the workgroup
@@ -96,22 +100,21 @@ __global__ __launch_bounds__(256) void eig_gram_kernel(const double* __restrict_
         }
         __syncthreads();
 #pragma unroll 4
-        for (int rr = 0; rr < ER; ++rr) {
-            double a[4], b[4];
+        for (int rr = 0; rr < ER; rr += 4) {
+            double f[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { a[i] = T[4 * ta + i][rr]; b[i] = T[4 * tb + i][rr]; }
+            for (int jb = 0; jb < 4; ++jb) f[jb] = T[16 * jb + l16][rr + kq];
+            const double a = T[16 * wave + l16][rr + kq];      // (one of the four above; read again rather than selected)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
+            for (int jb = 0; jb < 4; ++jb) acc[jb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, f[jb], acc[jb], 0, 0, 0);
         }
         __syncthreads();
     }
     double* out = Gpart + ((size_t)pair * S + slice) * EP * EP;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int jb = 0; jb < 4; ++jb)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) out[(4 * ta + i) * EP + 4 * tb + j] = acc[i][j];
+        for (int v = 0; v < 4; ++v) out[(16 * wave + 4 * v + kq) * EP + 16 * jb + l16] = acc[jb][v];
 }
 
 // Diagonalises the 64 x 64 Gram matrix of every panel: cyclic two-sided Jacobi in LDS, 32 disjoint rotations per step
@@ -217,7 +220,10 @@ __global__ __launch_bounds__(256) void eig_update_kernel(double* __restrict__ At
     pair_of(nblk, round, pair, I, J);
     const double* qsrc = Qin + (size_t)pair * EP * EP;
     for (int idx = tid; idx < EP * EP; idx += 256) Qs[idx >> 6][idx & 63] = qsrc[idx];      // Qs[c][c'] = Q[c][c']
-    const int tc = tid >> 4, tr = tid & 15;                    // output columns 4 tc.., rows 4 tr..
+    // fp64 MFMA 16x16x4: wave w owns rows 16w .. 16w+15 of the chunk for all 64 new columns.  out[c'][row] = sum_c Q[c][c']
+    // T[c][row]: A[i][k] = Q[kk + k][16ib + i], B[k][j] = T[kk + k][16w + j]; accumulator element v of a lane is new column
+    // 16ib + 4 v + lane / 16 at row 16w + lane % 16.
+    const int wave = tid >> 6, lane = tid & 63, l16 = lane & 15, kq = lane >> 4;
     for (int ch = 0; ch < UCH; ++ch) {
         const int r0 = (blockIdx.y * UCH + ch) * ER;
         if (r0 >= n) break;                                    // uniform for the workgroup
@@ -227,28 +233,22 @@ __global__ __launch_bounds__(256) void eig_update_kernel(double* __restrict__ At
             T[c][rr] = row < n ? M[(size_t)panel_col(I, J, c) * ld + row] : 0.0;
         }
         __syncthreads();
-        double acc[4][4];
+        f64x4 acc[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+        for (int ib = 0; ib < 4; ++ib) acc[ib] = (f64x4){0.0, 0.0, 0.0, 0.0};
 #pragma unroll 4
-        for (int c = 0; c < EP; ++c) {
-            double qv[4], tv[4];
+        for (int kk = 0; kk < EP; kk += 4) {
+            const double b = T[kk + kq][16 * wave + l16];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { qv[i] = Qs[c][4 * tc + i]; tv[i] = T[c][4 * tr + i]; }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fma(qv[i], tv[j], acc[i][j]);
+            for (int ib = 0; ib < 4; ++ib) acc[ib] = __builtin_amdgcn_mfma_f64_16x16x4f64(Qs[kk + kq][16 * ib + l16], b, acc[ib], 0, 0, 0);
         }
+        const int row = r0 + 16 * wave + l16;
+        if (row < n) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+            for (int ib = 0; ib < 4; ++ib)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int row = r0 + 4 * tr + j;
-                if (row < n) M[(size_t)panel_col(I, J, 4 * tc + i) * ld + row] = acc[i][j];
-            }
+                for (int v = 0; v < 4; ++v) M[(size_t)panel_col(I, J, 16 * ib + 4 * v + kq) * ld + row] = acc[ib][v];
+        }
     }
 }
 
@@ -317,7 +317,7 @@ hipError_t eig_refresh(hipStream_t st, const float* C, int n, void* ws, double* 
         hipLaunchKernelGGL(eig_clear_kernel, dim3(1), dim3(1), 0, st, flag);
         for (int round = 0; round < nblk - 1; ++round) {
             hipLaunchKernelGGL(eig_gram_kernel, dim3(npairs, S), dim3(256), 0, st, At, ld, n, nblk, round, chunks_per_slice, Gpart);
-            hipLaunchKernelGGL(eig_small_kernel, dim3(npairs), dim3(SMALL_NT), two_mats, st, Gpart, S, Q, flag, 12, 1e-15);
+            hipLaunchKernelGGL(eig_small_kernel, dim3(npairs), dim3(SMALL_NT), two_mats, st, Gpart, S, Q, flag, 4, 1e-15);
             hipLaunchKernelGGL(eig_update_kernel, dim3(npairs, (chunks + UCH - 1) / UCH, 2), dim3(256), two_mats, st, At, Vt, ld, n, nblk, round, Q);
         }
         unsigned bits = 0;
