@@ -99,6 +99,16 @@ __global__ __launch_bounds__(256) void cma_cov_kernel(essa_k::cma_consts c, cons
     const int i0 = blockIdx.y * CV_T, j0 = blockIdx.x * CV_T;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     float acc[4][4] = {};
+    // the tile of C is asked for first: it comes from HBM while the rank-one terms are added up
+    const int j = j0 + tx * 4;
+    const bool vec = (n % 4 == 0) && j + 3 < n;
+    float4 cold[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int i = i0 + ty * 4 + x;
+        cold[x] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (vec && i < n) cold[x] = *reinterpret_cast<const float4*>(C + (size_t)i * n + j);
+    }
     const int nvec = mu + 1;   // vector mu is p_c with coefficient c_1
     for (int v0 = 0; v0 < nvec; v0 += CV_CH) {
         __syncthreads();
@@ -135,15 +145,13 @@ __global__ __launch_bounds__(256) void cma_cov_kernel(essa_k::cma_consts c, cons
     }
     const float hs = sc->h_sigma;
     const float decay = 1.0f - c.c_1 - c.c_mu * c.w_sum + (1.0f - hs) * c.c_1 * c.c_c * (2.0f - c.c_c);
-    const int j = j0 + tx * 4;
-    const bool vec = (n % 4 == 0) && j + 3 < n;
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
         const int i = i0 + ty * 4 + x;
         if (i >= n) continue;
         if (vec) {
             float4* p = reinterpret_cast<float4*>(C + (size_t)i * n + j);
-            float4 cv = *p;
+            float4 cv = cold[x];
             cv.x = decay * cv.x + acc[x][0];
             cv.y = decay * cv.y + acc[x][1];
             cv.z = decay * cv.z + acc[x][2];
