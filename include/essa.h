@@ -334,7 +334,8 @@ essa_status essa_cmaes_update(essa_ctx* ctx, essa_cma* cma, const uint32_t* seed
  * updates).  Replaces the state's (B, D): columns of B are orthonormal eigenvectors (order and signs unspecified),
  * D the square roots of the eigenvalues (negative round-off clamped to zero).  C itself is left alone (it is read as
  * (C + C^T) / 2).  One-sided block Jacobi in fp64; sweeps until the largest |a_i . a_j| / (|a_i| |a_j|) over all
- * pairs of columns of C V met during a sweep is <= tol, at most max_sweeps (1..64) times.  The state keeps the basis of
+ * pairs of columns of C V met during a sweep is <= tol, at most max_sweeps (1..64) times; pairs already below tol / 100
+ * are left alone, so a C that has not moved since the last refresh costs one pass over it.  The state keeps the basis of
  * its last refresh in fp64 and the next refresh starts from it (a few sweeps when C has moved little); after
  * essa_cma_set_basis or essa_cma_import the next refresh starts from the identity.  Off the per-generation
  * path: the tutorial refreshes the basis every 1 / (10 n (c_1 + c_mu)) generations.  The call waits for the device

@@ -125,15 +125,17 @@ __global__ __launch_bounds__(256) void eig_gram_kernel(const double* __restrict_
 // integer maximum orders them).
 constexpr int SMALL_NT = 1024;
 __global__ __launch_bounds__(SMALL_NT) void eig_small_kernel(const double* __restrict__ Gpart, int S, double* __restrict__ Qout,
-                                                            unsigned* __restrict__ offmax, int max_inner, double inner_tol) {
+                                                            unsigned* __restrict__ offmax, unsigned* __restrict__ rotated, int max_inner,
+                                                            double inner_tol) {
     extern __shared__ __attribute__((aligned(16))) double dyn_small[];       // two 64 x 65 matrices: more than the static limit
     double (*G)[EPITCH] = reinterpret_cast<double (*)[EPITCH]>(dyn_small);
     double (*Q)[EPITCH] = reinterpret_cast<double (*)[EPITCH]>(dyn_small + EP * EPITCH);
     __shared__ double cs[EB][2];
     __shared__ int pq[EB][2];
     __shared__ double red[SMALL_NT / 64];
-    __shared__ int again;
+    __shared__ int again, did;                                 // did: some rotation of this panel was not the identity
     const int pair = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) did = 0;
     const double* src = Gpart + (size_t)pair * S * EP * EP;
     for (int idx = tid; idx < EP * EP; idx += SMALL_NT) {
         double g = src[idx];
@@ -170,11 +172,12 @@ __global__ __launch_bounds__(SMALL_NT) void eig_small_kernel(const double* __res
                 pair_of(EP, step, tid, p, q);
                 const double gpq = G[p][q], gpp = G[p][p], gqq = G[q][q];
                 double c = 1.0, s = 0.0;
-                if (fabs(gpq) > 1e-300 && fabs(gpq) > 1e-17 * sqrt(fabs(gpp * gqq))) {
+                if (fabs(gpq) > 1e-300 && fabs(gpq) > inner_tol * sqrt(fabs(gpp * gqq))) {
                     const double theta = (gqq - gpp) / (2.0 * gpq);
                     const double t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
                     c = 1.0 / sqrt(t * t + 1.0);
                     s = t * c;
+                    if (s != 0.0) did = 1;
                 }
                 pq[tid][0] = p; pq[tid][1] = q;
                 cs[tid][0] = c; cs[tid][1] = s;
@@ -203,6 +206,9 @@ __global__ __launch_bounds__(SMALL_NT) void eig_small_kernel(const double* __res
             __syncthreads();
         }
     }
+    // a panel that needed no rotation has Q = I exactly: the update kernel skips it (no traffic at all for its columns)
+    if (tid == 0) rotated[pair] = (unsigned)did;
+    if (!did) return;                                          // uniform: did was last written before the last barrier
     double* out = Qout + (size_t)pair * EP * EP;
     for (int idx = tid; idx < EP * EP; idx += SMALL_NT) out[idx] = Q[idx >> 6][idx & 63];
 }
@@ -210,11 +216,12 @@ __global__ __launch_bounds__(SMALL_NT) void eig_small_kernel(const double* __res
 // panel <- panel * Q for A (blockIdx.z = 0) and V (blockIdx.z = 1); a workgroup loads Q once and takes UCH chunks of 64 rows
 constexpr int UCH = 4;
 __global__ __launch_bounds__(256) void eig_update_kernel(double* __restrict__ At, double* __restrict__ Vt, int ld, int n, int nblk, int round,
-                                                        const double* __restrict__ Qin) {
+                                                        const double* __restrict__ Qin, const unsigned* __restrict__ rotated) {
     extern __shared__ __attribute__((aligned(16))) double dyn_upd[];
     double (*T)[EPITCH] = reinterpret_cast<double (*)[EPITCH]>(dyn_upd);
     double (*Qs)[EPITCH] = reinterpret_cast<double (*)[EPITCH]>(dyn_upd + EP * EPITCH);
     const int pair = blockIdx.x, tid = threadIdx.x;
+    if (rotated[pair] == 0) return;                            // Q = I: nothing to do (uniform for the workgroup)
     double* M = blockIdx.z == 0 ? At : Vt;
     int I, J;
     pair_of(nblk, round, pair, I, J);
@@ -286,7 +293,7 @@ size_t eig_basis_bytes(int n) {
 size_t eig_workspace_bytes(int n) {
     const size_t npad = (size_t)(n + EP - 1) / EP * EP, ld = npad, npairs = npad / EP;
     const size_t S = 8;
-    return 2 * npad * ld * sizeof(double) + npairs * S * EP * EP * sizeof(double) + npairs * EP * EP * sizeof(double) + 256;
+    return 2 * npad * ld * sizeof(double) + npairs * S * EP * EP * sizeof(double) + npairs * EP * EP * sizeof(double) + 256 + npairs * sizeof(unsigned);
 }
 
 hipError_t eig_refresh(hipStream_t st, const float* C, int n, void* ws, double* Vt, int warm, int max_sweeps, float tol, float* B, float* D,
@@ -299,6 +306,7 @@ hipError_t eig_refresh(hipStream_t st, const float* C, int n, void* ws, double* 
     double* Gpart = Cs + (size_t)npad * ld;
     double* Q = Gpart + (size_t)npairs * S * EP * EP;
     unsigned* flag = (unsigned*)(Q + (size_t)npairs * EP * EP);
+    unsigned* rotated = flag + 64;                             // [npairs], behind the 256 bytes of the flag
     constexpr size_t two_mats = (size_t)2 * EP * EPITCH * sizeof(double);
     static bool attr_done = false;
     if (!attr_done) {
@@ -311,14 +319,17 @@ hipError_t eig_refresh(hipStream_t st, const float* C, int n, void* ws, double* 
     // iteration is in its quadratic phase from the first sweep; on a cold start V = I and A = C
     hipLaunchKernelGGL(eig_init_kernel, dim3(npad), dim3(256), 0, st, C, n, ld, Cs, Vt, warm ? 0 : 1);
     hipLaunchKernelGGL(eig_matmul_kernel, dim3(npad / 64, npad / 64), dim3(256), 0, st, Vt, Cs, ld, At);
+    // a pair of columns whose cosine is a hundredth of the caller's tolerance or less is left alone (and a panel with only such
+    // pairs costs no update): the outer test cannot tell the difference, and an unchanged C costs one pass of Gram matrices
+    const double inner_tol = tol > 1e-13f ? 0.01 * (double)tol : 1e-15;
     int sweep = 0;
     float off = 0.f;
     for (; sweep < max_sweeps; ++sweep) {
         hipLaunchKernelGGL(eig_clear_kernel, dim3(1), dim3(1), 0, st, flag);
         for (int round = 0; round < nblk - 1; ++round) {
             hipLaunchKernelGGL(eig_gram_kernel, dim3(npairs, S), dim3(256), 0, st, At, ld, n, nblk, round, chunks_per_slice, Gpart);
-            hipLaunchKernelGGL(eig_small_kernel, dim3(npairs), dim3(SMALL_NT), two_mats, st, Gpart, S, Q, flag, 4, 1e-15);
-            hipLaunchKernelGGL(eig_update_kernel, dim3(npairs, (chunks + UCH - 1) / UCH, 2), dim3(256), two_mats, st, At, Vt, ld, n, nblk, round, Q);
+            hipLaunchKernelGGL(eig_small_kernel, dim3(npairs), dim3(SMALL_NT), two_mats, st, Gpart, S, Q, flag, rotated, 4, inner_tol);
+            hipLaunchKernelGGL(eig_update_kernel, dim3(npairs, (chunks + UCH - 1) / UCH, 2), dim3(256), two_mats, st, At, Vt, ld, n, nblk, round, Q, rotated);
         }
         unsigned bits = 0;
         hipError_t e = hipMemcpyAsync(&bits, flag, sizeof bits, hipMemcpyDeviceToHost, st);
