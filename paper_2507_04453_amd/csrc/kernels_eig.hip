@@ -29,6 +29,15 @@ __device__ __forceinline__ void pair_of(int nblk, int round, int p, int& I, int&
 
 __device__ __forceinline__ int panel_col(int I, int J, int c) { return c < EB ? I * EB + c : J * EB + (c - EB); }
 
+// 1 / sqrt(x) for a normal x: the hardware's estimate and two Newton steps y <- y (3/2 - x/2 y^2)
+__device__ __forceinline__ double rsqrt_newton(double x) {
+    double y = __builtin_amdgcn_rsq(x);
+    const double hx = 0.5 * x;
+    y = y * fma(-hx * y, y, 1.5);
+    y = y * fma(-hx * y, y, 1.5);
+    return y;
+}
+
 // Cs[c][r] = (C[c][r] + C[r][c]) / 2 in fp64, zero beyond n; on a cold start also Vt = identity
 __global__ __launch_bounds__(256) void eig_init_kernel(const float* __restrict__ C, int n, int ld, double* __restrict__ Cs, double* __restrict__ Vt,
                                                       int cold) {
@@ -172,10 +181,25 @@ __global__ __launch_bounds__(SMALL_NT) void eig_small_kernel(const double* __res
                 pair_of(EP, step, tid, p, q);
                 const double gpq = G[p][q], gpp = G[p][p], gqq = G[q][q];
                 double c = 1.0, s = 0.0;
-                if (fabs(gpq) > 1e-300 && fabs(gpq) > inner_tol * sqrt(fabs(gpp * gqq))) {
-                    const double theta = (gqq - gpp) / (2.0 * gpq);
-                    const double t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
-                    c = 1.0 / sqrt(t * t + 1.0);
+                if (fabs(gpq) > 1e-300 && gpq * gpq > (inner_tol * inner_tol) * fabs(gpp * gqq)) {
+                    // t = tan(phi) = sign(a) b / (|a| + sqrt(a^2 + b^2)) with a = gqq - gpp, b = 2 gpq (the tutorial form with
+                    // theta = a / b, multiplied through by |b|), c = 1 / sqrt(1 + t^2), s = t c.  These 32 threads are the
+                    // critical path of a step, so the square roots and the division are the hardware's reciprocal (square
+                    // root) estimates with Newton steps: c to full precision (c^2 + s^2 = c^2 (1 + t^2) = 1 to rounding whatever
+                    // t is, which is what keeps Q orthogonal); an error in t only moves the angle by its relative size.
+                    const double a = gqq - gpp, b = 2.0 * gpq, h2 = a * a + b * b;
+                    double t;
+                    if (h2 > 1e-280 && h2 < 1e280) {
+                        const double den = fabs(a) + h2 * rsqrt_newton(h2);
+                        double r = __builtin_amdgcn_rcp(den);
+                        r = fma(fma(-den, r, 1.0), r, r);
+                        r = fma(fma(-den, r, 1.0), r, r);
+                        t = (a >= 0.0 ? b : -b) * r;
+                    } else {
+                        const double theta = a / b;
+                        t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
+                    }
+                    c = rsqrt_newton(fma(t, t, 1.0));
                     s = t * c;
                     if (s != 0.0) did = 1;
                 }
