@@ -1382,13 +1382,14 @@ def test_graph_lifetime_rules(essa):
 
 
 # ------------------------------------------------------------------------------------------------ row counts up to 64
-@pytest.mark.parametrize("d_in,d_out,r,K", [(320, 200, 8, 5), (3584, 264, 16, 7), (1024, 72, 32, 3)])
+@pytest.mark.parametrize("d_in,d_out,r,K", [(320, 200, 8, 5), (3584, 264, 16, 7), (1024, 72, 32, 3), (5120, 136, 16, 4)])
 def test_forward_small_row_counts_stream_kernel(essa, ctx, d_in, d_out, r, K):
     """Up to 64 rows on int8 weights take the kernel that splits K over the waves of a 32-channel workgroup, with one
     block of 32 rows or two: one row, a few rows, one full block, one row more (two blocks), two full blocks, and one row
     more (the 32-row tiles again); ragged channels; both output types; the one-limb mode; the rank-r term and the base
     alone; the fused reward (a pass of its own behind this kernel); and the rows of a larger call (64-row tiles, K split in
-    halves) give the same bits in fp32 and bf16."""
+    halves) give the same bits in fp32 and bf16.  The 5120-wide case has more chunks per wave than the kernel asks weights for
+    at once (a second bunch)."""
     _say("small row counts d_in=%d d_out=%d r=%d" % (d_in, d_out, r))
     p = wl.make_projection("t", d_in, d_out, r, "int8", layer=18, proj=r % 4)
     W, f = oracle_proj(p)
