@@ -2,9 +2,9 @@
 // (paper: Algorithm 1, reconstruction step + inference pass; see kernels_forward.hip for the algebra).
 //
 // Idea: the int8 weights never leave the integer domain.  Each activation row is re-expressed in
-// 15-bit fixed point relative to its own largest entry, x ~ delta_i * (128 * hi + lo) with two int8
-// limbs, and the base product runs on the int8 MFMA (exact int32 accumulation, one pass per limb):
-//     W_deq x_i = delta_i * s_o * (128 * <hi_i, q_o> + <lo_i, q_o>).
+// 16-bit signed fixed point relative to its own largest entry, x ~ delta_i * (256 * hi + lo) with two signed
+// int8 limbs, and the base product runs on the int8 MFMA (exact int32 accumulation, one pass per limb):
+//     W_deq x_i = delta_i * s_o * (256 * <hi_i, q_o> + <lo_i, q_o>).
 // There is no weight conversion at all; every weight byte is loaded from HBM straight into the MFMA
 // operand registers of the one wave that owns its 32 output channels (pre-tiled layout, 1 KB
 // contiguous per load instruction, k-chunk major), while the activation limbs of all the rows of the tile are staged
@@ -1136,7 +1136,7 @@ __global__ __launch_bounds__(NT, (Q4 && MB == 2) ? 4 : 1) void gemm_i8_kernel(st
 
     // ---- epilogue 1: the two K halves exchange accumulators.  Half kh keeps row blocks with (mb & 1) == kh
     // (all of them when there is only one) and hands the others to its partner.  With two limbs each half first
-    // folds them into one fp32 value, 128 hi + lo, so that half as many bytes cross the LDS (one more rounding of
+    // folds them into one fp32 value, 256 hi + lo, so that half as many bytes cross the LDS (one more rounding of
     // 2^-24; the accumulator dump keeps its integers).
     // exchange slot (n, writer kh, limb, j): 16 x 64 ints, written as [q/4][lane] 16-byte vectors
     constexpr bool FSUM = Q4 || (LIMBS == 2 && !DUMP);       // one fp32 value per element travels instead of the limbs
@@ -1498,7 +1498,7 @@ __global__ __launch_bounds__(NT, 1) void gemm_i8_stream_kernel(stream_args a) {
 // the vector-ALU scaling is the number of 128-byte requests a workgroup sends to the L2 per K tile; with 256 channels
 // per tile the activation limbs (as many bytes per K tile as the nibbles of 256 channels) are asked for half as often
 // as with 128.  Wave n owns channels 32n.. of the tile for both blocks of 32 rows, over the whole K tile: per row
-// block the hi-limb MFMAs, a shift by 7 of their sums, the lo-limb MFMAs on top of them, then one conversion and one
+// block the hi-limb MFMAs, a shift by 8 of their sums, the lo-limb MFMAs on top of them, then one conversion and one
 // FMA with the group's scale per output -- the same integer sum and the same fp32 operations as the narrower tiles,
 // so a row's result does not depend on which kernel took it.  Registers are capped at 128: two workgroups share a CU
 // and overlap each other's MFMA, scaling and LDS phases (the loop itself runs them one after the other).

@@ -8,7 +8,7 @@ Tolerances (relative to the whole reference tensor: max|d|/max|ref| and ||d||/||
                    exact-product paths (ESSA_COMPUTE_BF16, generic kernel): rms 2e-5, max 2e-4 (fp32 accumulation,
                    bf16 head+tail operands in the rank-r term);
                    default int8-limb path: rms 2e-4, max 2e-3 -- each activation is rounded to a grid of
-                   amax_row/16383, a uniform error of rms amax/56752, i.e. about 7e-5 of the output for N(0,1) rows.
+                   amax_row/32639, a uniform error of rms amax/113064, i.e. about 3e-5 of the output for N(0,1) rows.
 """
 import math
 
@@ -167,7 +167,7 @@ def test_forward_small_shapes_bf16(essa, ctx, quant, d_in, d_out, r, K, R):
     own_A = to_dev(np.tile(f["S_A"].astype(np.float32), (K, 1)))
     own_B = to_dev(np.tile(f["S_B"].astype(np.float32), (K, 1)))
     ref_own = base + (xv.astype(np.float64) @ p.A.astype(np.float64).T) @ p.B.astype(np.float64).T
-    # the default path rounds activations to 15-bit fixed point; ESSA_COMPUTE_BF16 and the generic kernel are exact in
+    # the default path rounds activations to 16-bit fixed point; ESSA_COMPUTE_BF16 and the generic kernel are exact in
     # the products
     variants = [(0, LIMB_RMS, LIMB_MAX), (essa.COMPUTE_BF16, EXACT_RMS, EXACT_MAX)] if d_in % 16 == 0 else [(0, EXACT_RMS, EXACT_MAX)]
     for fl, t_rms, t_max in variants:
